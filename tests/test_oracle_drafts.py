@@ -1,0 +1,185 @@
+"""Pins for the oracle's draft construction (Sections 4.1-4.3): hand-worked
+cases, closed forms and brute force on tiny inputs.  CPU only."""
+import os
+
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import context_ngram_groups, context_rows, bigram_scores, rank_ids, Bigram, build_drafts
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "context_ngram_cases.txt")
+
+
+def _golden_cases():
+    cases = []
+    for line in open(GOLDEN):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        head, ctx, exp = [p.strip() for p in line.split("|")]
+        q, w = [int(t) for t in head.split()]
+        rows = []
+        if exp != "-":
+            for item in exp.split():
+                toks, cnt, last = item.split(":")
+                rows.append((tuple(int(t) for t in toks.split(",")), int(cnt), int(last)))
+        cases.append((q, w, [int(t) for t in ctx.split()], rows))
+    return cases
+
+
+@pytest.mark.parametrize("q,w,ctx,rows", _golden_cases())
+def test_matcher_hand_worked_cases(q, w, ctx, rows):
+    assert context_ngram_groups(ctx, q, w) == rows
+
+
+def _brute_force_groups(x, q, w):
+    """Quadratic enumeration: every matching window is compared with every other."""
+    n = len(x)
+    starts = [i for i in range(n) if i + q + w <= n and all(x[i + t] == x[n - q + t] for t in range(q))]
+    out = []
+    for i in starts:
+        same = [j for j in starts if all(x[j + q + t] == x[i + q + t] for t in range(w))]
+        if i == max(same):                                   # one representative per continuation: its last match
+            out.append((tuple(x[i + q:i + q + w]), len(same), i))
+    # rank: repeatedly pull the best remaining (count, then later start)
+    ranked = []
+    while out:
+        best = out[0]
+        for g in out[1:]:
+            if g[1] > best[1] or (g[1] == best[1] and g[2] > best[2]):
+                best = g
+        ranked.append(best)
+        out.remove(best)
+    return ranked
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_matcher_equals_brute_force_on_small_alphabets(seed):
+    rng = np.random.default_rng(seed)
+    for _ in range(40):
+        n = int(rng.integers(1, 60))
+        x = [int(t) for t in rng.integers(0, int(rng.integers(1, 4)) + 1, size=n)]   # alphabet of 1..4 symbols
+        q, w = int(rng.integers(1, 4)), int(rng.integers(1, 5))
+        assert context_ngram_groups(x, q, w) == _brute_force_groups(x, q, w)
+
+
+def test_matcher_closed_forms():
+    # constant stream: one continuation, n-q-w+1 occurrences, last start n-q-w
+    for n, q, w in [(10, 1, 1), (33, 3, 5), (7, 2, 5)]:
+        assert context_ngram_groups([4] * n, q, w) == [((4,) * w, n - q - w + 1, n - q - w)]
+    # period-p stream of distinct symbols, whole periods: the query matches once per period and every match
+    # has the same continuation
+    p, reps, q, w = 5, 6, 2, 3
+    x = list(range(p)) * reps
+    n = len(x)
+    (cont, cnt, last), = context_ngram_groups(x, q, w)
+    assert cont == tuple((n + t) % p for t in range(w))      # what the period dictates comes next
+    assert cnt == reps - 1 and last == n - p - q
+    # tokens that never occurred before: nothing
+    assert context_ngram_groups(list(range(20)), 1, 1) == []
+
+
+def test_matcher_on_synthetic_prompts_matches_brute_force():
+    x = [int(t) for t in si.prompt_spans(32000, 600, 0.5, seed=4)]
+    hits = 0
+    for cut in range(50, 600, 7):
+        for q in (1, 2, 3):
+            g = context_ngram_groups(x[:cut], q, 4)
+            assert g == _brute_force_groups(x[:cut], q, 4)
+            hits += bool(g)
+    assert hits > 20                                         # the copied spans do produce matches
+
+
+def test_context_rows_backoff_cap_and_dedup():
+    x = [1, 2, 3, 9, 9, 2, 3, 8, 8, 7, 3, 6, 6, 1, 2, 3]
+    # q=3 ("1 2 3") -> 9 9 ; q=2 ("2 3") -> 8 8 (later), 9 9 (dup) ; q=1 ("3") -> 6 6, 8 8 (dup), 9 9 (dup)
+    assert context_rows(x, 2, 8, 1, 3) == [(9, 9), (8, 8), (6, 6)]
+    assert context_rows(x, 2, 2, 1, 3) == [(9, 9), (8, 8)]
+    assert context_rows(x, 2, 8, 3, 3) == [(9, 9)]
+    assert context_rows(x, 2, 8, 1, 1) == [(6, 6), (8, 8), (9, 9)]
+    assert context_rows(x, 2, 0, 1, 3) == []
+
+
+# -- bigram ---------------------------------------------------------------------
+
+def test_bigram_scores_are_plain_dot_products():
+    rng = np.random.default_rng(0)
+    E, U = rng.standard_normal((7, 5)), rng.standard_normal((7, 5))
+    z = bigram_scores(E, U, 3)
+    for v in range(7):
+        assert np.isclose(z[v], sum(U[v, i] * E[3, i] for i in range(5)), rtol=1e-14)
+
+
+def _select_by_loop(z, k):
+    left = list(range(len(z)))
+    out = []
+    for _ in range(k):
+        best = left[0]
+        for v in left[1:]:
+            if z[v] > z[best]:                  # strict: an equal later id never displaces an earlier one
+                best = v
+        out.append(best)
+        left.remove(best)
+    return out
+
+
+def test_rank_ids_against_selection_loop_with_ties():
+    rng = np.random.default_rng(1)
+    for _ in range(50):
+        V = int(rng.integers(1, 40))
+        z = rng.integers(0, 6, size=V).astype(np.float64)        # many exact ties
+        k = int(rng.integers(1, V + 1))
+        assert list(rank_ids(z, k)) == _select_by_loop(z, k)
+    z = rng.standard_normal(100)
+    assert sorted(rank_ids(z, 100)) == list(range(100))           # k = V is a permutation
+    assert list(rank_ids(np.arange(10.0), 3)) == [9, 8, 7]
+
+
+def test_duplicate_unembedding_rows_rank_by_id():
+    rng = np.random.default_rng(2)
+    E, U = rng.standard_normal((6, 4)), rng.standard_normal((6, 4))
+    U[4] = U[1]                                                    # exact tie between ids 1 and 4
+    b = Bigram(E, U)
+    for x in range(6):
+        order = list(b.topk(x, 6))
+        assert order.index(1) + 1 == order.index(4)
+
+
+def test_chain_rows_follow_the_top1_bigram():
+    m = si.MODELS["tiny"]
+    w = si.make_weights(m, seed=0)
+    b = Bigram(w["tok_emb"], w["unemb"])
+    rows = b.rows(17, 5, 4)
+    top = list(b.topk(17, 5))
+    assert [r[0] for r in rows] == top
+    assert b.next1(17) == top[0]
+    for r in rows:
+        for j in range(3):
+            assert r[j + 1] == b.next1(r[j]) == int(np.argmax(b.scores(r[j])))
+
+
+# -- mixed strategy ---------------------------------------------------------------
+
+def test_mixed_strategy_rows_and_sources():
+    m = si.MODELS["tiny"]
+    wts = si.make_weights(m, seed=0)
+    b = Bigram(wts["tok_emb"], wts["unemb"])
+    x = [1, 2, 3, 9, 9, 2, 3, 8, 8, 7, 3, 6, 6, 1, 2, 3]
+    d, src, n_ctx = build_drafts(x, b, k=5, w=2, k_ctx_max=5, q_min=1, q_max=3)
+    assert n_ctx == 3 and list(src) == [0, 0, 0, 1, 1]
+    assert [tuple(r) for r in d[:3]] == [(9, 9), (8, 8), (6, 6)]
+    assert [tuple(r) for r in d[3:]] == b.rows(3, 2, 2)
+    # cap on context rows: the bigram takes what is left
+    d, src, n_ctx = build_drafts(x, b, k=5, w=2, k_ctx_max=1, q_min=1, q_max=3)
+    assert n_ctx == 1 and list(src) == [0, 1, 1, 1, 1]
+    assert [tuple(r) for r in d[1:]] == b.rows(3, 4, 2)
+    # nothing in the context: all bigram
+    d, src, n_ctx = build_drafts(list(range(30, 40)), b, k=3, w=2, k_ctx_max=3, q_min=1, q_max=1)
+    assert n_ctx == 0 and list(src) == [1, 1, 1] and [tuple(r) for r in d] == b.rows(39, 3, 2)
+    # more context rows than k: the first k by rank
+    d, src, n_ctx = build_drafts(x, b, k=2, w=2, k_ctx_max=8, q_min=1, q_max=3)
+    assert n_ctx == 2 and [tuple(r) for r in d] == [(9, 9), (8, 8)]
+    # w = 0: plain decoding, an empty batch
+    d, src, n_ctx = build_drafts(x, b, k=1, w=0, k_ctx_max=1, q_min=1, q_max=1)
+    assert d.shape == (1, 0) and n_ctx == 0

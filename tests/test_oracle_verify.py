@@ -1,0 +1,143 @@
+"""Pins for the oracle's guess-and-verify step and decode loops: the method's
+defining invariant (speculative greedy == plain greedy), injected drafts with a
+known accepted length, closed-form accept-all, cache consistency.  CPU only."""
+import copy
+
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import (Model, Bigram, prefill, verify_step, commit, accept_lengths, select_winner,
+                    greedy_plain, greedy_plain_cached, greedy_speculative, build_drafts)
+
+
+@pytest.fixture(scope="module")
+def tiny():
+    desc = si.MODELS["tiny"]
+    w = si.make_weights(desc, seed=0)
+    run = si.RUNS["cfg1"]
+    prompt = si.make_prompt(run, desc["vocab"], seed=1)
+    m = Model(desc, w)
+    plain = greedy_plain(m, prompt, 24)             # the definition: no cache, whole sequence re-run per token
+    return desc, w, run, prompt, m, plain
+
+
+def test_accept_lengths_and_winner_by_hand():
+    drafts = np.array([[5, 6, 7], [5, 6, 9], [1, 6, 7], [5, 6, 7]])
+    greedy = np.array([[5, 6, 9, 0], [5, 6, 9, 4], [5, 6, 7, 1], [5, 6, 7, 2]])
+    a = accept_lengths(drafts, greedy)
+    assert list(a) == [2, 3, 0, 3]
+    assert select_winner(a) == (1, 3)               # rows 1 and 3 tie at 3: the lower row wins
+    assert select_winner(np.array([0, 0, 0])) == (0, 0)
+    assert list(accept_lengths(np.zeros((2, 0), dtype=np.int32), np.array([[3], [3]]))) == [0, 0]
+
+
+def test_cached_plain_equals_uncached_plain(tiny):
+    desc, w, run, prompt, m, plain = tiny
+    assert greedy_plain_cached(m, prompt, 24) == plain
+
+
+def test_speculative_equals_plain_greedy_cfg1(tiny):
+    """The defining invariant: whatever the drafts, the committed tokens are the
+    plain greedy tokens."""
+    desc, w, run, prompt, m, plain = tiny
+    gen, stats = greedy_speculative(m, prompt, 24, run["k"], run["w"], run["k_ctx_max"], run["q_min"], run["q_max"])
+    assert gen == plain
+    assert sum(stats["new_hist"]) == stats["calls"]
+
+
+@pytest.mark.parametrize("k,w,kc,qmin,qmax", [(1, 0, 0, 1, 1), (1, 5, 1, 1, 1), (6, 2, 0, 1, 1), (5, 4, 5, 1, 3)])
+def test_speculative_equals_plain_greedy_other_shapes(tiny, k, w, kc, qmin, qmax):
+    desc, w_, run, prompt, m, plain = tiny
+    gen, _ = greedy_speculative(m, prompt, 24, k, w, kc, qmin, qmax)
+    assert gen == plain
+
+
+def test_injected_drafts_accept_exactly_up_to_the_corruption(tiny):
+    desc, w_, run, prompt, m, plain = tiny
+    st = prefill(m, prompt)
+    assert st.tokens[-1] == plain[0]
+    w = 5
+    truth = plain[1:1 + w]
+    V = desc["vocab"]
+    rows = []
+    for c in range(w + 1):                      # row c: correct for c tokens, then wrong
+        row = list(truth)
+        if c < w:
+            row[c] = (truth[c] + 1 + c) % V
+        rows.append(row)
+    res = verify_step(m, st, np.array(rows))
+    assert list(res["accept_len"]) == list(range(w + 1))
+    assert res["winner"] == w and res["n_accept"] == w
+    assert res["new_tokens"] == plain[1:w + 2]
+    # every row that accepted at least a tokens saw the same inputs up to column a: same greedy token there
+    for a in range(w + 1):
+        col = {int(res["greedy"][r, a]) for r in range(a, w + 1)}
+        assert col == {plain[1 + a]}
+    # rows in another order, with a duplicate: same tokens, winner = first of the best rows
+    perm = [3, 5, 0, 5, 1]
+    res2 = verify_step(m, st, np.array([rows[i] for i in perm]))
+    assert list(res2["accept_len"]) == perm and res2["winner"] == 1
+    assert res2["new_tokens"] == res["new_tokens"]
+    assert np.array_equal(res2["greedy"][1], res2["greedy"][3])
+
+
+def test_all_wrong_drafts_reduce_to_a_plain_decode_step(tiny):
+    desc, w_, run, prompt, m, plain = tiny
+    st = prefill(m, prompt)
+    wrong = np.array([[(plain[1] + 1 + r) % desc["vocab"], 0, 0] for r in range(3)])
+    res = verify_step(m, st, wrong)
+    assert res["n_accept"] == 0 and res["winner"] == 0 and res["new_tokens"] == [plain[1]]
+    res1 = verify_step(m, st, np.zeros((1, 0), dtype=np.int32))          # (k, w) = (1, 0)
+    assert res1["new_tokens"] == [plain[1]]
+    assert np.allclose(res["logits"][:, 0], res1["logits"][0, 0], atol=1e-12)    # column 0 is the same in every row
+
+
+def test_commit_keeps_the_cache_consistent_with_a_fresh_prefill(tiny):
+    desc, w_, run, prompt, m, plain = tiny
+    st = prefill(m, prompt)
+    truth = plain[1:4]
+    drafts = np.array([[truth[0], truth[1], (truth[2] + 1) % desc["vocab"]], [truth[0], 0, 0]])
+    res = verify_step(m, st, drafts)
+    assert res["n_accept"] == 2
+    n_new = commit(st, res)
+    assert n_new == 3 and st.tokens == [int(t) for t in prompt] + plain[:4]
+    fresh = prefill(m, st.tokens[:-1])
+    assert fresh.tokens[-1] == st.tokens[-1]
+    for li in range(desc["n_layers"]):
+        assert np.allclose(st.cache.k[li], fresh.cache.k[li], atol=1e-12)
+        assert np.allclose(st.cache.v[li], fresh.cache.v[li], atol=1e-12)
+    nxt = verify_step(m, st, np.zeros((1, 0), dtype=np.int32))
+    assert nxt["new_tokens"] == [plain[4]]
+    # budget truncation
+    st2 = prefill(m, prompt)
+    assert commit(st2, verify_step(m, st2, drafts), max_new=2) == 2
+    assert st2.tokens == [int(t) for t in prompt] + plain[:3] and len(st2.cache) == len(st2.tokens) - 1
+
+
+def test_zero_output_projections_accept_the_whole_bigram_chain():
+    """W_o = W_down = 0: the model's logits are U . RMSNorm(E[x]), whose argmax is
+    the bigram's top-1 (a positive per-vector scale cannot change ranks, gains
+    are 1).  So bigram row 0 -- the chain of top-1s -- is accepted in full."""
+    desc = si.MODELS["tiny"]
+    w = si.make_weights(desc, seed=3)
+    for lw in w["layers"]:
+        lw["wo"] = np.zeros_like(lw["wo"])
+        lw["w_down"] = np.zeros_like(lw["w_down"])
+    m = Model(desc, w)
+    b = Bigram(m.tok_emb, m.unemb)
+    st = prefill(m, [10, 20, 30])
+    drafts, src, n_ctx = build_drafts(st.tokens, b, k=4, w=6, k_ctx_max=0, q_min=1, q_max=1)
+    res = verify_step(m, st, drafts)
+    assert res["winner"] == 0 and res["n_accept"] == 6
+    assert list(res["accept_len"][1:]) == [0, 0, 0]               # ranks 2..4 start with a different token
+    gen, stats = greedy_speculative(m, [10, 20, 30], 29, 4, 6, 0, 1, 1)
+    assert stats["new_hist"][7] == stats["calls"] == 4            # 1 from prefill + 4 calls x 7 tokens
+
+
+def test_attention_cost_model_counts():
+    """Section 3: each of the k rows multiplies w+1 queries by l+w keys."""
+    for (l, k, w) in [(25, 1, 0), (100, 10, 5), (500, 32, 15)]:
+        pairs = sum(1 for r in range(k) for j in range(w + 1) for s in range((l - 1) + j + 1))
+        assert pairs == k * ((w + 1) * (l - 1) + (w + 1) * (w + 2) // 2)
+        assert pairs <= k * (w + 1) * (l + w)
