@@ -1,0 +1,204 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched speculative verify step on one MI355X.
+
+A "step" is one pass of the whole hot path: ngg_build_drafts + ngg_verify_step +
+ngg_commit on the 7B-shaped bf16 decoder (prompt 2048, k=10, w=5), seeded
+synthetic weights and prompt already resident in HBM.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
+
+
+def algorithmic_bytes(m, P, M, with_bigram=True):
+    """Bytes one model call on M block tokens over a cached context of P tokens must move:
+    layer weights + output embedding (+ once more for the bigram sweep) + cached keys/values
+    read once + the block's own keys/values written."""
+    B = 2 if m["dtype"] == "bf16" else 4
+    d, f, L, V = m["d_model"], m["d_ffn"], m["n_layers"], m["vocab"]
+    dq, dkv = m["n_heads"] * m["head_dim"], m["n_kv_heads"] * m["head_dim"]
+    layer_w = (dq * d + 2 * dkv * d + d * dq + 3 * d * f) * B
+    total = L * layer_w + V * d * B * (2 if with_bigram else 1)
+    total += 2 * L * P * dkv * B + 2 * L * M * dkv * B
+    return total, layer_w
+
+
+def gemm_bytes(m, which):
+    B = 2 if m["dtype"] == "bf16" else 4
+    d, f = m["d_model"], m["d_ffn"]
+    dq, dkv = m["n_heads"] * m["head_dim"], m["n_kv_heads"] * m["head_dim"]
+    return {"gemm_qkv": (dq + 2 * dkv) * d * B, "gemm_o": d * dq * B, "gemm_gateup": 2 * f * d * B,
+            "gemm_down": d * f * B, "gemm_unembed": m["vocab"] * d * B}[which]
+
+
+def cpu_baseline(si, oracle, run, dev_weights, model_desc, tokens_per_call):
+    """The oracle, as it stands, on a bounded sample: the 2-layer twin of the workload (same
+    widths, same prompt length, same k and w), a few verify steps; the per-step time is scaled to
+    the full layer count by the parameters each step reads."""
+    import numpy as np
+    twin = si.reduced_layers(model_desc, 2)
+    w = dict(tok_emb=dev_weights["tok_emb"].float().cpu().numpy(), unemb=dev_weights["unemb"].float().cpu().numpy(),
+             final_norm=dev_weights["final_norm"].float().cpu().numpy(),
+             layers=[{k: v.float().cpu().numpy() for k, v in lw.items()} for lw in dev_weights["layers"][:2]])
+    model = oracle.Model(twin, w)
+    prompt = si.make_prompt(run, twin["vocab"], seed=1)
+    t0 = time.time()
+    st = oracle.prefill(model, prompt)
+    t_prefill = time.time() - t0
+    bigram = oracle.Bigram(model.tok_emb, model.unemb)
+    times = []
+    for _ in range(3):
+        t0 = time.time()
+        drafts, _, _ = oracle.build_drafts(st.tokens, bigram, run["k"], run["w"], run["k_ctx_max"], run["q_min"], run["q_max"])
+        res = oracle.verify_step(model, st, drafts)
+        oracle.commit(st, res)
+        times.append(time.time() - t0)
+    t_step_twin = min(times)
+    layer = sum(int(np.prod(v.shape)) for k, v in w["layers"][0].items())
+    emb = int(np.prod(w["unemb"].shape))
+    scale = (model_desc["n_layers"] * layer + 2 * emb) / (2 * layer + 2 * emb)
+    t_step = t_step_twin * scale
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count()
+    return {"value": tokens_per_call / t_step, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": (f"numpy fp64 oracle on the 2-layer twin of the workload (prompt {len(prompt)}, k={run['k']}, "
+                       f"w={run['w']}): 3 verify steps, best {t_step_twin:.2f} s/step, scaled x{scale:.2f} by parameters "
+                       f"read to {model_desc['n_layers']} layers = {t_step:.1f} s/step; at the GPU run's "
+                       f"{tokens_per_call:.2f} tokens/call; oracle prefill of the twin took {t_prefill:.1f} s"),
+            "s_per_step": t_step}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg3")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true",
+                    help="do not record HIP events around the dominant kernel during the timed steps")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import synth_inputs as si
+    import paper_2411_03786_amd as ngg
+
+    run = si.RUNS[args.workload]
+    m = si.MODELS[run["model"]]
+    k, w = run["k"], run["w"]
+    torch.cuda.set_device(0)
+    dev_w = si.make_weights_device(m, seed=0)
+    prompt = si.make_prompt(run, m["vocab"], seed=1)
+    n_budget = (args.steps + args.warmup + 64) * (w + 1) + 64
+    ctx = ngg.Context(m, dev_w, max_seq=len(prompt) + n_budget, max_k=k, max_w=w)
+    ctx.prefill(prompt)
+    torch.cuda.synchronize()
+
+    def step():
+        ctx.build_drafts(run, fetch=False)
+        r = ctx.verify_step(None, k, w, fetch=False)
+        ctx.commit()
+        return r["n_new"]
+
+    for _ in range(args.warmup):
+        step()
+    n_start = len(ctx.get_tokens())
+    if not args.no_kernel_events:
+        ctx.profile_reset()
+        ctx.profile_enable(1 << ngg.PROF_CLASSES.index("gemm_gateup"))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    new_tokens = 0
+    for _ in range(args.steps):
+        new_tokens += step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ctx.profile_enable(0)
+    dom_ms, dom_n = (0.0, 0)
+    if not args.no_kernel_events:
+        dom_ms, dom_n = ctx.profile_read()["gemm_gateup"]
+    ms_per_step = elapsed * 1e3 / args.steps
+    tokens_per_call = new_tokens / args.steps
+    P_mid = n_start - 1 + new_tokens // 2
+
+    # per-class device time of a few more steps (all classes; perturbs timing, so outside the timed region)
+    ctx.profile_reset()
+    ctx.profile_enable(-1)
+    for _ in range(5):
+        step()
+    prof = ctx.profile_read()
+    ctx.profile_enable(0)
+    breakdown = {name: {"ms_per_step": ms / 5, "launches_per_step": cnt / 5} for name, (ms, cnt) in prof.items() if cnt}
+
+    # single-token decode step (k=1, w=0: one model call, no drafting) at the same context length
+    dec = []
+    for i in range(args.warmup + args.steps):
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ctx.verify_step(None, 1, 0, fetch=False)
+        ctx.commit()
+        torch.cuda.synchronize()
+        if i >= args.warmup:
+            dec.append(time.perf_counter() - t1)
+    decode_ms = 1e3 * sum(dec) / len(dec)
+
+    M = k * (w + 1)
+    step_bytes, _ = algorithmic_bytes(m, P_mid, M, with_bigram=True)
+    dec_bytes, _ = algorithmic_bytes(m, P_mid, 1, with_bigram=False)
+    roof = None
+    if dom_n:
+        gb = gemm_bytes(m, "gemm_gateup")
+        avg_us = dom_ms * 1e3 / dom_n
+        ach = gb / (avg_us * 1e-6) / 1e9
+        roof = {"kernel": "gemm_skinny_kernel<bf16, gate/up + SwiGLU epilogue>", "bound": "hbm", "achieved": ach,
+                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBPS, "traffic": None,
+                "bytes_per_launch": gb, "avg_launch_us": avg_us, "launches": dom_n}
+    out = {
+        "metric": "accepted tokens/s at k x w (verify-step latency in ms_per_step; HBM GB/s vs peak in roofline)",
+        "value": new_tokens / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if m["dtype"] == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {run['model']}-shaped decoder, {m['n_layers']} layers, d_model {m['d_model']}, "
+                               f"vocab {m['vocab']}, prompt {len(prompt)}, k={k}, w={w}, context N-gram q={run['q_max']}, "
+                               f"k_ctx_max={run['k_ctx_max']}", "k": k, "w": w, "prompt_len": len(prompt)},
+        "verify_step_latency_us": ms_per_step * 1e3,
+        "decode_step_latency_us": decode_ms * 1e3,
+        "verify_over_decode": ms_per_step / decode_ms,
+        "candidate_tokens_per_s": k * w / (ms_per_step * 1e-3),
+        "tokens_per_call": tokens_per_call,
+        "step_hbm": {"algorithmic_bytes": step_bytes, "GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
+                     "frac_of_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS},
+        "decode_hbm": {"algorithmic_bytes": dec_bytes, "GBps": dec_bytes / (decode_ms * 1e-3) / 1e9,
+                       "frac_of_peak": dec_bytes / (decode_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS},
+        "kernel_breakdown": breakdown,
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        out["cpu_baseline"] = cpu_baseline(si, oracle, run, dev_w, m, tokens_per_call)
+    else:
+        out["cpu_baseline"] = None
+    ctx.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

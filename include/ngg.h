@@ -1,0 +1,180 @@
+/*
+ * ngg -- one batched, learning-free speculative verify step for greedy decoding
+ * of a decoder-only transformer on AMD MI355X (gfx950).
+ *
+ * Plain C ABI.  No call throws or aborts; every call returns an ngg_status and
+ * leaves a message readable through ngg_last_error().  Argument errors are
+ * detected on the host before anything is launched.  A context is used from
+ * one host thread at a time.  All work of a context is enqueued on the HIP
+ * stream given to ngg_create; calls that fill host buffers synchronise that
+ * stream before returning.
+ *
+ * State of a context (Section 3, "Assumptions on parallelism for
+ * verification"): the context holds n tokens (prompt + generated); every token
+ * except the final one has its keys and values cached (positions 0 .. n-2).
+ */
+#ifndef NGG_H
+#define NGG_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ngg_ctx ngg_ctx; /* opaque; owns KV caches, activations, token history, bigram table */
+
+typedef enum {
+  NGG_OK = 0,
+  NGG_EINVAL = -1,    /* null pointer, bad shape, token id out of range, unsupported model shape */
+  NGG_ECAPACITY = -2, /* sequence would exceed max_seq, or k / w exceed max_k / max_w */
+  NGG_ESTATE = -3,    /* call out of order: verify before prefill, commit without a verify */
+  NGG_EHIP = -4,      /* a HIP runtime call failed; the message holds hipGetErrorString */
+  NGG_ENOMEM = -5     /* device or host allocation failed */
+} ngg_status;
+
+typedef enum { NGG_F32 = 0, NGG_BF16 = 1 } ngg_dtype;
+
+/* Decoder shape.  The base model M of Section 4.1 is a pre-norm decoder with
+ * RMSNorm, rotary multi-head attention (rotate-half pairing: element i pairs
+ * with i + head_dim/2), SwiGLU feed-forward, no biases, a final RMSNorm and an
+ * untied output embedding.  Constraints checked by ngg_create: head_dim in
+ * {32, 64, 128}; d_model, d_ffn and n_heads*head_dim multiples of 32; vocab a
+ * multiple of 16; n_heads a multiple of n_kv_heads. */
+typedef struct {
+  int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  int32_t dtype;      /* ngg_dtype of weights, KV cache and GEMM inputs; accumulation is always fp32 */
+  float rms_eps, rope_theta;
+  int32_t max_seq;    /* capacity of the token history and of the KV cache */
+  int32_t max_k;      /* largest number of draft rows k */
+  int32_t max_w;      /* largest draft width w */
+} ngg_model_desc;
+
+/* DEVICE pointers, row-major [out][in], element type desc.dtype.  BORROWED:
+ * the caller keeps them alive and unchanged for the life of the context. */
+typedef struct {
+  const void *attn_norm; /* [d_model] */
+  const void *wq;        /* [n_heads*head_dim][d_model] */
+  const void *wk;        /* [n_kv_heads*head_dim][d_model] */
+  const void *wv;        /* [n_kv_heads*head_dim][d_model] */
+  const void *wo;        /* [d_model][n_heads*head_dim] */
+  const void *mlp_norm;  /* [d_model] */
+  const void *w_gate;    /* [d_ffn][d_model] */
+  const void *w_up;      /* [d_ffn][d_model] */
+  const void *w_down;    /* [d_model][d_ffn] */
+} ngg_layer_weights;
+
+typedef struct {
+  const void *tok_emb;    /* input embedding,  [vocab][d_model] (device) */
+  const void *unemb;      /* output embedding, [vocab][d_model] (device) */
+  const void *final_norm; /* [d_model] (device) */
+  const ngg_layer_weights *layers; /* HOST array of n_layers entries (read during ngg_create only) */
+} ngg_weights;
+
+/* Draft batch shape (glossary of the paper): k rows, w speculated tokens per
+ * row; context N-gram queries use the last q tokens, q tried from q_max down
+ * to q_min (q_min == q_max is the matcher of Section 4.2); at most k_ctx_max
+ * rows come from the context (k_ctx_max == k is the rule of Section 4.3). */
+typedef struct {
+  int32_t k, w, k_ctx_max, q_min, q_max;
+} ngg_draft_cfg;
+
+/* Result of one verify call.  All pointers are HOST buffers owned by the
+ * caller; any of them may be NULL to skip that output. */
+typedef struct {
+  int32_t k, w;        /* filled by the call */
+  int32_t winner;      /* row with the longest accepted prefix (lowest row on ties) */
+  int32_t n_accept;    /* accepted drafted tokens of the winner, 0 .. w */
+  int32_t n_new;       /* n_accept + 1: tokens a commit would append (before budget truncation) */
+  int32_t *greedy;     /* [k][w+1] greedy token after every block position */
+  int32_t *accept_len; /* [k] */
+  int32_t *new_tokens; /* [w+1], first n_new valid */
+  float *logits;       /* [k][w+1][vocab] fp32, or NULL (costs a k*(w+1)*vocab*4-byte device->host copy) */
+} ngg_verify_out;
+
+typedef struct {
+  int64_t calls;          /* verify calls */
+  int64_t tokens;         /* generated tokens (including the one produced by prefill) */
+  int64_t new_hist[34];   /* new_hist[i] = calls that appended i tokens (i <= max_w+1 <= 33) */
+  int64_t winner_src[2];  /* calls won by a context row / by a bigram row */
+  int64_t ctx_rows;       /* context rows found, summed over calls */
+  double ms_prefill, ms_drafts, ms_verify, ms_commit; /* host wall time per phase, including syncs */
+} ngg_stats;
+
+/* Creates a context: allocates caches and activations on the current device,
+ * builds the rotary table and the bigram's top-1 table next1[x] = argmax_v
+ * <unemb[v], tok_emb[x]> (the O(1) lookup of Section 4.1, "Extensions").
+ * hip_stream is a hipStream_t (NULL = the default stream), borrowed. */
+ngg_status ngg_create(const ngg_model_desc *desc, const ngg_weights *weights, void *hip_stream, ngg_ctx **out);
+ngg_status ngg_destroy(ngg_ctx *ctx);
+
+/* Resets the context to `prompt` (HOST, n_prompt >= 1 tokens), caches keys and
+ * values of every prompt token and appends the model's first greedy token:
+ * afterwards n = n_prompt + 1.  Runs the verify kernels on chunks of the
+ * prompt; it is plumbing, not part of the timed step. */
+ngg_status ngg_prefill(ngg_ctx *ctx, const int32_t *prompt, int32_t n_prompt);
+
+/* Draft construction (Section 4): context N-gram rows first (Section 4.2:
+ * earlier occurrences of the last q tokens, the w tokens that follow, ranked by
+ * count, ties to the later match), then rows of the model bigram (Section 4.1:
+ * top-k of <unemb[v], tok_emb[x_last]>, ties to the lower id, each extended to
+ * w tokens by chaining next1).  The drafts stay on the device for
+ * ngg_verify_step(drafts = NULL); the host copies are optional:
+ * drafts [k][w], row_src [k] (0 = context, 1 = bigram), n_ctx_rows. */
+ngg_status ngg_build_drafts(ngg_ctx *ctx, const ngg_draft_cfg *cfg, int32_t *drafts, int8_t *row_src,
+                            int32_t *n_ctx_rows);
+
+/* One model call on the block of shape (k, w+1) of Section 3: row r =
+ * [x_last, drafts[r][0..w)] at positions n-1 .. n-1+w, all rows sharing the
+ * cached context (read once).  Then the per-position greedy argmax (lowest id
+ * on ties), the accepted length of every row and the winner.  drafts: HOST
+ * [k][w], or NULL to use what ngg_build_drafts left on the device (same k, w).
+ * Does not change the committed state.  NGG_ECAPACITY if n + w > max_seq. */
+ngg_status ngg_verify_step(ngg_ctx *ctx, const int32_t *drafts, int32_t k, int32_t w, ngg_verify_out *out);
+
+/* Commits the last verify call (Appendix D: the cache becomes that of the
+ * longest accepted speculation): appends min(n_new, max_new) tokens and the
+ * winner row's keys/values for the block columns they came from.  max_new <= 0
+ * is NGG_EINVAL; NGG_ESTATE without a preceding verify.  n_committed may be NULL. */
+ngg_status ngg_commit(ngg_ctx *ctx, int32_t max_new, int32_t *n_committed);
+
+/* Prefill + repeated (build_drafts, verify_step, commit) until n_gen tokens
+ * were generated (the first comes from the prefill).  cfg == NULL, or k = 1 and
+ * w = 0, is plain greedy decoding, one token per model call.  out_tokens: HOST
+ * [n_gen]; stats may be NULL. */
+ngg_status ngg_greedy_decode(ngg_ctx *ctx, const int32_t *prompt, int32_t n_prompt, int32_t n_gen,
+                             const ngg_draft_cfg *cfg, int32_t *out_tokens, ngg_stats *stats);
+
+/* Committed token history: copies min(n, cap) tokens to dst (HOST), n to *n. */
+ngg_status ngg_get_tokens(const ngg_ctx *ctx, int32_t *dst, int32_t cap, int32_t *n);
+
+/* Message of the last failing call on this context (ctx == NULL: of the last
+ * failing ngg_create on this thread).  Never NULL. */
+const char *ngg_last_error(const ngg_ctx *ctx);
+
+/* Per-kernel-class device time, taken with HIP events recorded on the context's
+ * stream around every launch of the classes whose bit is set in class_mask
+ * (bit i = class i, -1 = all, 0 = off).  Events between launches cost a little
+ * time: enable few classes while timing whole steps.  ngg_profile_read sums the
+ * milliseconds and launch counts per class since the last ngg_profile_reset. */
+enum {
+  NGG_PROF_GEMM_QKV = 0, NGG_PROF_GEMM_O, NGG_PROF_GEMM_GATEUP, NGG_PROF_GEMM_DOWN, NGG_PROF_GEMM_UNEMBED,
+  NGG_PROF_ATTENTION, NGG_PROF_NORM, NGG_PROF_DRAFTS, NGG_PROF_ACCEPT_COMMIT, NGG_PROF_OTHER, NGG_PROF_COUNT
+};
+ngg_status ngg_profile_enable(ngg_ctx *ctx, int32_t class_mask);
+ngg_status ngg_profile_reset(ngg_ctx *ctx);
+ngg_status ngg_profile_read(ngg_ctx *ctx, double *ms /*[NGG_PROF_COUNT]*/, int64_t *launches /*[NGG_PROF_COUNT]*/);
+
+/* Debug aid for parity tests: copies an internal device buffer to dst (HOST), at most cap bytes,
+ * and reports its full size in *bytes.  Names: "h" (residual stream, fp32 [M][d_model]), "z"
+ * (bigram scores of the last ngg_build_drafts, fp32 [vocab]), "next1" (int32 [vocab]), "hist"
+ * (int32 token history), "block_tok" (int32 block tokens of the last forward), "kcache" /
+ * "vcache" (whole caches: keys [layer][kv head][position][head_dim], values transposed
+ * [layer][kv head][head_dim][position], positions padded to *stride), "attn" (attention output of
+ * the last layer, model dtype [M][n_heads*head_dim]).  Synchronises the stream. */
+ngg_status ngg_debug_peek(ngg_ctx *ctx, const char *name, void *dst, int64_t cap, int64_t *bytes, int32_t *stride);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NGG_H */

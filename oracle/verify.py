@@ -56,7 +56,9 @@ def prefill(model: Model, prompt) -> State:
     for li, (kk, vv) in enumerate(kv):
         cache.append(li, kk[0], vv[0])
     first = int(greedy_argmax(logits[0, -1]))
-    return State(prompt + [first], cache)
+    st = State(prompt + [first], cache)
+    st.first_logits = logits[0, -1]              # logits that chose the first generated token
+    return st
 
 
 def verify_step(model: Model, state: State, drafts):

@@ -1,0 +1,574 @@
+// C ABI of libngg (declared in include/ngg.h): context, argument checks, the launch sequence of
+// one verify step and the decode loop.  Host logic only; every step of the path runs in kernels.
+#include "ngg.h"
+#include "ngg_internal.h"
+
+#include <chrono>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+using namespace ngg;
+
+namespace {
+
+constexpr int kPrefillChunk = 64;
+thread_local std::string g_create_error = "";
+
+struct ProfSpan { int cls; hipEvent_t e0, e1; };
+
+}  // namespace
+
+struct ngg_ctx {
+  ngg_model_desc d{};
+  ngg_weights w{};
+  std::vector<ngg_layer_weights> layers;
+  hipStream_t stream = nullptr;
+  int esize = 2;          // bytes per weight / KV element
+  int Spad = 0, Mcap = 0, max_splits = 0, unembed_tiles = 0;
+  // device buffers
+  int32_t *hist = nullptr, *drafts = nullptr, *block_tok = nullptr, *res = nullptr, *next1 = nullptr;
+  int32_t *mlist = nullptr, *reps = nullptr, *ctx_rows = nullptr, *n_ctx = nullptr;
+  int8_t *row_src = nullptr;
+  void *kcache = nullptr, *vcache = nullptr, *kscr = nullptr, *vscr = nullptr;
+  float *h = nullptr, *part_o = nullptr, *part_ml = nullptr, *pmax_val = nullptr, *z = nullptr, *logits = nullptr;
+  float *rope_cos = nullptr, *rope_sin = nullptr;
+  int *pmax_idx = nullptr;
+  void *xn = nullptr, *q = nullptr, *attn = nullptr, *act = nullptr;
+  int32_t *res_host = nullptr;     // pinned
+  // host state
+  std::vector<int32_t> tokens;     // committed history mirror
+  int n = 0;                       // context length (0 = no prefill yet)
+  bool have_verify = false;
+  int last_k = 0, last_w = 0;
+  bool drafts_on_device = false;
+  int drafts_k = 0, drafts_w = 0;
+  std::string err;
+  // profiling
+  int prof_mask = 0;               // bit i: record events around kernels of class i
+  std::vector<ProfSpan> spans;
+  std::vector<hipEvent_t> free_events;
+};
+
+namespace {
+
+ngg_status fail(ngg_ctx *c, ngg_status st, const char *fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (c) c->err = buf;
+  else g_create_error = buf;
+  return st;
+}
+
+#define NGG_HIP(c, call)                                                                                  \
+  do {                                                                                                    \
+    hipError_t e_ = (call);                                                                               \
+    if (e_ != hipSuccess) return fail((c), NGG_EHIP, "%s failed: %s", #call, hipGetErrorString(e_));      \
+  } while (0)
+
+inline size_t rup(size_t x, size_t m) { return (x + m - 1) / m * m; }
+
+struct ProfScope {
+  ngg_ctx *c;
+  ProfSpan sp{};
+  bool on;
+  ProfScope(ngg_ctx *ctx, int cls) : c(ctx), on(((ctx->prof_mask >> cls) & 1) != 0) {
+    if (!on) return;
+    sp.cls = cls;
+    for (hipEvent_t *e : {&sp.e0, &sp.e1}) {
+      if (!c->free_events.empty()) { *e = c->free_events.back(); c->free_events.pop_back(); }
+      else if (hipEventCreate(e) != hipSuccess) { on = false; return; }
+    }
+    (void)hipEventRecord(sp.e0, c->stream);
+  }
+  ~ProfScope() {
+    if (!on) return;
+    (void)hipEventRecord(sp.e1, c->stream);
+    c->spans.push_back(sp);
+  }
+};
+
+template <typename P>
+ngg_status dev_alloc(ngg_ctx *c, P **p, size_t bytes, bool zero) {
+  void *v = nullptr;
+  hipError_t e = hipMalloc(&v, bytes ? bytes : 16);
+  if (e != hipSuccess) return fail(c, NGG_ENOMEM, "hipMalloc(%zu) failed: %s", bytes, hipGetErrorString(e));
+  *p = (P *)v;
+  if (zero) NGG_HIP(c, hipMemsetAsync(v, 0, bytes ? bytes : 16, c->stream));
+  return NGG_OK;
+}
+
+// One forward over a block of R rows x C columns sitting at positions P .. P+C-1 on a cached
+// context of P tokens (Section 3).  Leaves this block's keys/values in the scratch, and, when
+// `unembed` is set, the per-tile argmax partials (and optional logits) of every block position.
+ngg_status forward(ngg_ctx *c, int R, int C, int P, bool from_hist, int w, bool unembed, bool want_logits) {
+  const ngg_model_desc &d = c->d;
+  const int M = R * C;
+  const int dt = d.dtype;
+  const int dq = d.n_heads * d.head_dim;
+  hipStream_t s = c->stream;
+  {
+    ProfScope ps(c, NGG_PROF_OTHER);
+    launch_embed(dt, c->w.tok_emb, c->hist, c->drafts, c->block_tok, c->h, d.d_model, M, C, w, P, from_hist ? 1 : 0, s);
+  }
+  // key spans: enough workgroups to fill 256 CUs, but spans of at least 256 keys so the partial
+  // outputs stay small next to the keys and values read
+  int n_splits = 0, span = 0;
+  if (P > 0) {
+    int want = (512 + d.n_heads - 1) / d.n_heads;
+    int by_len = (P + 255) / 256;
+    n_splits = std::max(1, std::min(std::min(want, by_len), c->max_splits));
+    span = (int)rup((size_t)(P + n_splits - 1) / n_splits, 32);
+    n_splits = (P + span - 1) / span;
+  }
+  for (int l = 0; l < d.n_layers; ++l) {
+    const ngg_layer_weights &lw = c->layers[l];
+    const size_t kv_layer = (size_t)l * d.n_kv_heads;
+    char *kscr_l = (char *)c->kscr + kv_layer * c->Mcap * d.head_dim * c->esize;
+    char *vscr_l = (char *)c->vscr + kv_layer * d.head_dim * c->Mcap * c->esize;
+    { ProfScope ps(c, NGG_PROF_NORM); launch_rmsnorm(dt, c->h, lw.attn_norm, c->xn, d.d_model, M, d.rms_eps, s); }
+    {
+      ProfScope ps(c, NGG_PROF_GEMM_QKV);
+      GemmArgs g{};
+      g.X = c->xn; g.ldx = d.d_model; g.W0 = lw.wq; g.W1 = lw.wk; g.W2 = lw.wv;
+      g.M = M; g.N = dq + 2 * d.n_kv_heads * d.head_dim; g.K = d.d_model;
+      g.q = c->q; g.kscr = kscr_l; g.vscr = vscr_l;
+      g.H = d.n_heads; g.Hkv = d.n_kv_heads; g.hd = d.head_dim; g.Mcap = c->Mcap; g.C = C; g.P = P;
+      g.rope_cos = c->rope_cos; g.rope_sin = c->rope_sin;
+      launch_gemm(dt, EPI_QKV, g, s);
+    }
+    {
+      ProfScope ps(c, NGG_PROF_ATTENTION);
+      AttnArgs a{};
+      a.q = c->q;
+      a.kcache = (char *)c->kcache + kv_layer * c->Spad * d.head_dim * c->esize;
+      a.vcache = (char *)c->vcache + kv_layer * d.head_dim * c->Spad * c->esize;
+      a.kscr = kscr_l; a.vscr = vscr_l;
+      a.part_o = c->part_o; a.part_ml = c->part_ml; a.out = c->attn;
+      a.H = d.n_heads; a.Hkv = d.n_kv_heads; a.Mcap = c->Mcap; a.Spad = c->Spad; a.M = M; a.C = C; a.P = P;
+      a.n_splits = n_splits; a.span = span;
+      a.scale = 1.0f / std::sqrt((float)d.head_dim);
+      launch_attention(dt, d.head_dim, a, s);
+    }
+    {
+      ProfScope ps(c, NGG_PROF_GEMM_O);
+      GemmArgs g{};
+      g.X = c->attn; g.ldx = dq; g.W0 = lw.wo; g.M = M; g.N = d.d_model; g.K = dq; g.h = c->h;
+      launch_gemm(dt, EPI_RESIDUAL, g, s);
+    }
+    { ProfScope ps(c, NGG_PROF_NORM); launch_rmsnorm(dt, c->h, lw.mlp_norm, c->xn, d.d_model, M, d.rms_eps, s); }
+    {
+      ProfScope ps(c, NGG_PROF_GEMM_GATEUP);
+      GemmArgs g{};
+      g.X = c->xn; g.ldx = d.d_model; g.W0 = lw.w_gate; g.W1 = lw.w_up; g.M = M; g.N = d.d_ffn; g.K = d.d_model;
+      g.act = c->act;
+      launch_gemm(dt, EPI_GATEUP, g, s);
+    }
+    {
+      ProfScope ps(c, NGG_PROF_GEMM_DOWN);
+      GemmArgs g{};
+      g.X = c->act; g.ldx = d.d_ffn; g.W0 = lw.w_down; g.M = M; g.N = d.d_model; g.K = d.d_ffn; g.h = c->h;
+      launch_gemm(dt, EPI_RESIDUAL, g, s);
+    }
+  }
+  if (unembed) {
+    { ProfScope ps(c, NGG_PROF_NORM); launch_rmsnorm(dt, c->h, c->w.final_norm, c->xn, d.d_model, M, d.rms_eps, s); }
+    ProfScope ps(c, NGG_PROF_GEMM_UNEMBED);
+    GemmArgs g{};
+    g.X = c->xn; g.ldx = d.d_model; g.W0 = c->w.unemb; g.M = M; g.N = d.vocab; g.K = d.d_model;
+    g.logits = want_logits ? c->logits : nullptr;
+    g.pmax_val = c->pmax_val; g.pmax_idx = c->pmax_idx; g.Mcap = c->Mcap;
+    launch_gemm(dt, EPI_UNEMBED, g, s);
+  }
+  NGG_HIP(c, hipGetLastError());
+  return NGG_OK;
+}
+
+ngg_status ensure_logits(ngg_ctx *c) {
+  if (c->logits) return NGG_OK;
+  return dev_alloc(c, &c->logits, (size_t)c->Mcap * c->d.vocab * sizeof(float), false);
+}
+
+ngg_status build_next1(ngg_ctx *c) {
+  // next1[x] = argmax_v <unemb[v], tok_emb[x]>: the unembedding GEMM applied to rows of the input
+  // embedding (no normalisation), 64 vocabulary entries per pass.
+  const ngg_model_desc &d = c->d;
+  for (int x0 = 0; x0 < d.vocab; x0 += 64) {
+    const int M = std::min(64, d.vocab - x0);
+    GemmArgs g{};
+    g.X = (const char *)c->w.tok_emb + (size_t)x0 * d.d_model * c->esize;
+    g.ldx = d.d_model; g.W0 = c->w.unemb; g.M = M; g.N = d.vocab; g.K = d.d_model;
+    g.pmax_val = c->pmax_val; g.pmax_idx = c->pmax_idx; g.Mcap = c->Mcap;
+    launch_gemm(d.dtype, EPI_UNEMBED, g, c->stream);
+    launch_next1_finish(c->pmax_val, c->pmax_idx, c->unembed_tiles, c->Mcap, M, c->next1 + x0, c->stream);
+  }
+  NGG_HIP(c, hipGetLastError());
+  NGG_HIP(c, hipStreamSynchronize(c->stream));
+  return NGG_OK;
+}
+
+double now_ms() {
+  return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *ngg_last_error(const ngg_ctx *ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }
+
+ngg_status ngg_destroy(ngg_ctx *c) {
+  if (!c) return NGG_EINVAL;
+  (void)hipStreamSynchronize(c->stream);
+  void *bufs[] = {c->hist, c->drafts, c->block_tok, c->res, c->next1, c->mlist, c->reps, c->ctx_rows, c->n_ctx,
+                  c->row_src, c->kcache, c->vcache, c->kscr, c->vscr, c->h, c->part_o, c->part_ml, c->pmax_val, c->z,
+                  c->logits, c->rope_cos, c->rope_sin, c->pmax_idx, c->xn, c->q, c->attn, c->act};
+  for (void *b : bufs)
+    if (b) (void)hipFree(b);
+  if (c->res_host) (void)hipHostFree(c->res_host);
+  for (auto &sp : c->spans) { (void)hipEventDestroy(sp.e0); (void)hipEventDestroy(sp.e1); }
+  for (auto e : c->free_events) (void)hipEventDestroy(e);
+  delete c;
+  return NGG_OK;
+}
+
+ngg_status ngg_create(const ngg_model_desc *desc, const ngg_weights *weights, void *hip_stream, ngg_ctx **out) {
+  if (!desc || !weights || !out) return fail(nullptr, NGG_EINVAL, "ngg_create: null argument");
+  *out = nullptr;
+  const ngg_model_desc &d = *desc;
+  if (d.dtype != NGG_F32 && d.dtype != NGG_BF16) return fail(nullptr, NGG_EINVAL, "ngg_create: dtype must be NGG_F32 or NGG_BF16");
+  if (d.n_layers < 1 || d.d_model < 32 || d.n_heads < 1 || d.n_kv_heads < 1 || d.d_ffn < 32 || d.vocab < 16)
+    return fail(nullptr, NGG_EINVAL, "ngg_create: non-positive model dimension");
+  if (d.head_dim != 32 && d.head_dim != 64 && d.head_dim != 128)
+    return fail(nullptr, NGG_EINVAL, "ngg_create: head_dim %d not in {32, 64, 128}", d.head_dim);
+  if (d.d_model % 32 || d.d_ffn % 32 || (d.n_heads * d.head_dim) % 32)
+    return fail(nullptr, NGG_EINVAL, "ngg_create: d_model, d_ffn and n_heads*head_dim must be multiples of 32");
+  if (d.vocab % 16) return fail(nullptr, NGG_EINVAL, "ngg_create: vocab must be a multiple of 16");
+  if (d.n_heads % d.n_kv_heads) return fail(nullptr, NGG_EINVAL, "ngg_create: n_heads must be a multiple of n_kv_heads");
+  if (d.max_k < 1 || d.max_k > 32 || d.max_w < 0 || d.max_w > 32)
+    return fail(nullptr, NGG_EINVAL, "ngg_create: need 1 <= max_k <= 32 and 0 <= max_w <= 32");
+  if (d.max_seq < 2) return fail(nullptr, NGG_EINVAL, "ngg_create: max_seq must be at least 2");
+  if (!(d.rms_eps >= 0.0f) || !(d.rope_theta > 0.0f)) return fail(nullptr, NGG_EINVAL, "ngg_create: bad rms_eps / rope_theta");
+  if (!weights->tok_emb || !weights->unemb || !weights->final_norm || !weights->layers)
+    return fail(nullptr, NGG_EINVAL, "ngg_create: null weight pointer");
+  for (int l = 0; l < d.n_layers; ++l) {
+    const ngg_layer_weights &lw = weights->layers[l];
+    if (!lw.attn_norm || !lw.wq || !lw.wk || !lw.wv || !lw.wo || !lw.mlp_norm || !lw.w_gate || !lw.w_up || !lw.w_down)
+      return fail(nullptr, NGG_EINVAL, "ngg_create: null weight pointer in layer %d", l);
+  }
+
+  ngg_ctx *c = new (std::nothrow) ngg_ctx;
+  if (!c) return fail(nullptr, NGG_ENOMEM, "ngg_create: out of host memory");
+  c->d = d;
+  c->w = *weights;
+  c->layers.assign(weights->layers, weights->layers + d.n_layers);
+  c->w.layers = c->layers.data();
+  c->stream = (hipStream_t)hip_stream;
+  c->esize = d.dtype == NGG_BF16 ? 2 : 4;
+  c->Spad = (int)rup((size_t)d.max_seq + 1, 32);
+  c->Mcap = (int)rup((size_t)std::max(d.max_k * (d.max_w + 1), kPrefillChunk), 32);
+  c->max_splits = 32;
+  c->unembed_tiles = gemm_unembed_tiles(d.vocab);
+
+  const size_t kv_elems = (size_t)d.n_layers * d.n_kv_heads * d.head_dim;
+  const int dq = d.n_heads * d.head_dim;
+  ngg_status st = NGG_OK;
+#define TRY(x) do { if (st == NGG_OK) st = (x); } while (0)
+  TRY(dev_alloc(c, &c->hist, (size_t)c->Spad * 4, true));
+  TRY(dev_alloc(c, &c->drafts, (size_t)d.max_k * std::max(1, d.max_w) * 4, true));
+  TRY(dev_alloc(c, &c->block_tok, (size_t)c->Mcap * 4, true));
+  TRY(dev_alloc(c, &c->res, (size_t)(res_greedy_off(d.max_k) + c->Mcap) * 4, true));
+  TRY(dev_alloc(c, &c->next1, (size_t)d.vocab * 4, true));
+  TRY(dev_alloc(c, &c->mlist, (size_t)c->Spad * 4, true));
+  TRY(dev_alloc(c, &c->reps, (size_t)c->Spad * 8, true));
+  TRY(dev_alloc(c, &c->ctx_rows, (size_t)d.max_k * std::max(1, d.max_w) * 4, true));
+  TRY(dev_alloc(c, &c->n_ctx, 16, true));
+  TRY(dev_alloc(c, &c->row_src, (size_t)d.max_k, true));
+  TRY(dev_alloc(c, &c->kcache, kv_elems * c->Spad * c->esize, true));
+  TRY(dev_alloc(c, &c->vcache, kv_elems * c->Spad * c->esize, true));
+  TRY(dev_alloc(c, &c->kscr, kv_elems * c->Mcap * c->esize, true));
+  TRY(dev_alloc(c, &c->vscr, kv_elems * c->Mcap * c->esize, true));
+  TRY(dev_alloc(c, &c->h, (size_t)c->Mcap * d.d_model * 4, true));
+  TRY(dev_alloc(c, &c->xn, (size_t)c->Mcap * d.d_model * c->esize, true));
+  TRY(dev_alloc(c, &c->q, (size_t)c->Mcap * dq * c->esize, true));
+  TRY(dev_alloc(c, &c->attn, (size_t)c->Mcap * dq * c->esize, true));
+  TRY(dev_alloc(c, &c->act, (size_t)c->Mcap * d.d_ffn * c->esize, true));
+  TRY(dev_alloc(c, &c->part_o, (size_t)d.n_heads * (c->max_splits + 1) * c->Mcap * d.head_dim * 4, true));
+  TRY(dev_alloc(c, &c->part_ml, (size_t)d.n_heads * (c->max_splits + 1) * c->Mcap * 2 * 4, true));
+  TRY(dev_alloc(c, &c->pmax_val, (size_t)c->unembed_tiles * c->Mcap * 4, true));
+  TRY(dev_alloc(c, &c->pmax_idx, (size_t)c->unembed_tiles * c->Mcap * 4, true));
+  TRY(dev_alloc(c, &c->z, (size_t)d.vocab * 4, true));
+  const int half = d.head_dim / 2;
+  TRY(dev_alloc(c, &c->rope_cos, (size_t)c->Spad * half * 4, false));
+  TRY(dev_alloc(c, &c->rope_sin, (size_t)c->Spad * half * 4, false));
+#undef TRY
+  if (st == NGG_OK && hipHostMalloc((void **)&c->res_host, (size_t)(res_greedy_off(d.max_k) + c->Mcap) * 4) != hipSuccess)
+    st = fail(c, NGG_ENOMEM, "ngg_create: hipHostMalloc failed");
+  if (st == NGG_OK) {
+    // rotary table in double on the host: angle = pos * theta^(-2i/head_dim)
+    std::vector<float> cs((size_t)c->Spad * half), sn((size_t)c->Spad * half);
+    for (int i = 0; i < half; ++i) {
+      const double inv = std::pow((double)d.rope_theta, -2.0 * i / d.head_dim);
+      for (int p = 0; p < c->Spad; ++p) {
+        cs[(size_t)p * half + i] = (float)std::cos(p * inv);
+        sn[(size_t)p * half + i] = (float)std::sin(p * inv);
+      }
+    }
+    hipError_t e = hipMemcpy(c->rope_cos, cs.data(), cs.size() * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(c->rope_sin, sn.data(), sn.size() * 4, hipMemcpyHostToDevice);
+    if (e != hipSuccess) st = fail(c, NGG_EHIP, "ngg_create: rotary table upload failed: %s", hipGetErrorString(e));
+  }
+  if (st == NGG_OK) st = build_next1(c);
+  if (st != NGG_OK) {
+    g_create_error = c->err;
+    ngg_destroy(c);
+    return st;
+  }
+  c->tokens.reserve(d.max_seq);
+  *out = c;
+  return NGG_OK;
+}
+
+ngg_status ngg_prefill(ngg_ctx *c, const int32_t *prompt, int32_t n_prompt) {
+  if (!c) return NGG_EINVAL;
+  if (!prompt || n_prompt < 1) return fail(c, NGG_EINVAL, "ngg_prefill: need a prompt of at least one token");
+  if (n_prompt + 1 > c->d.max_seq) return fail(c, NGG_ECAPACITY, "ngg_prefill: prompt of %d tokens exceeds max_seq %d", n_prompt, c->d.max_seq);
+  for (int i = 0; i < n_prompt; ++i)
+    if (prompt[i] < 0 || prompt[i] >= c->d.vocab) return fail(c, NGG_EINVAL, "ngg_prefill: token %d at %d out of range", prompt[i], i);
+  c->n = 0;
+  c->have_verify = false;
+  c->drafts_on_device = false;
+  c->tokens.assign(prompt, prompt + n_prompt);
+  NGG_HIP(c, hipMemcpyAsync(c->hist, prompt, (size_t)n_prompt * 4, hipMemcpyHostToDevice, c->stream));
+  const ngg_model_desc &d = c->d;
+  for (int p0 = 0; p0 < n_prompt; p0 += kPrefillChunk) {
+    const int C = std::min(kPrefillChunk, n_prompt - p0);
+    const bool last = p0 + C == n_prompt;
+    ngg_status st = forward(c, 1, C, p0, true, 0, last, false);
+    if (st != NGG_OK) return st;
+    ProfScope ps(c, NGG_PROF_ACCEPT_COMMIT);
+    if (last)
+      launch_argmax_accept(c->pmax_val, c->pmax_idx, c->unembed_tiles, c->Mcap, C, 0, C, nullptr, c->res,
+                           res_greedy_off(d.max_k), c->stream);
+    launch_commit(d.dtype, c->kcache, c->vcache, c->kscr, c->vscr, d.n_layers, d.n_kv_heads, d.head_dim, c->Spad,
+                  c->Mcap, C, p0, nullptr, 0, C, C, c->hist, c->stream);
+  }
+  // first generated token = greedy prediction after the last prompt token
+  const int last_c = (n_prompt - 1) % kPrefillChunk;
+  int32_t first = 0;
+  NGG_HIP(c, hipMemcpyAsync(&first, c->res + res_greedy_off(d.max_k) + last_c, 4, hipMemcpyDeviceToHost, c->stream));
+  NGG_HIP(c, hipStreamSynchronize(c->stream));
+  NGG_HIP(c, hipMemcpyAsync(c->hist + n_prompt, &first, 4, hipMemcpyHostToDevice, c->stream));
+  NGG_HIP(c, hipStreamSynchronize(c->stream));
+  c->tokens.push_back(first);
+  c->n = n_prompt + 1;
+  return NGG_OK;
+}
+
+ngg_status ngg_build_drafts(ngg_ctx *c, const ngg_draft_cfg *cfg, int32_t *drafts, int8_t *row_src, int32_t *n_ctx_rows) {
+  if (!c) return NGG_EINVAL;
+  if (!cfg) return fail(c, NGG_EINVAL, "ngg_build_drafts: null cfg");
+  if (c->n < 1) return fail(c, NGG_ESTATE, "ngg_build_drafts: no context (call ngg_prefill first)");
+  if (cfg->k < 1 || cfg->w < 0) return fail(c, NGG_EINVAL, "ngg_build_drafts: need k >= 1 and w >= 0");
+  if (cfg->k > c->d.max_k || cfg->w > c->d.max_w) return fail(c, NGG_ECAPACITY, "ngg_build_drafts: k=%d w=%d exceed max_k=%d max_w=%d", cfg->k, cfg->w, c->d.max_k, c->d.max_w);
+  if (cfg->k_ctx_max < 0 || cfg->q_min < 1 || cfg->q_max < cfg->q_min || cfg->q_max > 64)
+    return fail(c, NGG_EINVAL, "ngg_build_drafts: need k_ctx_max >= 0 and 1 <= q_min <= q_max <= 64");
+  if (cfg->k > c->d.vocab) return fail(c, NGG_EINVAL, "ngg_build_drafts: k exceeds the vocabulary");
+  {
+    ProfScope ps(c, NGG_PROF_DRAFTS);
+    DraftArgs a{};
+    a.hist = c->hist; a.n = c->n; a.k = cfg->k; a.w = cfg->w; a.k_ctx_max = cfg->k_ctx_max; a.q_min = cfg->q_min; a.q_max = cfg->q_max;
+    a.mlist = c->mlist; a.reps = c->reps; a.ctx_rows = c->ctx_rows; a.n_ctx = c->n_ctx;
+    a.tok_emb = c->w.tok_emb; a.unemb = c->w.unemb; a.d = c->d.d_model; a.vocab = c->d.vocab; a.z = c->z; a.next1 = c->next1;
+    a.drafts = c->drafts; a.row_src = c->row_src;
+    launch_build_drafts(c->d.dtype, a, c->stream);
+  }
+  NGG_HIP(c, hipGetLastError());
+  c->drafts_on_device = true;
+  c->drafts_k = cfg->k;
+  c->drafts_w = cfg->w;
+  if (drafts || row_src || n_ctx_rows) {
+    if (drafts && cfg->w > 0) NGG_HIP(c, hipMemcpyAsync(drafts, c->drafts, (size_t)cfg->k * cfg->w * 4, hipMemcpyDeviceToHost, c->stream));
+    if (row_src) NGG_HIP(c, hipMemcpyAsync(row_src, c->row_src, (size_t)cfg->k, hipMemcpyDeviceToHost, c->stream));
+    if (n_ctx_rows) NGG_HIP(c, hipMemcpyAsync(n_ctx_rows, c->n_ctx, 4, hipMemcpyDeviceToHost, c->stream));
+    NGG_HIP(c, hipStreamSynchronize(c->stream));
+  }
+  return NGG_OK;
+}
+
+ngg_status ngg_verify_step(ngg_ctx *c, const int32_t *drafts, int32_t k, int32_t w, ngg_verify_out *out) {
+  if (!c) return NGG_EINVAL;
+  if (!out) return fail(c, NGG_EINVAL, "ngg_verify_step: null out");
+  if (c->n < 1) return fail(c, NGG_ESTATE, "ngg_verify_step: no context (call ngg_prefill first)");
+  if (k < 1 || w < 0) return fail(c, NGG_EINVAL, "ngg_verify_step: need k >= 1 and w >= 0");
+  if (k > c->d.max_k || w > c->d.max_w) return fail(c, NGG_ECAPACITY, "ngg_verify_step: k=%d w=%d exceed max_k=%d max_w=%d", k, w, c->d.max_k, c->d.max_w);
+  if (c->n + w > c->d.max_seq) return fail(c, NGG_ECAPACITY, "ngg_verify_step: n=%d + w=%d exceeds max_seq=%d", c->n, w, c->d.max_seq);
+  const ngg_model_desc &d = c->d;
+  if (drafts) {
+    for (int i = 0; i < k * w; ++i)
+      if (drafts[i] < 0 || drafts[i] >= d.vocab) return fail(c, NGG_EINVAL, "ngg_verify_step: draft token %d out of range", drafts[i]);
+    if (w > 0) NGG_HIP(c, hipMemcpyAsync(c->drafts, drafts, (size_t)k * w * 4, hipMemcpyHostToDevice, c->stream));
+    c->drafts_on_device = true;
+    c->drafts_k = k;
+    c->drafts_w = w;
+  } else if (w > 0 && (!c->drafts_on_device || c->drafts_k != k || c->drafts_w != w)) {
+    return fail(c, NGG_ESTATE, "ngg_verify_step: no device drafts of shape (%d, %d); call ngg_build_drafts or pass drafts", k, w);
+  }
+  if (out->logits) { ngg_status st = ensure_logits(c); if (st != NGG_OK) return st; }
+  const int C = w + 1, M = k * C;
+  ngg_status st = forward(c, k, C, c->n - 1, false, w, true, out->logits != nullptr);
+  if (st != NGG_OK) return st;
+  const int goff = res_greedy_off(d.max_k);
+  {
+    ProfScope ps(c, NGG_PROF_ACCEPT_COMMIT);
+    launch_argmax_accept(c->pmax_val, c->pmax_idx, c->unembed_tiles, c->Mcap, M, k, C, c->drafts, c->res, goff, c->stream);
+  }
+  NGG_HIP(c, hipGetLastError());
+  NGG_HIP(c, hipMemcpyAsync(c->res_host, c->res, (size_t)(goff + M) * 4, hipMemcpyDeviceToHost, c->stream));
+  if (out->logits) NGG_HIP(c, hipMemcpyAsync(out->logits, c->logits, (size_t)M * d.vocab * 4, hipMemcpyDeviceToHost, c->stream));
+  NGG_HIP(c, hipStreamSynchronize(c->stream));
+  out->k = k; out->w = w;
+  out->winner = c->res_host[RES_WINNER];
+  out->n_accept = c->res_host[RES_NACCEPT];
+  out->n_new = c->res_host[RES_NNEW];
+  if (out->greedy) memcpy(out->greedy, c->res_host + goff, (size_t)M * 4);
+  if (out->accept_len) memcpy(out->accept_len, c->res_host + RES_ACCEPT, (size_t)k * 4);
+  if (out->new_tokens) memcpy(out->new_tokens, c->res_host + RES_NEWTOK, (size_t)out->n_new * 4);
+  c->have_verify = true;
+  c->last_k = k;
+  c->last_w = w;
+  return NGG_OK;
+}
+
+ngg_status ngg_commit(ngg_ctx *c, int32_t max_new, int32_t *n_committed) {
+  if (!c) return NGG_EINVAL;
+  if (max_new <= 0) return fail(c, NGG_EINVAL, "ngg_commit: max_new must be positive");
+  if (!c->have_verify) return fail(c, NGG_ESTATE, "ngg_commit: no verify call to commit");
+  const ngg_model_desc &d = c->d;
+  const int n_new = std::min(c->res_host[RES_NNEW], max_new);
+  if (c->n + n_new > d.max_seq) return fail(c, NGG_ECAPACITY, "ngg_commit: n=%d + %d exceeds max_seq=%d", c->n, n_new, d.max_seq);
+  {
+    ProfScope ps(c, NGG_PROF_ACCEPT_COMMIT);
+    launch_commit(d.dtype, c->kcache, c->vcache, c->kscr, c->vscr, d.n_layers, d.n_kv_heads, d.head_dim, c->Spad, c->Mcap,
+                  c->last_w + 1, c->n - 1, c->res, 0, 0, max_new, c->hist, c->stream);
+  }
+  NGG_HIP(c, hipGetLastError());
+  for (int i = 0; i < n_new; ++i) c->tokens.push_back(c->res_host[RES_NEWTOK + i]);
+  c->n += n_new;
+  c->have_verify = false;
+  c->drafts_on_device = false;
+  if (n_committed) *n_committed = n_new;
+  return NGG_OK;
+}
+
+ngg_status ngg_greedy_decode(ngg_ctx *c, const int32_t *prompt, int32_t n_prompt, int32_t n_gen, const ngg_draft_cfg *cfg,
+                             int32_t *out_tokens, ngg_stats *stats) {
+  if (!c) return NGG_EINVAL;
+  if (!out_tokens || n_gen < 1) return fail(c, NGG_EINVAL, "ngg_greedy_decode: need out_tokens and n_gen >= 1");
+  if ((long)n_prompt + n_gen > c->d.max_seq) return fail(c, NGG_ECAPACITY, "ngg_greedy_decode: %d + %d tokens exceed max_seq=%d", n_prompt, n_gen, c->d.max_seq);
+  ngg_draft_cfg plain{1, 0, 0, 1, 1};
+  if (!cfg) cfg = &plain;
+  ngg_stats st{};
+  double t0 = now_ms();
+  ngg_status rc = ngg_prefill(c, prompt, n_prompt);
+  if (rc != NGG_OK) return rc;
+  st.ms_prefill = now_ms() - t0;
+  std::vector<int8_t> src(cfg->k);
+  while (c->n - n_prompt < n_gen) {
+    // drafts wider than the remaining budget are pointless, and n + w must stay within max_seq
+    ngg_draft_cfg step = *cfg;
+    const int left = n_gen - (c->n - n_prompt);
+    step.w = std::min(step.w, std::max(0, std::min(left - 1, c->d.max_seq - c->n)));
+    int32_t n_ctx = 0;
+    t0 = now_ms();
+    rc = ngg_build_drafts(c, &step, nullptr, src.data(), &n_ctx);
+    if (rc != NGG_OK) return rc;
+    double t1 = now_ms();
+    ngg_verify_out vo{};
+    rc = ngg_verify_step(c, nullptr, step.k, step.w, &vo);
+    if (rc != NGG_OK) return rc;
+    double t2 = now_ms();
+    int32_t n_new = 0;
+    rc = ngg_commit(c, left, &n_new);
+    if (rc != NGG_OK) return rc;
+    double t3 = now_ms();
+    st.ms_drafts += t1 - t0; st.ms_verify += t2 - t1; st.ms_commit += t3 - t2;
+    st.calls += 1;
+    st.new_hist[n_new] += 1;
+    st.winner_src[src[vo.winner] ? 1 : 0] += 1;
+    st.ctx_rows += n_ctx;
+  }
+  NGG_HIP(c, hipStreamSynchronize(c->stream));
+  st.tokens = n_gen;
+  memcpy(out_tokens, c->tokens.data() + n_prompt, (size_t)n_gen * 4);
+  if (stats) *stats = st;
+  return NGG_OK;
+}
+
+ngg_status ngg_get_tokens(const ngg_ctx *c, int32_t *dst, int32_t cap, int32_t *n) {
+  if (!c || !n) return NGG_EINVAL;
+  *n = c->n;
+  if (dst && cap > 0) memcpy(dst, c->tokens.data(), (size_t)std::min(cap, c->n) * 4);
+  return NGG_OK;
+}
+
+ngg_status ngg_profile_enable(ngg_ctx *c, int32_t class_mask) {
+  if (!c) return NGG_EINVAL;
+  c->prof_mask = class_mask;
+  return NGG_OK;
+}
+
+ngg_status ngg_profile_reset(ngg_ctx *c) {
+  if (!c) return NGG_EINVAL;
+  NGG_HIP(c, hipStreamSynchronize(c->stream));
+  for (auto &sp : c->spans) { c->free_events.push_back(sp.e0); c->free_events.push_back(sp.e1); }
+  c->spans.clear();
+  return NGG_OK;
+}
+
+ngg_status ngg_profile_read(ngg_ctx *c, double *ms, int64_t *launches) {
+  if (!c || !ms || !launches) return NGG_EINVAL;
+  NGG_HIP(c, hipStreamSynchronize(c->stream));
+  for (int i = 0; i < NGG_PROF_COUNT; ++i) { ms[i] = 0.0; launches[i] = 0; }
+  for (auto &sp : c->spans) {
+    float t = 0.0f;
+    NGG_HIP(c, hipEventElapsedTime(&t, sp.e0, sp.e1));
+    ms[sp.cls] += t;
+    launches[sp.cls] += 1;
+  }
+  return NGG_OK;
+}
+
+ngg_status ngg_debug_peek(ngg_ctx *c, const char *name, void *dst, int64_t cap, int64_t *bytes, int32_t *stride) {
+  if (!c || !name || !bytes) return NGG_EINVAL;
+  const ngg_model_desc &d = c->d;
+  const void *src = nullptr;
+  size_t sz = 0;
+  const size_t kv = (size_t)d.n_layers * d.n_kv_heads * d.head_dim * c->Spad * c->esize;
+  const std::string nm(name);
+  if (nm == "h") { src = c->h; sz = (size_t)c->Mcap * d.d_model * 4; }
+  else if (nm == "z") { src = c->z; sz = (size_t)d.vocab * 4; }
+  else if (nm == "next1") { src = c->next1; sz = (size_t)d.vocab * 4; }
+  else if (nm == "hist") { src = c->hist; sz = (size_t)c->Spad * 4; }
+  else if (nm == "block_tok") { src = c->block_tok; sz = (size_t)c->Mcap * 4; }
+  else if (nm == "kcache") { src = c->kcache; sz = kv; }
+  else if (nm == "vcache") { src = c->vcache; sz = kv; }
+  else if (nm == "attn") { src = c->attn; sz = (size_t)c->Mcap * d.n_heads * d.head_dim * c->esize; }
+  else return fail(c, NGG_EINVAL, "ngg_debug_peek: unknown buffer '%s'", name);
+  *bytes = (int64_t)sz;
+  if (stride) *stride = c->Spad;
+  if (dst && cap > 0) {
+    NGG_HIP(c, hipMemcpyAsync(dst, src, std::min((size_t)cap, sz), hipMemcpyDeviceToHost, c->stream));
+    NGG_HIP(c, hipStreamSynchronize(c->stream));
+  }
+  return NGG_OK;
+}
+
+}  // extern "C"

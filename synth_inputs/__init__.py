@@ -176,3 +176,27 @@ def make_prompt(run: dict, vocab: int, seed: int = 1) -> np.ndarray:
     if run["prompt"] == "motif":
         return prompt_motif(vocab, run["prompt_len"], seed)
     return prompt_spans(vocab, run["prompt_len"], run["copied"], seed)
+
+
+def make_weights_device(m: dict, seed: int = 0, std: float = 0.02, device: str = "cuda") -> dict:
+    """Same structure as make_weights, generated on the device with torch's seeded generator
+    (for shapes too large to draw on the host in reasonable time).  The stream differs from
+    make_weights'; tensors are of the model's storage type."""
+    import torch
+    dt = torch.bfloat16 if m["dtype"] == "bf16" else torch.float32
+    gen = torch.Generator(device=device)
+    gen.manual_seed(1000003 * seed + 0x77)
+
+    def mat(shape):
+        return (torch.randn(shape, generator=gen, device=device, dtype=torch.float32) * std).to(dt)
+
+    def gain(shape):
+        return torch.ones(shape, device=device, dtype=dt)
+
+    V, d = m["vocab"], m["d_model"]
+    w = dict(tok_emb=mat((V, d)), unemb=mat((V, d)), final_norm=gain((d,)), layers=[])
+    shapes = layer_shapes(m)
+    for _ in range(m["n_layers"]):
+        w["layers"].append({name: (gain(shapes[name]) if name.endswith("norm") else mat(shapes[name]))
+                            for name in LAYER_TENSORS})
+    return w

@@ -1,0 +1,93 @@
+"""Host-side checks that need no GPU: the C-ABI library loads, exports every
+symbol include/ngg.h declares, and rejects bad arguments before touching the device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2411_03786_amd as ngg
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(ngg.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    return ngg.load_library()
+
+
+def test_library_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "ngg.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(ngg_[a-z0-9_]+)\s*\(", header))
+    assert {"ngg_build_drafts", "ngg_verify_step", "ngg_commit", "ngg_greedy_decode"} <= declared
+    for name in sorted(declared):
+        assert hasattr(lib, name), f"{name} declared in ngg.h but not exported"
+    assert declared == set(ngg.EXPORTS)
+
+
+def test_struct_sizes_match_the_header():
+    assert C.sizeof(ngg.ngg_model_desc) == 13 * 4
+    assert C.sizeof(ngg.ngg_layer_weights) == 9 * 8
+    assert C.sizeof(ngg.ngg_draft_cfg) == 5 * 4
+    assert C.sizeof(ngg.ngg_verify_out) == 5 * 4 + 4 + 4 * 8          # 4 bytes of padding before the pointers
+    assert C.sizeof(ngg.ngg_stats) == 8 * (2 + 34 + 2 + 1) + 4 * 8
+
+
+def _desc(**over):
+    base = dict(n_layers=2, d_model=128, n_heads=4, n_kv_heads=4, head_dim=32, d_ffn=512, vocab=512, dtype=0,
+                rms_eps=1e-5, rope_theta=10000.0, max_seq=256, max_k=4, max_w=3)
+    base.update(over)
+    return ngg.ngg_model_desc(*[base[n] for n, _ in ngg.ngg_model_desc._fields_])
+
+
+@pytest.mark.parametrize("over,frag", [
+    (dict(dtype=7), "dtype"), (dict(head_dim=48), "head_dim"), (dict(d_model=100), "multiples of 32"),
+    (dict(vocab=500), "vocab"), (dict(n_kv_heads=3), "n_kv_heads"), (dict(max_k=0), "max_k"),
+    (dict(max_k=33), "max_k"), (dict(max_w=40), "max_w"), (dict(max_seq=1), "max_seq"), (dict(n_layers=0), "dimension"),
+])
+def test_create_rejects_bad_shapes_before_any_device_work(lib, over, frag):
+    d = _desc(**over)
+    w = ngg.ngg_weights()
+    layers = (ngg.ngg_layer_weights * 2)()
+    w.tok_emb = w.unemb = w.final_norm = 16           # non-null dummies; never dereferenced on this path
+    w.layers = layers
+    out = C.c_void_p()
+    st = lib.ngg_create(C.byref(d), C.byref(w), None, C.byref(out))
+    assert st == ngg.NGG_EINVAL and not out.value
+    assert frag in lib.ngg_last_error(None).decode()
+
+
+def test_create_rejects_null_pointers(lib):
+    out = C.c_void_p()
+    assert lib.ngg_create(None, None, None, C.byref(out)) == ngg.NGG_EINVAL
+    d = _desc()
+    w = ngg.ngg_weights()                              # all null
+    assert lib.ngg_create(C.byref(d), C.byref(w), None, C.byref(out)) == ngg.NGG_EINVAL
+    assert "null weight" in lib.ngg_last_error(None).decode()
+    layers = (ngg.ngg_layer_weights * 2)()             # null layer pointers
+    w.tok_emb = w.unemb = w.final_norm = 16
+    w.layers = layers
+    assert lib.ngg_create(C.byref(d), C.byref(w), None, C.byref(out)) == ngg.NGG_EINVAL
+    assert "layer 0" in lib.ngg_last_error(None).decode()
+
+
+def test_calls_on_a_null_context_fail_cleanly(lib):
+    assert lib.ngg_prefill(None, None, 0) == ngg.NGG_EINVAL
+    assert lib.ngg_commit(None, 1, None) == ngg.NGG_EINVAL
+    assert lib.ngg_destroy(None) == ngg.NGG_EINVAL
+    assert lib.ngg_verify_step(None, None, 1, 0, None) == ngg.NGG_EINVAL
+    assert isinstance(lib.ngg_last_error(None), bytes)
+
+
+def test_binding_refuses_to_run_without_a_gpu():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("GPU present")
+    import synth_inputs as si
+    desc = si.MODELS["tiny"]
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        ngg.Context(desc, si.make_weights(desc), max_seq=64, max_k=2, max_w=2)
