@@ -39,8 +39,8 @@ typedef enum { NGG_F32 = 0, NGG_BF16 = 1 } ngg_dtype;
  * RMSNorm, rotary multi-head attention (rotate-half pairing: element i pairs
  * with i + head_dim/2), SwiGLU feed-forward, no biases, a final RMSNorm and an
  * untied output embedding.  Constraints checked by ngg_create: head_dim in
- * {32, 64, 128}; d_model, d_ffn and n_heads*head_dim multiples of 32; vocab a
- * multiple of 16; n_heads a multiple of n_kv_heads. */
+ * {32, 64, 128}; d_model, d_ffn, n_heads*head_dim and vocab multiples of 32;
+ * n_heads a multiple of n_kv_heads. */
 typedef struct {
   int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
   int32_t dtype;      /* ngg_dtype of weights, KV cache and GEMM inputs; accumulation is always fp32 */
@@ -51,7 +51,10 @@ typedef struct {
 } ngg_model_desc;
 
 /* DEVICE pointers, row-major [out][in], element type desc.dtype.  BORROWED:
- * the caller keeps them alive and unchanged for the life of the context. */
+ * the caller keeps them alive and unchanged for the life of the context.
+ * (ngg_create copies every matrix into an MFMA-operand-order layout of its own,
+ * which costs a second copy of the weights in HBM; tok_emb and the norm gains
+ * are read in place on every step.) */
 typedef struct {
   const void *attn_norm; /* [d_model] */
   const void *wq;        /* [n_heads*head_dim][d_model] */

@@ -35,10 +35,15 @@ struct ngg_ctx {
   int32_t *mlist = nullptr, *reps = nullptr, *ctx_rows = nullptr, *n_ctx = nullptr;
   int8_t *row_src = nullptr;
   void *kcache = nullptr, *vcache = nullptr, *kscr = nullptr, *vscr = nullptr;
-  float *h = nullptr, *part_o = nullptr, *part_ml = nullptr, *pmax_val = nullptr, *z = nullptr, *logits = nullptr;
+  float *h = nullptr, *hpart = nullptr, *part_o = nullptr, *part_ml = nullptr, *pmax_val = nullptr, *z = nullptr, *logits = nullptr;
   float *rope_cos = nullptr, *rope_sin = nullptr;
   int *pmax_idx = nullptr;
   void *xn = nullptr, *q = nullptr, *attn = nullptr, *act = nullptr;
+  // the library's own operand-order copies of every matrix it multiplies with
+  void *wtiled = nullptr;          // one allocation
+  struct LayerT { const void *wqkv, *wo, *wgu, *wdown; };
+  std::vector<LayerT> lt;
+  const void *unemb_t = nullptr;
   int32_t *res_host = nullptr;     // pinned
   // host state
   std::vector<int32_t> tokens;     // committed history mirror
@@ -128,16 +133,19 @@ ngg_status forward(ngg_ctx *c, int R, int C, int P, bool from_hist, int w, bool 
     span = (int)rup((size_t)(P + n_splits - 1) / n_splits, 32);
     n_splits = (P + span - 1) / span;
   }
+  const size_t part_stride = (size_t)c->Mcap * d.d_model;
+  const int ks_o = gemm_residual_splits(dt, d.d_model, dq), ks_down = gemm_residual_splits(dt, d.d_model, d.d_ffn);
+  int pending = 0;                                   // residual partials the next RMSNorm has to add
   for (int l = 0; l < d.n_layers; ++l) {
     const ngg_layer_weights &lw = c->layers[l];
     const size_t kv_layer = (size_t)l * d.n_kv_heads;
     char *kscr_l = (char *)c->kscr + kv_layer * c->Mcap * d.head_dim * c->esize;
     char *vscr_l = (char *)c->vscr + kv_layer * d.head_dim * c->Mcap * c->esize;
-    { ProfScope ps(c, NGG_PROF_NORM); launch_rmsnorm(dt, c->h, lw.attn_norm, c->xn, d.d_model, M, d.rms_eps, s); }
+    { ProfScope ps(c, NGG_PROF_NORM); launch_rmsnorm(dt, c->h, c->hpart, pending, part_stride, lw.attn_norm, c->xn, d.d_model, M, c->Mcap, d.rms_eps, s); }
     {
       ProfScope ps(c, NGG_PROF_GEMM_QKV);
       GemmArgs g{};
-      g.X = c->xn; g.ldx = d.d_model; g.W0 = lw.wq; g.W1 = lw.wk; g.W2 = lw.wv;
+      g.X = c->xn; g.W0 = c->lt[l].wqkv;
       g.M = M; g.N = dq + 2 * d.n_kv_heads * d.head_dim; g.K = d.d_model;
       g.q = c->q; g.kscr = kscr_l; g.vscr = vscr_l;
       g.H = d.n_heads; g.Hkv = d.n_kv_heads; g.hd = d.head_dim; g.Mcap = c->Mcap; g.C = C; g.P = P;
@@ -160,29 +168,32 @@ ngg_status forward(ngg_ctx *c, int R, int C, int P, bool from_hist, int w, bool 
     {
       ProfScope ps(c, NGG_PROF_GEMM_O);
       GemmArgs g{};
-      g.X = c->attn; g.ldx = dq; g.W0 = lw.wo; g.M = M; g.N = d.d_model; g.K = dq; g.h = c->h;
+      g.X = c->attn; g.W0 = c->lt[l].wo; g.M = M; g.N = d.d_model; g.K = dq;
+      g.hpart = c->hpart; g.KS = ks_o; g.Mcap = c->Mcap;
       launch_gemm(dt, EPI_RESIDUAL, g, s);
     }
-    { ProfScope ps(c, NGG_PROF_NORM); launch_rmsnorm(dt, c->h, lw.mlp_norm, c->xn, d.d_model, M, d.rms_eps, s); }
+    { ProfScope ps(c, NGG_PROF_NORM); launch_rmsnorm(dt, c->h, c->hpart, ks_o, part_stride, lw.mlp_norm, c->xn, d.d_model, M, c->Mcap, d.rms_eps, s); }
     {
       ProfScope ps(c, NGG_PROF_GEMM_GATEUP);
       GemmArgs g{};
-      g.X = c->xn; g.ldx = d.d_model; g.W0 = lw.w_gate; g.W1 = lw.w_up; g.M = M; g.N = d.d_ffn; g.K = d.d_model;
-      g.act = c->act;
+      g.X = c->xn; g.W0 = c->lt[l].wgu; g.M = M; g.N = d.d_ffn; g.K = d.d_model;
+      g.act = c->act; g.Mcap = c->Mcap;
       launch_gemm(dt, EPI_GATEUP, g, s);
     }
     {
       ProfScope ps(c, NGG_PROF_GEMM_DOWN);
       GemmArgs g{};
-      g.X = c->act; g.ldx = d.d_ffn; g.W0 = lw.w_down; g.M = M; g.N = d.d_model; g.K = d.d_ffn; g.h = c->h;
+      g.X = c->act; g.W0 = c->lt[l].wdown; g.M = M; g.N = d.d_model; g.K = d.d_ffn;
+      g.hpart = c->hpart; g.KS = ks_down; g.Mcap = c->Mcap;
       launch_gemm(dt, EPI_RESIDUAL, g, s);
     }
+    pending = ks_down;
   }
   if (unembed) {
-    { ProfScope ps(c, NGG_PROF_NORM); launch_rmsnorm(dt, c->h, c->w.final_norm, c->xn, d.d_model, M, d.rms_eps, s); }
+    { ProfScope ps(c, NGG_PROF_NORM); launch_rmsnorm(dt, c->h, c->hpart, pending, part_stride, c->w.final_norm, c->xn, d.d_model, M, c->Mcap, d.rms_eps, s); }
     ProfScope ps(c, NGG_PROF_GEMM_UNEMBED);
     GemmArgs g{};
-    g.X = c->xn; g.ldx = d.d_model; g.W0 = c->w.unemb; g.M = M; g.N = d.vocab; g.K = d.d_model;
+    g.X = c->xn; g.W0 = c->unemb_t; g.M = M; g.N = d.vocab; g.K = d.d_model;
     g.logits = want_logits ? c->logits : nullptr;
     g.pmax_val = c->pmax_val; g.pmax_idx = c->pmax_idx; g.Mcap = c->Mcap;
     launch_gemm(dt, EPI_UNEMBED, g, s);
@@ -202,15 +213,48 @@ ngg_status build_next1(ngg_ctx *c) {
   const ngg_model_desc &d = c->d;
   for (int x0 = 0; x0 < d.vocab; x0 += 64) {
     const int M = std::min(64, d.vocab - x0);
+    launch_pack_rows(d.dtype, (const char *)c->w.tok_emb + (size_t)x0 * d.d_model * c->esize, c->xn, d.d_model, M, c->Mcap,
+                     c->stream);
     GemmArgs g{};
-    g.X = (const char *)c->w.tok_emb + (size_t)x0 * d.d_model * c->esize;
-    g.ldx = d.d_model; g.W0 = c->w.unemb; g.M = M; g.N = d.vocab; g.K = d.d_model;
+    g.X = c->xn;
+    g.W0 = c->unemb_t; g.M = M; g.N = d.vocab; g.K = d.d_model;
     g.pmax_val = c->pmax_val; g.pmax_idx = c->pmax_idx; g.Mcap = c->Mcap;
     launch_gemm(d.dtype, EPI_UNEMBED, g, c->stream);
     launch_next1_finish(c->pmax_val, c->pmax_idx, c->unembed_tiles, c->Mcap, M, c->next1 + x0, c->stream);
   }
   NGG_HIP(c, hipGetLastError());
   NGG_HIP(c, hipStreamSynchronize(c->stream));
+  return NGG_OK;
+}
+
+// Copies every matrix the step multiplies with into operand order (one-off, at create).
+ngg_status tile_all_weights(ngg_ctx *c) {
+  const ngg_model_desc &d = c->d;
+  const size_t dq = (size_t)d.n_heads * d.head_dim, dkv = (size_t)d.n_kv_heads * d.head_dim;
+  const size_t e_qkv = (dq + 2 * dkv) * d.d_model, e_o = (size_t)d.d_model * dq, e_gu = (size_t)2 * d.d_ffn * d.d_model,
+               e_down = (size_t)d.d_model * d.d_ffn, e_layer = e_qkv + e_o + e_gu + e_down;
+  const size_t total = e_layer * d.n_layers + (size_t)d.vocab * d.d_model;
+  ngg_status st = dev_alloc(c, &c->wtiled, total * c->esize, false);
+  if (st != NGG_OK) return st;
+  char *base = (char *)c->wtiled;
+  c->lt.resize(d.n_layers);
+  for (int l = 0; l < d.n_layers; ++l) {
+    const ngg_layer_weights &lw = c->layers[l];
+    char *p = base + (size_t)l * e_layer * c->esize;
+    char *qkv = p, *o = qkv + e_qkv * c->esize, *gu = o + e_o * c->esize, *down = gu + e_gu * c->esize;
+    launch_tile_weights(d.dtype, lw.wq, qkv, (int)dq, d.d_model, 0, c->stream);
+    launch_tile_weights(d.dtype, lw.wk, qkv, (int)dkv, d.d_model, (int)dq, c->stream);
+    launch_tile_weights(d.dtype, lw.wv, qkv, (int)dkv, d.d_model, (int)(dq + dkv), c->stream);
+    launch_tile_weights(d.dtype, lw.wo, o, d.d_model, (int)dq, 0, c->stream);
+    launch_tile_weights(d.dtype, lw.w_gate, gu, d.d_ffn, d.d_model, 0, c->stream);
+    launch_tile_weights(d.dtype, lw.w_up, gu, d.d_ffn, d.d_model, d.d_ffn, c->stream);
+    launch_tile_weights(d.dtype, lw.w_down, down, d.d_model, d.d_ffn, 0, c->stream);
+    c->lt[l] = {qkv, o, gu, down};
+  }
+  char *ue = base + e_layer * d.n_layers * c->esize;
+  launch_tile_weights(d.dtype, c->w.unemb, ue, d.vocab, d.d_model, 0, c->stream);
+  c->unemb_t = ue;
+  NGG_HIP(c, hipGetLastError());
   return NGG_OK;
 }
 
@@ -228,7 +272,7 @@ ngg_status ngg_destroy(ngg_ctx *c) {
   if (!c) return NGG_EINVAL;
   (void)hipStreamSynchronize(c->stream);
   void *bufs[] = {c->hist, c->drafts, c->block_tok, c->res, c->next1, c->mlist, c->reps, c->ctx_rows, c->n_ctx,
-                  c->row_src, c->kcache, c->vcache, c->kscr, c->vscr, c->h, c->part_o, c->part_ml, c->pmax_val, c->z,
+                  c->row_src, c->hpart, c->wtiled, c->kcache, c->vcache, c->kscr, c->vscr, c->h, c->part_o, c->part_ml, c->pmax_val, c->z,
                   c->logits, c->rope_cos, c->rope_sin, c->pmax_idx, c->xn, c->q, c->attn, c->act};
   for (void *b : bufs)
     if (b) (void)hipFree(b);
@@ -250,7 +294,7 @@ ngg_status ngg_create(const ngg_model_desc *desc, const ngg_weights *weights, vo
     return fail(nullptr, NGG_EINVAL, "ngg_create: head_dim %d not in {32, 64, 128}", d.head_dim);
   if (d.d_model % 32 || d.d_ffn % 32 || (d.n_heads * d.head_dim) % 32)
     return fail(nullptr, NGG_EINVAL, "ngg_create: d_model, d_ffn and n_heads*head_dim must be multiples of 32");
-  if (d.vocab % 16) return fail(nullptr, NGG_EINVAL, "ngg_create: vocab must be a multiple of 16");
+  if (d.vocab % 32) return fail(nullptr, NGG_EINVAL, "ngg_create: vocab must be a multiple of 32");
   if (d.n_heads % d.n_kv_heads) return fail(nullptr, NGG_EINVAL, "ngg_create: n_heads must be a multiple of n_kv_heads");
   if (d.max_k < 1 || d.max_k > 32 || d.max_w < 0 || d.max_w > 32)
     return fail(nullptr, NGG_EINVAL, "ngg_create: need 1 <= max_k <= 32 and 0 <= max_w <= 32");
@@ -275,7 +319,7 @@ ngg_status ngg_create(const ngg_model_desc *desc, const ngg_weights *weights, vo
   c->Spad = (int)rup((size_t)d.max_seq + 1, 32);
   c->Mcap = (int)rup((size_t)std::max(d.max_k * (d.max_w + 1), kPrefillChunk), 32);
   c->max_splits = 32;
-  c->unembed_tiles = gemm_unembed_tiles(d.vocab);
+  c->unembed_tiles = d.vocab / 32;
 
   const size_t kv_elems = (size_t)d.n_layers * d.n_kv_heads * d.head_dim;
   const int dq = d.n_heads * d.head_dim;
@@ -296,10 +340,11 @@ ngg_status ngg_create(const ngg_model_desc *desc, const ngg_weights *weights, vo
   TRY(dev_alloc(c, &c->kscr, kv_elems * c->Mcap * c->esize, true));
   TRY(dev_alloc(c, &c->vscr, kv_elems * c->Mcap * c->esize, true));
   TRY(dev_alloc(c, &c->h, (size_t)c->Mcap * d.d_model * 4, true));
-  TRY(dev_alloc(c, &c->xn, (size_t)c->Mcap * d.d_model * c->esize, true));
+  TRY(dev_alloc(c, &c->hpart, (size_t)kMaxResidualSplits * c->Mcap * d.d_model * 4, true));
+  TRY(dev_alloc(c, &c->xn, act_elems(d.dtype, c->Mcap, d.d_model) * c->esize, true));
   TRY(dev_alloc(c, &c->q, (size_t)c->Mcap * dq * c->esize, true));
-  TRY(dev_alloc(c, &c->attn, (size_t)c->Mcap * dq * c->esize, true));
-  TRY(dev_alloc(c, &c->act, (size_t)c->Mcap * d.d_ffn * c->esize, true));
+  TRY(dev_alloc(c, &c->attn, act_elems(d.dtype, c->Mcap, dq) * c->esize, true));
+  TRY(dev_alloc(c, &c->act, act_elems(d.dtype, c->Mcap, d.d_ffn) * c->esize, true));
   TRY(dev_alloc(c, &c->part_o, (size_t)d.n_heads * (c->max_splits + 1) * c->Mcap * d.head_dim * 4, true));
   TRY(dev_alloc(c, &c->part_ml, (size_t)d.n_heads * (c->max_splits + 1) * c->Mcap * 2 * 4, true));
   TRY(dev_alloc(c, &c->pmax_val, (size_t)c->unembed_tiles * c->Mcap * 4, true));
@@ -325,6 +370,7 @@ ngg_status ngg_create(const ngg_model_desc *desc, const ngg_weights *weights, vo
     if (e == hipSuccess) e = hipMemcpy(c->rope_sin, sn.data(), sn.size() * 4, hipMemcpyHostToDevice);
     if (e != hipSuccess) st = fail(c, NGG_EHIP, "ngg_create: rotary table upload failed: %s", hipGetErrorString(e));
   }
+  if (st == NGG_OK) st = tile_all_weights(c);
   if (st == NGG_OK) st = build_next1(c);
   if (st != NGG_OK) {
     g_create_error = c->err;
@@ -386,7 +432,7 @@ ngg_status ngg_build_drafts(ngg_ctx *c, const ngg_draft_cfg *cfg, int32_t *draft
     DraftArgs a{};
     a.hist = c->hist; a.n = c->n; a.k = cfg->k; a.w = cfg->w; a.k_ctx_max = cfg->k_ctx_max; a.q_min = cfg->q_min; a.q_max = cfg->q_max;
     a.mlist = c->mlist; a.reps = c->reps; a.ctx_rows = c->ctx_rows; a.n_ctx = c->n_ctx;
-    a.tok_emb = c->w.tok_emb; a.unemb = c->w.unemb; a.d = c->d.d_model; a.vocab = c->d.vocab; a.z = c->z; a.next1 = c->next1;
+    a.tok_emb = c->w.tok_emb; a.unemb_t = c->unemb_t; a.d = c->d.d_model; a.vocab = c->d.vocab; a.z = c->z; a.next1 = c->next1;
     a.drafts = c->drafts; a.row_src = c->row_src;
     launch_build_drafts(c->d.dtype, a, c->stream);
   }
@@ -560,7 +606,7 @@ ngg_status ngg_debug_peek(ngg_ctx *c, const char *name, void *dst, int64_t cap, 
   else if (nm == "block_tok") { src = c->block_tok; sz = (size_t)c->Mcap * 4; }
   else if (nm == "kcache") { src = c->kcache; sz = kv; }
   else if (nm == "vcache") { src = c->vcache; sz = kv; }
-  else if (nm == "attn") { src = c->attn; sz = (size_t)c->Mcap * d.n_heads * d.head_dim * c->esize; }
+  else if (nm == "attn") { src = c->attn; sz = act_elems(d.dtype, c->Mcap, d.n_heads * d.head_dim) * c->esize; }
   else return fail(c, NGG_EINVAL, "ngg_debug_peek: unknown buffer '%s'", name);
   *bytes = (int64_t)sz;
   if (stride) *stride = c->Spad;

@@ -5,71 +5,119 @@
 // The block's own keys (row r, columns <= j) form one more "span" with a per-row causal mask.
 // Partial (max, sum, output) triples are merged by a second kernel in span order (deterministic).
 //
-// Layouts: keys [kv head][position][head_dim]; values transposed [kv head][head_dim][position],
-// so both stream as MFMA row operands with the contraction index contiguous per lane.
+// Layouts: keys [kv head][position][head_dim]; values in tiles of 32 positions, transposed inside
+// the tile, [kv head][position/32][head_dim][32]: a tile of 32 keys and its 32 values are two
+// contiguous regions, staged through LDS once per workgroup (double buffered) and read from there
+// by the four waves (one group of 16 queries each) as MFMA row operands.
 #include "ngg_internal.h"
 
 namespace ngg {
+
+// element (position, dim) of a value tensor stored in tiles of 32 positions: [position/32][dim][32]
+template <int HD>
+__host__ __device__ __forceinline__ size_t v_offset(int pos, int dim) {
+  return ((size_t)(pos / 32) * HD + dim) * 32 + pos % 32;
+}
 
 template <typename T, int HD>
 __global__ __launch_bounds__(256) void attn_partial_kernel(const AttnArgs a) {
   constexpr int DS = HD / 32;   // contraction slices of q.k
   constexpr int DF = HD / 16;   // 16-row groups of the transposed output
-  const int split = blockIdx.x, h = blockIdx.y;
+  constexpr int PAD = 16 / (int)sizeof(T);
+  constexpr int KROW = HD + PAD, VROW = 32 + PAD;           // padded LDS rows: conflict-free fragment reads
+  constexpr int TILE_PIECES = 32 * HD * (int)sizeof(T) / 16;   // 16-byte pieces of a 32-key K (or V) tile
+  constexpr int PPT = (TILE_PIECES + 255) / 256;            // pieces per thread
+  constexpr int KPPR = HD * (int)sizeof(T) / 16;            // pieces per key row
+  constexpr int VPPR = 32 * (int)sizeof(T) / 16;            // pieces per dim row
+  const int split = blockIdx.x, h = blockIdx.y, mg = blockIdx.z;
   const int hkv = h / (a.H / a.Hkv);
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int li = lane & 15, g = lane >> 4;
   const bool suffix = split == a.n_splits;
   const int M = a.M, C = a.C;
 
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  T *ks = reinterpret_cast<T *>(smem);                      // [2][32][KROW], rows in fragment order
+  T *vs = ks + 2 * 32 * KROW;                               // [2][HD][VROW]
+
   const T *kbase, *vbase;
-  size_t v_ld;
-  int key_begin, key_end;
+  int key_begin, key_end, last_tile_key;
   if (!suffix) {
     kbase = (const T *)a.kcache + (size_t)hkv * a.Spad * HD;
-    vbase = (const T *)a.vcache + (size_t)hkv * HD * a.Spad;
-    v_ld = a.Spad;
+    vbase = (const T *)a.vcache + (size_t)hkv * a.Spad * HD;
     key_begin = split * a.span;
     key_end = min(a.P, key_begin + a.span);
-  } else {
-    kbase = (const T *)a.kscr + (size_t)hkv * a.Mcap * HD;
-    vbase = (const T *)a.vscr + (size_t)hkv * HD * a.Mcap;
-    v_ld = a.Mcap;
-    key_begin = 0;
-    key_end = M;
+  } else {                                                  // the block's own keys: only the rows this group of
+    kbase = (const T *)a.kscr + (size_t)hkv * a.Mcap * HD;  // 64 queries lives in
+    vbase = (const T *)a.vscr + (size_t)hkv * a.Mcap * HD;
+    const int q_lo = mg * 64, q_hi = min(M, q_lo + 64) - 1;
+    key_begin = ((q_lo / C) * C) / 32 * 32;
+    key_end = min(M, (q_hi / C + 1) * C);
   }
+  const int n_tiles = (key_end - key_begin + 31) / 32;
+  last_tile_key = key_begin + (n_tiles - 1) * 32;
 
-  const int n_mfrag = (M + 15) / 16;
-  for (int mf = wave; mf < n_mfrag; mf += 4) {
-    const int m0 = mf * 16;
-    const int mq = min(m0 + li, M - 1);            // this lane's query (result column)
-    const int qrow = mq / C, qcol = mq - qrow * C;
-    Frag<T> Q[DS];
+  // staging: thread copies PPT pieces of the K tile and PPT pieces of the V tile
+  int k_src[PPT], k_dst[PPT], v_src[PPT], v_dst[PPT];
 #pragma unroll
-    for (int ds = 0; ds < DS; ++ds) Q[ds] = load_frag((const T *)a.q + ((size_t)h * a.Mcap + mq) * HD + ds * 32 + g * 8);
-
-    int kb = key_begin, ke = key_end;
-    if (suffix) {                                  // only the rows this group of 16 queries lives in
-      const int rlo = m0 / C, rhi = min(m0 + 15, M - 1) / C;
-      kb = (rlo * C) / 32 * 32;
-      ke = min(M, (rhi + 1) * C);
+  for (int i = 0; i < PPT; ++i) {
+    int p = tid + 256 * i;
+    p = p < TILE_PIECES ? p : TILE_PIECES - 1;              // duplicates write the same bytes
+    const int kk = p / KPPR, kc = p - kk * KPPR;            // key inside the tile, 16-byte column
+    k_src[i] = kk * HD + kc * PAD;
+    k_dst[i] = (((kk >> 2) & 1) * 16 + (kk >> 3) * 4 + (kk & 3)) * KROW + kc * PAD;   // key 8a+4f+b -> row 16f+4a+b
+    const int dd = p / VPPR, vc = p - dd * VPPR;
+    v_src[i] = dd * 32 + vc * PAD;
+    v_dst[i] = dd * VROW + vc * PAD;
+  }
+  u32x4 kst[PPT], vst[PPT];
+  auto stage_load = [&](int t) {
+    const int k0 = min(key_begin + t * 32, last_tile_key);  // clamped: loads are unconditional
+#pragma unroll
+    for (int i = 0; i < PPT; ++i) {
+      kst[i] = *reinterpret_cast<const u32x4 *>(kbase + (size_t)k0 * HD + k_src[i]);
+      vst[i] = *reinterpret_cast<const u32x4 *>(vbase + (size_t)k0 * HD + v_src[i]);
     }
-    float mrun = kNegBig, lrun = 0.0f;
-    f32x4 O[DF];
+  };
+  auto stage_store = [&](int buf) {
 #pragma unroll
-    for (int df = 0; df < DF; ++df) O[df] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < PPT; ++i) {
+      *reinterpret_cast<u32x4 *>(ks + buf * 32 * KROW + k_dst[i]) = kst[i];
+      *reinterpret_cast<u32x4 *>(vs + buf * HD * VROW + v_dst[i]) = vst[i];
+    }
+  };
 
-    for (int k0 = kb; k0 < ke; k0 += 32) {
-      // scores, transposed: rows = keys, columns = queries.  Group f's row i is key
+  const int mf = mg * 4 + wave;                             // this wave's group of 16 queries
+  const bool active = mf * 16 < M;
+  const int m0 = mf * 16;
+  const int mq = min(m0 + li, M - 1);                       // this lane's query (result column)
+  const int qrow = mq / C, qcol = mq - qrow * C;
+  Frag<T> Q[DS];
+#pragma unroll
+  for (int ds = 0; ds < DS; ++ds) Q[ds] = load_frag((const T *)a.q + ((size_t)h * a.Mcap + mq) * HD + ds * 32 + g * 8);
+  float mrun = kNegBig, lrun = 0.0f;
+  f32x4 O[DF];
+#pragma unroll
+  for (int df = 0; df < DF; ++df) O[df] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  if (n_tiles > 0) stage_load(0);
+  for (int t = 0; t < n_tiles; ++t) {
+    const int buf = t & 1;
+    stage_store(buf);
+    __syncthreads();
+    stage_load(t + 1);
+    if (active) {
+      const int k0 = key_begin + t * 32;
+      const T *kt = ks + buf * 32 * KROW + li * KROW + g * 8;
+      const T *vt = vs + buf * HD * VROW + li * VROW + g * 8;
+      // scores, transposed: rows = keys, columns = queries.  Fragment f's row i is key
       // k0 + 8*(i/4) + 4f + (i%4), so this lane ends up with the 8 consecutive keys k0 + 8g .. +8.
       f32x4 S[2];
 #pragma unroll
       for (int f = 0; f < 2; ++f) {
         S[f] = f32x4{0.f, 0.f, 0.f, 0.f};
-        const int key = k0 + 8 * (li >> 2) + 4 * f + (li & 3);
-        const T *kp = kbase + (size_t)key * HD + g * 8;
 #pragma unroll
-        for (int ds = 0; ds < DS; ++ds) mma(S[f], load_frag(kp + ds * 32), Q[ds]);
+        for (int ds = 0; ds < DS; ++ds) mma(S[f], load_frag(kt + f * 16 * KROW + ds * 32), Q[ds]);
       }
       float sv[8];
       bool vis[8];
@@ -106,23 +154,22 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const AttnArgs a) {
       for (int df = 0; df < DF; ++df) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) O[df][r] *= alpha;
-        const T *vp = vbase + (size_t)(df * 16 + li) * v_ld + k0 + 8 * g;
-        mma(O[df], load_frag(vp), Pf);
+        mma(O[df], load_frag(vt + df * 16 * VROW), Pf);
       }
     }
+  }
 
-    const int m = m0 + li;
-    if (m < M) {
-      const size_t slot = ((size_t)h * (a.n_splits + 1) + split) * a.Mcap + m;
+  const int m = m0 + li;
+  if (active && m < M) {
+    const size_t slot = ((size_t)h * (a.n_splits + 1) + split) * a.Mcap + m;
 #pragma unroll
-      for (int df = 0; df < DF; ++df) {
-        float4 v{O[df][0], O[df][1], O[df][2], O[df][3]};
-        *reinterpret_cast<float4 *>(a.part_o + slot * HD + df * 16 + 4 * g) = v;
-      }
-      if (g == 0) {
-        a.part_ml[slot * 2 + 0] = mrun;
-        a.part_ml[slot * 2 + 1] = lrun;
-      }
+    for (int df = 0; df < DF; ++df) {
+      float4 v{O[df][0], O[df][1], O[df][2], O[df][3]};
+      *reinterpret_cast<float4 *>(a.part_o + slot * HD + df * 16 + 4 * g) = v;
+    }
+    if (g == 0) {
+      a.part_ml[slot * 2 + 0] = mrun;
+      a.part_ml[slot * 2 + 1] = lrun;
     }
   }
 }
@@ -142,12 +189,14 @@ __global__ __launch_bounds__(HD) void attn_merge_kernel(const AttnArgs a) {
     l += a.part_ml[slot * 2 + 1] * wgt;
     o += a.part_o[slot * HD + d] * wgt;
   }
-  ((T *)a.out)[(size_t)m * (a.H * HD) + h * HD + d] = from_f32<T>(o / l);
+  ((T *)a.out)[act_offset<T>(m, h * HD + d, a.Mcap)] = from_f32<T>(o / l);
 }
 
 template <typename T, int HD>
 static void launch_hd(const AttnArgs &a, hipStream_t s) {
-  hipLaunchKernelGGL((attn_partial_kernel<T, HD>), dim3(a.n_splits + 1, a.H), dim3(256), 0, s, a);
+  constexpr int PAD = 16 / (int)sizeof(T);
+  const size_t lds = (size_t)2 * (32 * (HD + PAD) + HD * (32 + PAD)) * sizeof(T);
+  hipLaunchKernelGGL((attn_partial_kernel<T, HD>), dim3(a.n_splits + 1, a.H, (a.M + 63) / 64), dim3(256), lds, s, a);
   hipLaunchKernelGGL((attn_merge_kernel<T, HD>), dim3(a.M, a.H), dim3(HD), 0, s, a);
 }
 

@@ -1,108 +1,165 @@
 // Skinny GEMM  Y[M x N] = X[M x K] . W[N x K]^T  for the k*(w+1) block rows of a verify call
 // (Section 3: a model call on a (k, w+1) block is meant to stay memory-bound, so the kernel is
-// built around streaming W once).  W rows are the MFMA "row" operand, X rows the "column"
-// operand; each workgroup owns FN groups of 16 output features, its waves split the contraction
-// index and reduce through LDS in a fixed order (deterministic).  Epilogues fuse rotary
-// embedding + KV-scratch write, SwiGLU, the residual add and the per-position argmax partials.
+// built around streaming W exactly once at HBM speed).
+//
+// W rows are the MFMA "row" operand.  The library keeps its own copy of every weight matrix in
+// operand order (16 rows x 32 contraction elements per 1 KB block, lane-major), so one load
+// instruction of a wave reads 1 KB of contiguous memory, a wave streams one contiguous region, and
+// the data goes from global memory straight into MFMA registers, prefetched RING steps ahead.  X rows are the "column" operand: the workgroup stages X[:, chunk] in LDS (double
+// buffered, rows padded by 16 bytes so the 16 lanes of a quarter-wave hit distinct banks) and all
+// waves read their fragments from there.  A workgroup has 4 waves arranged WN x WK: WN waves own
+// different pairs of 16-row groups of W, WK waves split the steps of a chunk and are summed through
+// LDS in a fixed order.  gridDim.y = KS splits the contraction across workgroups; only the
+// residual epilogue supports it: every split stores its own fp32 partial, and the RMSNorm kernel
+// that follows adds them in split order (deterministic, no atomics).
+//
+// Epilogues: rotary embedding + KV-scratch write (q, k, v), SwiGLU (gate, up), residual partial,
+// and per-position argmax partials for the greedy choice (output embedding).
 #include "ngg_internal.h"
 
 namespace ngg {
 
-template <typename T, int FN, int FM>
-struct Tile {
-  Frag<T> a[FN];
-  Frag<T> b[FM];
-};
+template <typename T, int EPI, int FM, int WN, int WK, int RING>
+__global__ __launch_bounds__(256) void gemm_skinny_kernel(const GemmArgs a) {
+  static_assert(WN * WK == 4, "four waves per workgroup");
+  constexpr int FN = 2;
+  constexpr int KC = KChunk<T>::value;
+  constexpr int SPC = KC / 32;               // steps per chunk
+  constexpr int SPW = SPC / WK;              // steps per wave per chunk
+  constexpr int PAD = 16 / (int)sizeof(T);
+  constexpr int LDX = KC + PAD;              // LDS row stride in elements
+  constexpr int ROWS = 16 * FM;
+  constexpr int PIECES = ROWS * KC * (int)sizeof(T) / 16 / 256;   // 16-byte pieces per thread per chunk
+  constexpr int PPR = KC * (int)sizeof(T) / 16;                   // pieces per row
+  constexpr int UC = (RING % SPW == 0) ? RING / SPW : 1;          // chunks per unrolled iteration
+  static_assert((UC * SPW) % RING == 0, "ring slots must be static after unrolling");
+  static_assert(PIECES >= 1, "chunk too small for 256 threads");
 
-template <typename T, int EPI, int FN, int FM, int WAVES>
-__global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const GemmArgs a) {
-  const int tile = blockIdx.x;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  T *xs = reinterpret_cast<T *>(smem);       // [2][ROWS][LDX]
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int li = lane & 15, g = lane >> 4;
+  const int wn = wave % WN, wk = wave / WN;
   const int K = a.K, M = a.M;
+  const int n_groups = a.n_groups;
+  int group = blockIdx.x * WN + wn;
+  const bool group_live = group < n_groups;
+  if (!group_live) group = n_groups - 1;     // idle waves still help staging X and hit every barrier
 
-  // ---- which 16-row groups of W this workgroup owns ---------------------------------------------
-  const T *wrow[FN];   // this lane's row of each group, offset to its 8-element slice
-  int nbase[FN];       // logical output feature of each group's first row
-  int head = 0, sub = 0, kind = 0;   // EPI_QKV: kind 0 = q, 1 = k, 2 = v
+  // ---- the two 16-row groups of W this wave owns (W is stored in operand order: see tile_weights) --
+  const int n_steps = K / 32;
+  const T *wblk[FN];                         // this lane's slice of the group's first 32-step block
+  int nbase[FN];
+  int head = 0, kind = 0;                    // EPI_QKV: kind 0 = q, 1 = k, 2 = v
   if constexpr (EPI == EPI_QKV) {
-    static_assert(FN == 2, "rotary pairs need two groups");
-    const int tph = a.hd / 32;                       // tiles per head
-    head = tile / tph;
-    sub = tile - head * tph;
-    const T *base;
-    int hrow;                                        // first row of the head inside its matrix
-    if (head < a.H) { kind = 0; base = (const T *)a.W0; hrow = head * a.hd; }
-    else if (head < a.H + a.Hkv) { kind = 1; base = (const T *)a.W1; hrow = (head - a.H) * a.hd; head -= a.H; }
-    else { kind = 2; base = (const T *)a.W2; hrow = (head - a.H - a.Hkv) * a.hd; head -= a.H + a.Hkv; }
+    const int tph = a.hd / 32;               // pair groups per head
+    const int hh = group / tph;              // head index over [q heads | k heads | v heads]
+    const int sub = group - hh * tph;
+    kind = hh < a.H ? 0 : (hh < a.H + a.Hkv ? 1 : 2);
+    head = kind == 0 ? hh : (kind == 1 ? hh - a.H : hh - a.H - a.Hkv);
 #pragma unroll
     for (int f = 0; f < FN; ++f) {
-      nbase[f] = f * (a.hd / 2) + sub * 16;          // element index inside the head
-      wrow[f] = base + (size_t)(hrow + nbase[f] + li) * K + g * 8;
+      nbase[f] = f * (a.hd / 2) + sub * 16;  // element index inside the head: (i, i + hd/2) pairs
+      wblk[f] = tiled_block((const T *)a.W0, (hh * a.hd + nbase[f]) / 16, n_steps, lane);
     }
   } else if constexpr (EPI == EPI_GATEUP) {
-    static_assert(FN == 2, "gate and up rows travel together");
-    nbase[0] = nbase[1] = tile * 16;
-    wrow[0] = (const T *)a.W0 + (size_t)(tile * 16 + li) * K + g * 8;
-    wrow[1] = (const T *)a.W1 + (size_t)(tile * 16 + li) * K + g * 8;
+    nbase[0] = nbase[1] = group * 16;        // gate rows [0, N), up rows [N, 2N) of one tiled matrix
+    wblk[0] = tiled_block((const T *)a.W0, group, n_steps, lane);
+    wblk[1] = tiled_block((const T *)a.W0, a.N / 16 + group, n_steps, lane);
   } else {
 #pragma unroll
     for (int f = 0; f < FN; ++f) {
-      nbase[f] = (tile * FN + f) * 16;
-      wrow[f] = (const T *)a.W0 + (size_t)(nbase[f] + li) * K + g * 8;
+      nbase[f] = (group * FN + f) * 16;
+      wblk[f] = tiled_block((const T *)a.W0, group * FN + f, n_steps, lane);
     }
   }
 
-  const int steps = K / 32;
-  const int s0 = (int)(((long)steps * wave) / WAVES);
-  const int s1 = (int)(((long)steps * (wave + 1)) / WAVES);
+  // ---- this workgroup's range of chunks -----------------------------------------------------------
+  const int n_chunks = (n_steps + SPC - 1) / SPC;
+  const int KS = gridDim.y, ks = blockIdx.y;
+  const int c0 = (int)(((long)n_chunks * ks) / KS), c1 = (int)(((long)n_chunks * (ks + 1)) / KS);
 
-  extern __shared__ float red[];   // [(WAVES-1)][FN*FM*4][64]
-
-  for (int m0 = 0; m0 < M; m0 += 16 * FM) {
-    const T *xrow[FM];
+  for (int m0 = 0; m0 < M; m0 += ROWS) {
+    // X staging: piece p = tid + 256*i covers row p / PPR, 16 bytes at column piece p % PPR
+    const T *xsrc[PIECES];
+    int xdst[PIECES];
 #pragma unroll
-    for (int fm = 0; fm < FM; ++fm) {
-      int m = m0 + fm * 16 + li;
-      m = m < M ? m : M - 1;                         // rows past M repeat the last one; never stored
-      xrow[fm] = (const T *)a.X + (size_t)m * a.ldx + g * 8;
+    for (int i = 0; i < PIECES; ++i) {
+      const int p = tid + 256 * i;
+      const int r = p / PPR, cp = p - r * PPR;
+      int m = m0 + r;
+      m = m < M ? m : M - 1;                 // rows past M repeat the last one; never stored
+      xsrc[i] = (const T *)a.X + (size_t)m * KC + cp * PAD;     // chunk c adds c * Mcap * KC
+      xdst[i] = r * LDX + cp * PAD;
     }
+    // Every global load below is unconditional (addresses are clamped into valid memory instead of
+    // being guarded): with straight-line loads the compiler can wait for exactly the load it needs
+    // (s_waitcnt vmcnt(n)) instead of draining the whole prefetch ring at every chunk boundary.
+    u32x4 stage[PIECES];
+    auto stage_load = [&](int c) {
+      const int cl = c < n_chunks ? c : n_chunks - 1;      // activation buffers are padded to whole chunks
+#pragma unroll
+      for (int i = 0; i < PIECES; ++i) stage[i] = *reinterpret_cast<const u32x4 *>(xsrc[i] + (size_t)cl * a.Mcap * KC);
+    };
+    auto stage_store = [&](int buf) {
+#pragma unroll
+      for (int i = 0; i < PIECES; ++i) *reinterpret_cast<u32x4 *>(xs + (size_t)buf * ROWS * LDX + xdst[i]) = stage[i];
+    };
+
     f32x4 acc[FN][FM];
 #pragma unroll
     for (int f = 0; f < FN; ++f)
 #pragma unroll
       for (int fm = 0; fm < FM; ++fm) acc[f][fm] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    auto load_tile = [&](Tile<T, FN, FM> &t, int s) {
+    // wave-step t is global step (c0 + t/SPW)*SPC + wk + WK*(t % SPW); steps past the end are clamped
+    // to the last one (loaded, never multiplied)
+    Frag<T> ring[RING][FN];
+    auto load_w = [&](Frag<T> (&slot)[FN], int t) {
+      int s = (c0 + t / SPW) * SPC + wk + WK * (t % SPW);
+      s = s < n_steps ? s : n_steps - 1;
 #pragma unroll
-      for (int f = 0; f < FN; ++f) t.a[f] = load_frag(wrow[f] + (size_t)s * 32);
-#pragma unroll
-      for (int fm = 0; fm < FM; ++fm) t.b[fm] = load_frag(xrow[fm] + (size_t)s * 32);
+      for (int f = 0; f < FN; ++f) slot[f] = load_frag_tiled(wblk[f] + (size_t)s * 512);
     };
-    auto mma_tile = [&](const Tile<T, FN, FM> &t) {
 #pragma unroll
-      for (int f = 0; f < FN; ++f)
-#pragma unroll
-        for (int fm = 0; fm < FM; ++fm) mma(acc[f][fm], t.a[f], t.b[fm]);
-    };
+    for (int u = 0; u < RING; ++u) load_w(ring[u], u);
+    stage_load(c0);
 
-    Tile<T, FN, FM> t0, t1;
-    int s = s0;
-    if (s < s1) load_tile(t0, s);
-    while (s < s1) {
-      if (s + 1 < s1) load_tile(t1, s + 1);
-      mma_tile(t0);
-      ++s;
-      if (s >= s1) break;
-      if (s + 1 < s1) load_tile(t0, s + 1);
-      mma_tile(t1);
-      ++s;
+    const int n_iter = (c1 - c0 + UC - 1) / UC * UC;       // whole unrolled groups; extra chunks only load
+    for (int ci = 0; ci < n_iter; ci += UC) {
+#pragma unroll
+      for (int cc = 0; cc < UC; ++cc) {
+        const int ch = c0 + ci + cc;
+        const int buf = (ci + cc) & 1;
+        stage_store(buf);
+        __syncthreads();
+        stage_load(ch + 1);
+        const T *xb = xs + (size_t)buf * ROWS * LDX + li * LDX + g * 8;
+#pragma unroll
+        for (int i = 0; i < SPW; ++i) {
+          const int slot = (cc * SPW + i) % RING;        // constant after unrolling
+          const int ls = wk + WK * i;                    // step inside the chunk
+          if (ch < c1 && ch * SPC + ls < n_steps) {      // uniform per wave; no global load inside
+            Frag<T> xb_f[FM];
+#pragma unroll
+            for (int fm = 0; fm < FM; ++fm) xb_f[fm] = load_frag(xb + fm * 16 * LDX + ls * 32);
+#pragma unroll
+            for (int f = 0; f < FN; ++f)
+#pragma unroll
+              for (int fm = 0; fm < FM; ++fm) mma(acc[f][fm], ring[slot][f], xb_f[fm]);
+          }
+          load_w(ring[slot], (ci + cc) * SPW + i + RING);
+        }
+      }
     }
+    __syncthreads();                                     // everyone is done with xs
 
-    // ---- reduce the waves' partial sums: wave 0 adds waves 1 .. WAVES-1 in that order ----------
-    if constexpr (WAVES > 1) {
-      if (wave > 0) {
-        float *dst = red + (size_t)(wave - 1) * (FN * FM * 4 * 64);
+    // ---- sum the WK waves that share a wn: wave (wn, 0) adds (wn, 1) .. (wn, WK-1) in that order ---
+    if constexpr (WK > 1) {
+      float *red = reinterpret_cast<float *>(smem);      // [(WK-1)][WN][FN*FM*4][64]
+      if (wk > 0) {
+        float *dst = red + (size_t)((wk - 1) * WN + wn) * (FN * FM * 4 * 64);
 #pragma unroll
         for (int f = 0; f < FN; ++f)
 #pragma unroll
@@ -111,9 +168,9 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const GemmArgs 
             for (int r = 0; r < 4; ++r) dst[((f * FM + fm) * 4 + r) * 64 + lane] = acc[f][fm][r];
       }
       __syncthreads();
-      if (wave == 0) {
-        for (int wv = 1; wv < WAVES; ++wv) {
-          const float *src = red + (size_t)(wv - 1) * (FN * FM * 4 * 64);
+      if (wk == 0) {
+        for (int o = 1; o < WK; ++o) {
+          const float *src = red + (size_t)((o - 1) * WN + wn) * (FN * FM * 4 * 64);
 #pragma unroll
           for (int f = 0; f < FN; ++f)
 #pragma unroll
@@ -124,30 +181,28 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const GemmArgs 
       }
     }
 
-    // ---- epilogue (wave 0): lane holds, per group f and column block fm, column m = m0+fm*16+li
-    //      and output features nbase[f] + 4g .. +4 -------------------------------------------------
-    if (wave == 0) {
+    // ---- epilogue, waves (wn, 0): lane holds, per group f and column block fm, column
+    //      m = m0 + fm*16 + li and output features nbase[f] + 4g .. +4 -----------------------------------
+    if (wk == 0 && group_live) {
 #pragma unroll
       for (int fm = 0; fm < FM; ++fm) {
         const int m = m0 + fm * 16 + li;
         const bool live = m < M;
         if constexpr (EPI == EPI_RESIDUAL) {
           if (live) {
+            float *dst = a.hpart + ((size_t)ks * a.Mcap + m) * a.N;
 #pragma unroll
-            for (int f = 0; f < FN; ++f) {
-              float4 *p = reinterpret_cast<float4 *>(a.h + (size_t)m * a.N + nbase[f] + 4 * g);
-              float4 v = *p;
-              v.x += acc[f][fm][0]; v.y += acc[f][fm][1]; v.z += acc[f][fm][2]; v.w += acc[f][fm][3];
-              *p = v;
-            }
+            for (int f = 0; f < FN; ++f)
+              *reinterpret_cast<float4 *>(dst + nbase[f] + 4 * g) =
+                  float4{acc[f][fm][0], acc[f][fm][1], acc[f][fm][2], acc[f][fm][3]};
           }
         } else if constexpr (EPI == EPI_GATEUP) {
           if (live) {
-            T *p = (T *)a.act + (size_t)m * a.N + nbase[0] + 4 * g;
+            T *p = (T *)a.act + act_offset<T>(m, nbase[0] + 4 * g, a.Mcap);   // 4 features stay inside one chunk
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
               const float gt = acc[0][fm][r], up = acc[1][fm][r];
-              const float sg = gt / (1.0f + fast_exp<float>(-gt));       // silu(gate)
+              const float sg = gt / (1.0f + expf(-gt));              // silu(gate)
               p[r] = from_f32<T>(sg * up);
             }
           }
@@ -165,24 +220,19 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const GemmArgs 
                 lo[r] = x1 * cs[r] - x2 * sn[r];
                 hi[r] = x2 * cs[r] + x1 * sn[r];
               }
-            } else {
-#pragma unroll
-              for (int r = 0; r < 4; ++r) { lo[r] = acc[0][fm][r]; hi[r] = acc[1][fm][r]; }
-            }
-            if (kind < 2) {
               T *dst = (kind == 0 ? (T *)a.q : (T *)a.kscr) + ((size_t)head * a.Mcap + m) * a.hd + nbase[0] + 4 * g;
 #pragma unroll
               for (int r = 0; r < 4; ++r) { dst[r] = from_f32<T>(lo[r]); dst[half + r] = from_f32<T>(hi[r]); }
-            } else {                                         // v is kept transposed: [dim][m]
-              T *dst = (T *)a.vscr + ((size_t)head * a.hd + nbase[0] + 4 * g) * a.Mcap + m;
+            } else {                                         // v: tiles of 32 block positions, [m/32][dim][32]
+              T *dst = (T *)a.vscr + (size_t)head * a.Mcap * a.hd + (size_t)(m / 32) * a.hd * 32 + (m % 32);
 #pragma unroll
               for (int r = 0; r < 4; ++r) {
-                dst[(size_t)r * a.Mcap] = from_f32<T>(lo[r]);
-                dst[(size_t)(half + r) * a.Mcap] = from_f32<T>(hi[r]);
+                dst[(size_t)(nbase[0] + 4 * g + r) * 32] = from_f32<T>(acc[0][fm][r]);
+                dst[(size_t)(nbase[0] + 4 * g + half + r) * 32] = from_f32<T>(acc[1][fm][r]);
               }
             }
           }
-        } else {   // EPI_UNEMBED: optional logits, and this tile's best (value, id) per column
+        } else {   // EPI_UNEMBED: optional logits, and this wave's best (value, id) per column
           float bv = kNegBig;
           int bi = 0x7fffffff;
 #pragma unroll
@@ -201,40 +251,72 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const GemmArgs 
             if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
           }
           if (live && g == 0) {
-            a.pmax_val[(size_t)tile * a.Mcap + m] = bv;
-            a.pmax_idx[(size_t)tile * a.Mcap + m] = bi;
+            a.pmax_val[(size_t)group * a.Mcap + m] = bv;
+            a.pmax_idx[(size_t)group * a.Mcap + m] = bi;
           }
         }
       }
     }
-    if constexpr (WAVES > 1) __syncthreads();          // LDS is reused by the next column block
+    __syncthreads();                                       // LDS is reused by the next column block
   }
 }
 
-template <typename T, int EPI, int FN, int FM, int WAVES>
-static void launch_one(const GemmArgs &a, int tiles, hipStream_t s) {
-  const size_t lds = (size_t)(WAVES - 1) * FN * FM * 4 * 64 * sizeof(float);
-  hipLaunchKernelGGL((gemm_skinny_kernel<T, EPI, FN, FM, WAVES>), dim3(tiles), dim3(WAVES * 64), lds, s, a);
+template <typename T, int EPI, int FM, int WN, int WK, int RING>
+void launch_gemm_cfg(const GemmArgs &a, int KS, hipStream_t s) {
+  constexpr int KC = KChunk<T>::value;
+  constexpr int PAD = 16 / (int)sizeof(T);
+  size_t lds = (size_t)2 * 16 * FM * (KC + PAD) * sizeof(T);
+  const size_t red = (size_t)(WK - 1) * WN * 2 * FM * 4 * 64 * sizeof(float);
+  if (red > lds) lds = red;
+  const int blocks = (a.n_groups + WN - 1) / WN;
+  hipLaunchKernelGGL((gemm_skinny_kernel<T, EPI, FM, WN, WK, RING>), dim3(blocks, KS), dim3(256), lds, s, a);
 }
 
-template <typename T, int EPI, int FN, int WAVES>
-static void launch_fm(const GemmArgs &a, int tiles, hipStream_t s) {
-  if (a.M <= 16) launch_one<T, EPI, FN, 1, WAVES>(a, tiles, s);
-  else if (a.M <= 32) launch_one<T, EPI, FN, 2, WAVES>(a, tiles, s);
-  else launch_one<T, EPI, FN, 4, WAVES>(a, tiles, s);
-}
-
-int gemm_unembed_tiles(int N) { return N / 32 * 32 == N ? N / 32 : N / 16; }
-
-template <typename T>
-static void launch_t(int epi, const GemmArgs &a, hipStream_t s) {
+// pair groups (2 x 16 output features) of each epilogue
+int gemm_groups(int epi, const GemmArgs &a) {
   switch (epi) {
-    case EPI_QKV: launch_fm<T, EPI_QKV, 2, 4>(a, (a.H + 2 * a.Hkv) * (a.hd / 32), s); break;
-    case EPI_GATEUP: launch_fm<T, EPI_GATEUP, 2, 4>(a, a.N / 16, s); break;
-    case EPI_RESIDUAL: launch_fm<T, EPI_RESIDUAL, 1, 8>(a, a.N / 16, s); break;
+    case EPI_QKV: return (a.H + 2 * a.Hkv) * (a.hd / 32);
+    case EPI_GATEUP: return a.N / 16;
+    default: return a.N / 32;
+  }
+}
+
+template <typename T, int EPI, int WN, int WK, int RING>
+static void launch_fm(const GemmArgs &a, int KS, hipStream_t s) {
+  if (a.M <= 16) launch_gemm_cfg<T, EPI, 1, WN, WK, RING>(a, KS, s);
+  else if (a.M <= 32) launch_gemm_cfg<T, EPI, 2, WN, WK, RING>(a, KS, s);
+  else launch_gemm_cfg<T, EPI, 4, WN, WK, RING>(a, KS, s);
+}
+
+// Split of the contraction across workgroups for the residual GEMMs (two waves share a pair of row
+// groups, WN = 2): about one workgroup per CU, as long as each split keeps at least 2 chunks.
+int gemm_residual_splits(int dtype, int N, int K) {
+  const int kc = dtype == 1 ? KChunk<bf16_t>::value : KChunk<float>::value;
+  const int n_chunks = (K + kc - 1) / kc;
+  const int blocks = (N / 32 + 1) / 2;
+  int ks = (256 + blocks - 1) / blocks;
+  ks = ks > kMaxResidualSplits ? kMaxResidualSplits : ks;
+  while (ks > 1 && n_chunks / ks < 2) --ks;
+  return ks < 1 ? 1 : ks;
+}
+
+// Workgroup shapes measured on MI355X at the 7B shapes (M = 60 and M = 1): wide tiles (WN = 4) where
+// there are enough row groups to give every CU a workgroup, otherwise two waves per pair of groups.
+template <typename T>
+static void launch_t(int epi, const GemmArgs &a_in, hipStream_t s) {
+  GemmArgs a = a_in;
+  a.n_groups = gemm_groups(epi, a);
+  const bool wide = a.n_groups >= 4 * 200;
+  switch (epi) {
+    case EPI_QKV: launch_fm<T, EPI_QKV, 2, 2, 4>(a, 1, s); break;
+    case EPI_GATEUP:
+      if (wide && a.M > 16) launch_fm<T, EPI_GATEUP, 4, 1, 4>(a, 1, s);
+      else launch_fm<T, EPI_GATEUP, 2, 2, 4>(a, 1, s);
+      break;
+    case EPI_RESIDUAL: launch_fm<T, EPI_RESIDUAL, 2, 2, 4>(a, a.KS, s); break;
     default:
-      if (a.N % 32 == 0) launch_fm<T, EPI_UNEMBED, 2, 4>(a, a.N / 32, s);
-      else launch_fm<T, EPI_UNEMBED, 1, 4>(a, a.N / 16, s);
+      if (wide) launch_fm<T, EPI_UNEMBED, 4, 1, 8>(a, 1, s);
+      else launch_fm<T, EPI_UNEMBED, 2, 2, 4>(a, 1, s);
   }
 }
 

@@ -10,6 +10,7 @@ namespace ngg {
 typedef __bf16 bf16_t;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr float kNegBig = -1.0e30f;   // "minus infinity" that stays finite under subtraction
 
@@ -38,6 +39,48 @@ __device__ __forceinline__ Frag<float> load_frag(const float *p) {
   f.v[4] = b.x; f.v[5] = b.y; f.v[6] = b.z; f.v[7] = b.w;
   return f;
 }
+// Operand-order ("tiled") weight storage.  A matrix [N][K] is cut into blocks of 16 rows x 32
+// contraction elements, stored group-major: block (n/16, k/32) starts at element
+// ((n/16) * (K/32) + k/32) * 512.  Inside a bf16 block lane l = ((k%32)/8)*16 + n%16 owns elements
+// l*8 .. l*8+8 (its fragment); an fp32 block is two 1 KB halves, half h holding elements 4h .. 4h+4
+// of every lane's fragment at l*4.  A wave's load instruction therefore reads 1 KB contiguously.
+__host__ __device__ __forceinline__ size_t tiled_offset(int n, int k, int K, int elem_size) {
+  const size_t block = ((size_t)(n / 16) * (K / 32) + k / 32) * 512;
+  const int l = ((k % 32) / 8) * 16 + n % 16, e = k % 8;
+  return block + (elem_size == 2 ? l * 8 + e : (e / 4) * 256 + l * 4 + e % 4);
+}
+template <typename T>
+__device__ __forceinline__ const T *tiled_block(const T *w, int group16, int n_steps, int lane) {
+  return w + (size_t)group16 * n_steps * 512 + lane * (sizeof(T) == 2 ? 8 : 4);
+}
+__device__ __forceinline__ Frag<bf16_t> load_frag_tiled(const bf16_t *p) { return load_frag(p); }
+__device__ __forceinline__ Frag<float> load_frag_tiled(const float *p) {
+  Frag<float> f;
+  const float4 a = *reinterpret_cast<const float4 *>(p);
+  const float4 b = *reinterpret_cast<const float4 *>(p + 256);
+  f.v[0] = a.x; f.v[1] = a.y; f.v[2] = a.z; f.v[3] = a.w;
+  f.v[4] = b.x; f.v[5] = b.y; f.v[6] = b.z; f.v[7] = b.w;
+  return f;
+}
+
+// Activation matrices that feed a GEMM (normalised hidden state, attention output, SwiGLU output)
+// are stored chunk-major: [K / KC][Mcap][KC] with KC = 256 (bf16) or 128 (fp32) contraction
+// elements, so that the slice of all block rows a workgroup stages per step of the GEMM is one
+// contiguous region spread over every L2 channel (row-major rows lie a multiple of the channel
+// interleave apart, which made all workgroups of a die hit the same few channels at once).
+template <typename T> struct KChunk;
+template <> struct KChunk<bf16_t> { static constexpr int value = 256; };
+template <> struct KChunk<float> { static constexpr int value = 128; };
+template <typename T>
+__host__ __device__ __forceinline__ size_t act_offset(int m, int k, int Mcap) {
+  constexpr int KC = KChunk<T>::value;
+  return ((size_t)(k / KC) * Mcap + m) * KC + k % KC;
+}
+inline size_t act_elems(int dtype, int Mcap, int K) {
+  const int kc = dtype == 1 ? KChunk<bf16_t>::value : KChunk<float>::value;
+  return (size_t)((K + kc - 1) / kc) * Mcap * kc;
+}
+
 template <typename T> __device__ __forceinline__ Frag<T> zero_frag();
 template <> __device__ __forceinline__ Frag<bf16_t> zero_frag<bf16_t>() {
   Frag<bf16_t> f;
@@ -85,35 +128,38 @@ template <> __device__ __forceinline__ float fast_exp<bf16_t>(float x) { return 
 enum GemmEpilogue { EPI_QKV = 0, EPI_RESIDUAL = 1, EPI_GATEUP = 2, EPI_UNEMBED = 3 };
 
 struct GemmArgs {
-  const void *X;          // [M][ldx] activations, element type T
-  int ldx;
-  const void *W0, *W1, *W2;   // weight blocks, row-major [rows][K]
+  const void *X;          // activations, chunk-major [K/KC][Mcap][KC], element type T
+  const void *W0;         // weight matrix in operand order (QKV: rows [q | k | v]; gate/up: rows [gate | up])
   int M, N, K;            // N = total logical output rows
-  // EPI_RESIDUAL
-  float *h;               // [M][N] fp32, updated in place
+  int n_groups;           // pairs of 16-row groups (filled by the launcher)
+  // EPI_RESIDUAL: split ks of KS stores its fp32 partial at hpart[ks][m][n]; the next RMSNorm adds them
+  float *hpart;           // [KS][Mcap][N]
+  int KS;
   // EPI_GATEUP
-  void *act;              // [M][N] T  (N = d_ffn)
+  void *act;              // chunk-major [N/KC][Mcap][KC] T  (N = d_ffn)
   // EPI_QKV
   void *q;                // [H][Mcap][hd] T
   void *kscr;             // this layer's [Hkv][Mcap][hd] T
-  void *vscr;             // this layer's [Hkv][hd][Mcap] T (transposed)
+  void *vscr;             // this layer's [Hkv][Mcap/32][hd][32] T (tiles of 32 positions, transposed inside)
   int H, Hkv, hd, Mcap, C, P;   // m = row*C + col sits at position P + col
   const float *rope_cos, *rope_sin;   // [Spad][hd/2]
   // EPI_UNEMBED
   float *logits;          // [M][N] fp32 or null
-  float *pmax_val;        // [tiles][Mcap]
-  int *pmax_idx;          // [tiles][Mcap]
+  float *pmax_val;        // [N/32][Mcap]
+  int *pmax_idx;          // [N/32][Mcap]
 };
+
+constexpr int kMaxResidualSplits = 8;
 
 struct AttnArgs {
   const void *q;          // [H][Mcap][hd]
   const void *kcache;     // this layer's [Hkv][Spad][hd]
-  const void *vcache;     // this layer's [Hkv][hd][Spad]
+  const void *vcache;     // this layer's [Hkv][Spad/32][hd][32]
   const void *kscr;       // this layer's [Hkv][Mcap][hd]
-  const void *vscr;       // this layer's [Hkv][hd][Mcap]
+  const void *vscr;       // this layer's [Hkv][Mcap/32][hd][32]
   float *part_o;          // [H][n_splits+1][Mcap][hd]
   float *part_ml;         // [H][n_splits+1][Mcap][2]
-  void *out;              // [M][H*hd] T
+  void *out;              // chunk-major [H*hd/KC][Mcap][KC] T
   int H, Hkv, Mcap, Spad, M, C, P, n_splits, span;
   float scale;
 };
@@ -121,12 +167,16 @@ struct AttnArgs {
 // launchers (host).  dtype: 0 = fp32, 1 = bf16.  Every launcher validates nothing: the API layer
 // checks shapes before calling.
 void launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t s);
-int gemm_unembed_tiles(int N);
+int gemm_residual_splits(int dtype, int N, int K);
 void launch_attention(int dtype, int hd, const AttnArgs &a, hipStream_t s);
 
 void launch_embed(int dtype, const void *tok_emb, const int32_t *hist, const int32_t *drafts, int32_t *block_tok,
                   float *h, int d, int M, int C, int w, int hist_base, int from_hist, hipStream_t s);
-void launch_rmsnorm(int dtype, const float *h, const void *gain, void *xn, int d, int M, float eps, hipStream_t s);
+// h[m] += sum of n_part partials (hpart[s][m], stride part_stride floats between splits), then
+// xn[m] = rmsnorm(h[m]) * gain, written chunk-major
+void launch_pack_rows(int dtype, const void *src, void *dst, int d, int M, int Mcap, hipStream_t s);
+void launch_rmsnorm(int dtype, float *h, const float *hpart, int n_part, size_t part_stride, const void *gain, void *xn,
+                    int d, int M, int Mcap, float eps, hipStream_t s);
 
 struct DraftArgs {
   const int32_t *hist; int n;
@@ -135,13 +185,17 @@ struct DraftArgs {
   int32_t *reps;          // [2*max_seq] scratch: (count, last_start) of each distinct continuation
   int32_t *ctx_rows;      // [max_k][max_w]
   int32_t *n_ctx;         // [1]
-  const void *tok_emb, *unemb; int d, vocab;
+  const void *tok_emb;    // row-major [vocab][d]
+  const void *unemb_t;    // operand order
+  int d, vocab;
   float *z;               // [vocab]
   const int32_t *next1;   // [vocab]
   int32_t *drafts;        // [k][w]
   int8_t *row_src;        // [k]
 };
 void launch_build_drafts(int dtype, const DraftArgs &a, hipStream_t s);
+// copies src [N][K] (row-major) into rows row0 .. row0+N of the operand-order matrix dst
+void launch_tile_weights(int dtype, const void *src, void *dst, int N, int K, int row0, hipStream_t s);
 
 // result block layout (int32 words)
 enum { RES_WINNER = 0, RES_NACCEPT = 1, RES_NNEW = 2, RES_NCTX = 3, RES_NEWTOK = 8, RES_ACCEPT = 48 };

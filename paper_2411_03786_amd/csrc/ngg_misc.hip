@@ -49,22 +49,91 @@ __device__ __forceinline__ float block_sum_256(float v, float *sh) {
   return t;
 }
 
-template <typename T>
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const float *h, const T *gain, T *xn, int d, float eps) {
+// Every thread owns J groups of 4 consecutive features (group index tid + 256*j): all loads of the
+// row and of its residual partials are issued before anything is used, so the kernel costs one
+// memory round trip instead of one per feature.
+template <typename T, int J>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(float *__restrict__ h, const float *__restrict__ hpart, int n_part,
+                                                      size_t part_stride, const T *__restrict__ gain, T *__restrict__ xn,
+                                                      int d, int Mcap, float eps) {
   __shared__ float sh[4];
-  const float *row = h + (size_t)blockIdx.x * d;
+  const int m = blockIdx.x, d4 = d / 4;
+  float4 v[J];
+  float4 gn[J];
+#pragma unroll
+  for (int j = 0; j < J; ++j) {
+    const int i4 = threadIdx.x + 256 * j;
+    v[j] = float4{0.f, 0.f, 0.f, 0.f};
+    gn[j] = float4{0.f, 0.f, 0.f, 0.f};
+    if (i4 < d4) {
+      v[j] = *reinterpret_cast<const float4 *>(h + (size_t)m * d + 4 * i4);
+      const T *gp = gain + 4 * i4;
+      gn[j] = float4{to_f32(gp[0]), to_f32(gp[1]), to_f32(gp[2]), to_f32(gp[3])};
+    }
+  }
+  for (int s = 0; s < n_part; ++s) {                      // residual add: partials in split order
+    float4 p[J];
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+      const int i4 = threadIdx.x + 256 * j;
+      p[j] = float4{0.f, 0.f, 0.f, 0.f};
+      if (i4 < d4) p[j] = *reinterpret_cast<const float4 *>(hpart + (size_t)s * part_stride + (size_t)m * d + 4 * i4);
+    }
+#pragma unroll
+    for (int j = 0; j < J; ++j) { v[j].x += p[j].x; v[j].y += p[j].y; v[j].z += p[j].z; v[j].w += p[j].w; }
+  }
   float ss = 0.0f;
-  for (int i = threadIdx.x; i < d; i += 256) { const float v = row[i]; ss += v * v; }
+#pragma unroll
+  for (int j = 0; j < J; ++j) {
+    const int i4 = threadIdx.x + 256 * j;
+    ss += v[j].x * v[j].x + v[j].y * v[j].y + v[j].z * v[j].z + v[j].w * v[j].w;
+    if (n_part > 0 && i4 < d4) *reinterpret_cast<float4 *>(h + (size_t)m * d + 4 * i4) = v[j];
+  }
   ss = block_sum_256(ss, sh);
   const float sc = 1.0f / sqrtf(ss / (float)d + eps);
-  for (int i = threadIdx.x; i < d; i += 256) xn[(size_t)blockIdx.x * d + i] = from_f32<T>(row[i] * sc * to_f32(gain[i]));
+#pragma unroll
+  for (int j = 0; j < J; ++j) {
+    const int i4 = threadIdx.x + 256 * j;
+    if (i4 < d4) {
+      T *o = xn + act_offset<T>(m, 4 * i4, Mcap);          // 4 features stay inside one chunk
+      o[0] = from_f32<T>(v[j].x * sc * gn[j].x);
+      o[1] = from_f32<T>(v[j].y * sc * gn[j].y);
+      o[2] = from_f32<T>(v[j].z * sc * gn[j].z);
+      o[3] = from_f32<T>(v[j].w * sc * gn[j].w);
+    }
+  }
 }
 
-void launch_rmsnorm(int dtype, const float *h, const void *gain, void *xn, int d, int M, float eps, hipStream_t s) {
-  if (dtype == 1)
-    hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3(M), dim3(256), 0, s, h, (const bf16_t *)gain, (bf16_t *)xn, d, eps);
-  else
-    hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(M), dim3(256), 0, s, h, (const float *)gain, (float *)xn, d, eps);
+template <typename T>
+static void launch_rmsnorm_t(float *h, const float *hpart, int n_part, size_t part_stride, const void *gain, void *xn, int d,
+                             int M, int Mcap, float eps, hipStream_t s) {
+  const int j = (d / 4 + 255) / 256;
+#define NGG_NORM(J)                                                                                                  \
+  hipLaunchKernelGGL((rmsnorm_kernel<T, J>), dim3(M), dim3(256), 0, s, h, hpart, n_part, part_stride, (const T *)gain, \
+                     (T *)xn, d, Mcap, eps)
+  if (j <= 1) NGG_NORM(1);
+  else if (j <= 2) NGG_NORM(2);
+  else if (j <= 4) NGG_NORM(4);
+  else if (j <= 8) NGG_NORM(8);
+  else NGG_NORM(16);
+#undef NGG_NORM
+}
+
+void launch_rmsnorm(int dtype, float *h, const float *hpart, int n_part, size_t part_stride, const void *gain, void *xn,
+                    int d, int M, int Mcap, float eps, hipStream_t s) {
+  if (dtype == 1) launch_rmsnorm_t<bf16_t>(h, hpart, n_part, part_stride, gain, xn, d, M, Mcap, eps, s);
+  else launch_rmsnorm_t<float>(h, hpart, n_part, part_stride, gain, xn, d, M, Mcap, eps, s);
+}
+
+// rows of a row-major matrix -> chunk-major activation layout (used to feed embedding rows to the GEMM)
+template <typename T>
+__global__ __launch_bounds__(256) void pack_rows_kernel(const T *src, T *dst, int d, int Mcap) {
+  for (int i = threadIdx.x; i < d; i += 256) dst[act_offset<T>(blockIdx.x, i, Mcap)] = src[(size_t)blockIdx.x * d + i];
+}
+
+void launch_pack_rows(int dtype, const void *src, void *dst, int d, int M, int Mcap, hipStream_t s) {
+  if (dtype == 1) hipLaunchKernelGGL(pack_rows_kernel<bf16_t>, dim3(M), dim3(256), 0, s, (const bf16_t *)src, (bf16_t *)dst, d, Mcap);
+  else hipLaunchKernelGGL(pack_rows_kernel<float>, dim3(M), dim3(256), 0, s, (const float *)src, (float *)dst, d, Mcap);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -156,30 +225,69 @@ __global__ __launch_bounds__(1024) void ctx_match_kernel(const DraftArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Model bigram scores z[v] = <unemb[v], tok_emb[x_last]> (Section 4.1), one wave per row of the
-// output embedding, rows streamed once with 16-byte loads per lane; fp32 accumulation.
+// Model bigram scores z[v] = <unemb[v], tok_emb[x_last]> (Section 4.1).  The output embedding is
+// read in operand order: a wave owns groups of 16 vocabulary rows, every load instruction is 1 KB
+// of contiguous memory, lane (i, g) accumulates row i over its quarter of every 32-element slice
+// and the four quarters are added by two shuffles.  fp32 accumulation.
 // ---------------------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(256) void bigram_gemv_kernel(const T *tok_emb, const T *unemb, const int32_t *hist, int n,
+__global__ __launch_bounds__(256) void bigram_gemv_kernel(const T *tok_emb, const T *unemb_t, const int32_t *hist, int n,
                                                           int d, int vocab, float *z) {
   extern __shared__ float e[];
   const int x = hist[n - 1];
   for (int i = threadIdx.x; i < d; i += 256) e[i] = to_f32(tok_emb[(size_t)x * d + i]);
   __syncthreads();
-  const int lane = threadIdx.x & 63;
+  const int lane = threadIdx.x & 63, li = lane & 15, g = lane >> 4;
   const int wave = blockIdx.x * 4 + (threadIdx.x >> 6), n_waves = gridDim.x * 4;
-  for (int v = wave; v < vocab; v += n_waves) {
-    const T *row = unemb + (size_t)v * d;
+  const int n_steps = d / 32, n_groups = vocab / 16;
+  for (int grp = wave; grp < n_groups; grp += n_waves) {
+    const T *blk = tiled_block(unemb_t, grp, n_steps, lane);
     float acc = 0.0f;
-    for (int c = lane * 8; c < d; c += 512) {
-      const Frag<T> f = load_frag(row + c);
+    int s = 0;
+    for (; s + 4 <= n_steps; s += 4) {
+      Frag<T> f[4];
 #pragma unroll
-      for (int t = 0; t < 8; ++t) acc += to_f32(f.v[t]) * e[c + t];
+      for (int u = 0; u < 4; ++u) f[u] = load_frag_tiled(blk + (size_t)(s + u) * 512);
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int t = 0; t < 8; ++t) acc += to_f32(f[u].v[t]) * e[(s + u) * 32 + g * 8 + t];
     }
+    for (; s < n_steps; ++s) {
+      const Frag<T> f = load_frag_tiled(blk + (size_t)s * 512);
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
-    if (lane == 0) z[v] = acc;
+      for (int t = 0; t < 8; ++t) acc += to_f32(f.v[t]) * e[s * 32 + g * 8 + t];
+    }
+    acc += __shfl_xor(acc, 16);
+    acc += __shfl_xor(acc, 32);
+    if (g == 0) z[grp * 16 + li] = acc;
   }
+}
+
+// One-off copy of a row-major matrix into operand order (see tiled_offset).
+template <typename T>
+__global__ __launch_bounds__(256) void tile_weights_kernel(const T *src, T *dst, int N, int K, int row0) {
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const int pieces = K / 8;
+  if (idx >= (size_t)N * pieces) return;
+  const int n = (int)(idx / pieces), k = (int)(idx % pieces) * 8;
+  const T *p = src + (size_t)n * K + k;
+  T *q = dst + tiled_offset(row0 + n, k, K, (int)sizeof(T));
+  if constexpr (sizeof(T) == 2) {
+    *reinterpret_cast<u32x4 *>(q) = *reinterpret_cast<const u32x4 *>(p);
+  } else {
+    *reinterpret_cast<u32x4 *>(q) = *reinterpret_cast<const u32x4 *>(p);
+    *reinterpret_cast<u32x4 *>(q + 256) = *reinterpret_cast<const u32x4 *>(p + 4);
+  }
+}
+
+void launch_tile_weights(int dtype, const void *src, void *dst, int N, int K, int row0, hipStream_t s) {
+  const size_t total = (size_t)N * (K / 8);
+  const unsigned blocks = (unsigned)((total + 255) / 256);
+  if (dtype == 1)
+    hipLaunchKernelGGL(tile_weights_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, (const bf16_t *)src, (bf16_t *)dst, N, K, row0);
+  else
+    hipLaunchKernelGGL(tile_weights_kernel<float>, dim3(blocks), dim3(256), 0, s, (const float *)src, (float *)dst, N, K, row0);
 }
 
 // Top-(k - n_ctx) of z by (score desc, id asc), chained extension through next1, and assembly of
@@ -250,10 +358,10 @@ void launch_build_drafts(int dtype, const DraftArgs &a, hipStream_t s) {
     const size_t lds = (size_t)a.d * sizeof(float);
     if (dtype == 1)
       hipLaunchKernelGGL(bigram_gemv_kernel<bf16_t>, dim3(blocks), dim3(256), lds, s, (const bf16_t *)a.tok_emb,
-                         (const bf16_t *)a.unemb, a.hist, a.n, a.d, a.vocab, a.z);
+                         (const bf16_t *)a.unemb_t, a.hist, a.n, a.d, a.vocab, a.z);
     else
       hipLaunchKernelGGL(bigram_gemv_kernel<float>, dim3(blocks), dim3(256), lds, s, (const float *)a.tok_emb,
-                         (const float *)a.unemb, a.hist, a.n, a.d, a.vocab, a.z);
+                         (const float *)a.unemb_t, a.hist, a.n, a.d, a.vocab, a.z);
   }
   hipLaunchKernelGGL(topk_assemble_kernel, dim3(1), dim3(1024), 0, s, a);
 }
@@ -271,18 +379,27 @@ __device__ __forceinline__ void wave_argmax(float &bv, int &bi) {
   }
 }
 
-__global__ __launch_bounds__(256) void argmax_accept_kernel(const float *pmax_val, const int *pmax_idx, int tiles,
-                                                            int Mcap, int M, int k, int C, const int32_t *drafts,
-                                                            int32_t *res, int greedy_off) {
+__global__ __launch_bounds__(1024) void argmax_accept_kernel(const float *__restrict__ pmax_val,
+                                                             const int *__restrict__ pmax_idx, int tiles, int Mcap, int M,
+                                                             int k, int C, const int32_t *drafts, int32_t *res,
+                                                             int greedy_off) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int32_t *greedy = res + greedy_off;
-  for (int m = wave; m < M; m += 4) {
+  for (int m = wave; m < M; m += 16) {
     float bv = kNegBig;
     int bi = 0x7fffffff;
-    for (int t = lane; t < tiles; t += 64) {
-      const float v = pmax_val[(size_t)t * Mcap + m];
-      const int i = pmax_idx[(size_t)t * Mcap + m];
-      if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
+    for (int t0 = lane; t0 < tiles; t0 += 256) {            // four independent loads in flight
+      float v[4];
+      int ix[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int t = t0 + 64 * u;
+        v[u] = t < tiles ? pmax_val[(size_t)t * Mcap + m] : kNegBig;
+        ix[u] = t < tiles ? pmax_idx[(size_t)t * Mcap + m] : 0x7fffffff;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (v[u] > bv || (v[u] == bv && ix[u] < bi)) { bv = v[u]; bi = ix[u]; }
     }
     wave_argmax(bv, bi);
     if (lane == 0) greedy[m] = bi;
@@ -290,7 +407,7 @@ __global__ __launch_bounds__(256) void argmax_accept_kernel(const float *pmax_va
   __syncthreads();
   if (k <= 0) return;                                        // prefill / table mode: argmax only
   const int w = C - 1;
-  for (int r = tid; r < k; r += 256) {
+  for (int r = tid; r < k; r += 1024) {
     int acc = 0;
     while (acc < w && drafts[r * w + acc] == greedy[r * C + acc]) ++acc;
     res[RES_ACCEPT + r] = acc;
@@ -310,7 +427,7 @@ __global__ __launch_bounds__(256) void argmax_accept_kernel(const float *pmax_va
 
 void launch_argmax_accept(const float *pmax_val, const int *pmax_idx, int tiles, int Mcap, int M, int k, int C,
                           const int32_t *drafts, int32_t *res, int greedy_off, hipStream_t s) {
-  hipLaunchKernelGGL(argmax_accept_kernel, dim3(1), dim3(256), 0, s, pmax_val, pmax_idx, tiles, Mcap, M, k, C, drafts,
+  hipLaunchKernelGGL(argmax_accept_kernel, dim3(1), dim3(1024), 0, s, pmax_val, pmax_idx, tiles, Mcap, M, k, C, drafts,
                      res, greedy_off);
 }
 
@@ -354,8 +471,9 @@ __global__ __launch_bounds__(256) void commit_kernel(T *kcache, T *vcache, const
   T *vc = vcache + lh * hd * Spad;
   for (int i = threadIdx.x; i < n_new * hd; i += 256) {
     const int j = i / hd, dd = i - j * hd;
-    kc[(size_t)(P + j) * hd + dd] = ks[(size_t)(row * C + j) * hd + dd];
-    vc[(size_t)dd * Spad + P + j] = vs[(size_t)dd * Mcap + row * C + j];
+    const int src = row * C + j, dst = P + j;            // values live in tiles of 32 positions: [pos/32][dim][32]
+    kc[(size_t)dst * hd + dd] = ks[(size_t)src * hd + dd];
+    vc[((size_t)(dst / 32) * hd + dd) * 32 + dst % 32] = vs[((size_t)(src / 32) * hd + dd) * 32 + src % 32];
   }
   if (res && layer == 0 && hkv == 0)
     for (int i = threadIdx.x; i < n_new; i += 256) hist[P + 1 + i] = res[RES_NEWTOK + i];
