@@ -20,8 +20,9 @@
 namespace ngg {
 
 template <typename T, int EPI, int FM, int WN, int WK, int RING>
-__global__ __launch_bounds__(256) void gemm_skinny_kernel(const GemmArgs a) {
-  static_assert(WN * WK == 4, "four waves per workgroup");
+__global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArgs a) {
+  static_assert(WN * WK == 4 || WN * WK == 8, "four or eight waves per workgroup");
+  constexpr int NT = 64 * WN * WK;           // threads per workgroup
   constexpr int FN = 2;
   constexpr int KC = KChunk<T>::value;
   constexpr int SPC = KC / 32;               // steps per chunk
@@ -29,11 +30,11 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const GemmArgs a) {
   constexpr int PAD = 16 / (int)sizeof(T);
   constexpr int LDX = KC + PAD;              // LDS row stride in elements
   constexpr int ROWS = 16 * FM;
-  constexpr int PIECES = ROWS * KC * (int)sizeof(T) / 16 / 256;   // 16-byte pieces per thread per chunk
+  constexpr int PIECES = ROWS * KC * (int)sizeof(T) / 16 / NT;    // 16-byte pieces per thread per chunk
   constexpr int PPR = KC * (int)sizeof(T) / 16;                   // pieces per row
   constexpr int UC = (RING % SPW == 0) ? RING / SPW : 1;          // chunks per unrolled iteration
   static_assert((UC * SPW) % RING == 0, "ring slots must be static after unrolling");
-  static_assert(PIECES >= 1, "chunk too small for 256 threads");
+  static_assert(PIECES >= 1, "chunk too small for the workgroup");
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   T *xs = reinterpret_cast<T *>(smem);       // [2][ROWS][LDX]
@@ -81,12 +82,12 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const GemmArgs a) {
   const int c0 = (int)(((long)n_chunks * ks) / KS), c1 = (int)(((long)n_chunks * (ks + 1)) / KS);
 
   for (int m0 = 0; m0 < M; m0 += ROWS) {
-    // X staging: piece p = tid + 256*i covers row p / PPR, 16 bytes at column piece p % PPR
+    // X staging: piece p = tid + NT*i covers row p / PPR, 16 bytes at column piece p % PPR
     const T *xsrc[PIECES];
     int xdst[PIECES];
 #pragma unroll
     for (int i = 0; i < PIECES; ++i) {
-      const int p = tid + 256 * i;
+      const int p = tid + NT * i;
       const int r = p / PPR, cp = p - r * PPR;
       int m = m0 + r;
       m = m < M ? m : M - 1;                 // rows past M repeat the last one; never stored
@@ -199,12 +200,13 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const GemmArgs a) {
         } else if constexpr (EPI == EPI_GATEUP) {
           if (live) {
             T *p = (T *)a.act + act_offset<T>(m, nbase[0] + 4 * g, a.Mcap);   // 4 features stay inside one chunk
+            float o[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
               const float gt = acc[0][fm][r], up = acc[1][fm][r];
-              const float sg = gt / (1.0f + expf(-gt));              // silu(gate)
-              p[r] = from_f32<T>(sg * up);
+              o[r] = gt / (1.0f + expf(-gt)) * up;                   // silu(gate) * up
             }
+            store4(p, o[0], o[1], o[2], o[3]);
           }
         } else if constexpr (EPI == EPI_QKV) {
           if (live) {
@@ -221,8 +223,8 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const GemmArgs a) {
                 hi[r] = x2 * cs[r] + x1 * sn[r];
               }
               T *dst = (kind == 0 ? (T *)a.q : (T *)a.kscr) + ((size_t)head * a.Mcap + m) * a.hd + nbase[0] + 4 * g;
-#pragma unroll
-              for (int r = 0; r < 4; ++r) { dst[r] = from_f32<T>(lo[r]); dst[half + r] = from_f32<T>(hi[r]); }
+              store4(dst, lo[0], lo[1], lo[2], lo[3]);
+              store4(dst + half, hi[0], hi[1], hi[2], hi[3]);
             } else {                                         // v: tiles of 32 block positions, [m/32][dim][32]
               T *dst = (T *)a.vscr + (size_t)head * a.Mcap * a.hd + (size_t)(m / 32) * a.hd * 32 + (m % 32);
 #pragma unroll
@@ -269,7 +271,7 @@ void launch_gemm_cfg(const GemmArgs &a, int KS, hipStream_t s) {
   const size_t red = (size_t)(WK - 1) * WN * 2 * FM * 4 * 64 * sizeof(float);
   if (red > lds) lds = red;
   const int blocks = (a.n_groups + WN - 1) / WN;
-  hipLaunchKernelGGL((gemm_skinny_kernel<T, EPI, FM, WN, WK, RING>), dim3(blocks, KS), dim3(256), lds, s, a);
+  hipLaunchKernelGGL((gemm_skinny_kernel<T, EPI, FM, WN, WK, RING>), dim3(blocks, KS), dim3(64 * WN * WK), lds, s, a);
 }
 
 // pair groups (2 x 16 output features) of each epilogue

@@ -118,6 +118,17 @@ template <typename T> __device__ __forceinline__ T from_f32(float x);
 template <> __device__ __forceinline__ float from_f32<float>(float x) { return x; }
 template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float x) { return (bf16_t)x; }
 
+// four consecutive elements in one store (8 bytes of bf16 or 16 bytes of fp32); dst is so aligned
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void store4(bf16_t *dst, float a, float b, float c, float d) {
+  bf16x4 v;
+  v[0] = (bf16_t)a; v[1] = (bf16_t)b; v[2] = (bf16_t)c; v[3] = (bf16_t)d;
+  *reinterpret_cast<bf16x4 *>(dst) = v;
+}
+__device__ __forceinline__ void store4(float *dst, float a, float b, float c, float d) {
+  *reinterpret_cast<float4 *>(dst) = float4{a, b, c, d};
+}
+
 template <typename T> __device__ __forceinline__ float fast_exp(float x);
 template <> __device__ __forceinline__ float fast_exp<float>(float x) { return expf(x); }
 template <> __device__ __forceinline__ float fast_exp<bf16_t>(float x) { return __expf(x); }

@@ -96,10 +96,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float *__restrict__ h, con
     const int i4 = threadIdx.x + 256 * j;
     if (i4 < d4) {
       T *o = xn + act_offset<T>(m, 4 * i4, Mcap);          // 4 features stay inside one chunk
-      o[0] = from_f32<T>(v[j].x * sc * gn[j].x);
-      o[1] = from_f32<T>(v[j].y * sc * gn[j].y);
-      o[2] = from_f32<T>(v[j].z * sc * gn[j].z);
-      o[3] = from_f32<T>(v[j].w * sc * gn[j].w);
+      store4(o, v[j].x * sc * gn[j].x, v[j].y * sc * gn[j].y, v[j].z * sc * gn[j].z, v[j].w * sc * gn[j].w);
     }
   }
 }
