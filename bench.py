@@ -42,6 +42,19 @@ def gemm_bytes(m, which):
             "gemm_down": d * f * B, "gemm_unembed": m["vocab"] * d * B}[which]
 
 
+def measured_traffic(workload):
+    """HBM bytes per launch of the dominant kernel from the rocprofv3 --pmc runs recorded under
+    profiles/ (FETCH_SIZE and WRITE_SIZE scaled by a copy kernel of known size), or None."""
+    path = os.path.join(ROOT, "profiles", f"gemm_gateup_{workload}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes"):
+                return int(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(si, oracle, run, dev_weights, model_desc, tokens_per_call):
     """The oracle, as it stands, on a bounded sample: the 2-layer twin of the workload (same
     widths, same prompt length, same k and w), a few verify steps; the per-step time is scaled to
@@ -89,6 +102,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run three 1 GiB device-to-device copies (known traffic for scaling rocprofv3 counters)")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not record HIP events around the dominant kernel during the timed steps")
     args = ap.parse_args()
@@ -117,6 +132,14 @@ def main():
         r = ctx.verify_step(None, k, w, fetch=False)
         ctx.commit()
         return r["n_new"]
+
+    if args.pmc_calibration:
+        src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()
@@ -169,7 +192,8 @@ def main():
         avg_us = dom_ms * 1e3 / dom_n
         ach = gb / (avg_us * 1e-6) / 1e9
         roof = {"kernel": "gemm_skinny_kernel<bf16, gate/up + SwiGLU epilogue>", "bound": "hbm", "achieved": ach,
-                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBPS, "traffic": None,
+                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBPS,
+                "traffic": measured_traffic(args.workload),
                 "bytes_per_launch": gb, "avg_launch_us": avg_us, "launches": dom_n}
     out = {
         "metric": "accepted tokens/s at k x w (verify-step latency in ms_per_step; HBM GB/s vs peak in roofline)",
