@@ -37,7 +37,8 @@ struct ngg_ctx {
   void *kcache = nullptr, *vcache = nullptr, *kscr = nullptr, *vscr = nullptr;
   float *h = nullptr, *hpart = nullptr, *part_o = nullptr, *part_ml = nullptr, *pmax_val = nullptr, *z = nullptr, *logits = nullptr;
   float *rope_cos = nullptr, *rope_sin = nullptr;
-  int *pmax_idx = nullptr;
+  int *pmax_idx = nullptr, *cand_idx = nullptr;
+  float *cand_val = nullptr;
   void *xn = nullptr, *q = nullptr, *attn = nullptr, *act = nullptr;
   // the library's own operand-order copies of every matrix it multiplies with
   void *wtiled = nullptr;          // one allocation
@@ -272,7 +273,7 @@ ngg_status ngg_destroy(ngg_ctx *c) {
   if (!c) return NGG_EINVAL;
   (void)hipStreamSynchronize(c->stream);
   void *bufs[] = {c->hist, c->drafts, c->block_tok, c->res, c->next1, c->mlist, c->reps, c->ctx_rows, c->n_ctx,
-                  c->row_src, c->hpart, c->wtiled, c->kcache, c->vcache, c->kscr, c->vscr, c->h, c->part_o, c->part_ml, c->pmax_val, c->z,
+                  c->row_src, c->hpart, c->wtiled, c->cand_val, c->cand_idx, c->kcache, c->vcache, c->kscr, c->vscr, c->h, c->part_o, c->part_ml, c->pmax_val, c->z,
                   c->logits, c->rope_cos, c->rope_sin, c->pmax_idx, c->xn, c->q, c->attn, c->act};
   for (void *b : bufs)
     if (b) (void)hipFree(b);
@@ -350,6 +351,8 @@ ngg_status ngg_create(const ngg_model_desc *desc, const ngg_weights *weights, vo
   TRY(dev_alloc(c, &c->pmax_val, (size_t)c->unembed_tiles * c->Mcap * 4, true));
   TRY(dev_alloc(c, &c->pmax_idx, (size_t)c->unembed_tiles * c->Mcap * 4, true));
   TRY(dev_alloc(c, &c->z, (size_t)d.vocab * 4, true));
+  TRY(dev_alloc(c, &c->cand_val, (size_t)256 * 32 * 4, true));
+  TRY(dev_alloc(c, &c->cand_idx, (size_t)256 * 32 * 4, true));
   const int half = d.head_dim / 2;
   TRY(dev_alloc(c, &c->rope_cos, (size_t)c->Spad * half * 4, false));
   TRY(dev_alloc(c, &c->rope_sin, (size_t)c->Spad * half * 4, false));
@@ -432,7 +435,7 @@ ngg_status ngg_build_drafts(ngg_ctx *c, const ngg_draft_cfg *cfg, int32_t *draft
     DraftArgs a{};
     a.hist = c->hist; a.n = c->n; a.k = cfg->k; a.w = cfg->w; a.k_ctx_max = cfg->k_ctx_max; a.q_min = cfg->q_min; a.q_max = cfg->q_max;
     a.mlist = c->mlist; a.reps = c->reps; a.ctx_rows = c->ctx_rows; a.n_ctx = c->n_ctx;
-    a.tok_emb = c->w.tok_emb; a.unemb_t = c->unemb_t; a.d = c->d.d_model; a.vocab = c->d.vocab; a.z = c->z; a.next1 = c->next1;
+    a.tok_emb = c->w.tok_emb; a.unemb_t = c->unemb_t; a.d = c->d.d_model; a.vocab = c->d.vocab; a.z = c->z; a.cand_val = c->cand_val; a.cand_idx = c->cand_idx; a.next1 = c->next1;
     a.drafts = c->drafts; a.row_src = c->row_src;
     launch_build_drafts(c->d.dtype, a, c->stream);
   }

@@ -200,6 +200,8 @@ struct DraftArgs {
   const void *unemb_t;    // operand order
   int d, vocab;
   float *z;               // [vocab]
+  float *cand_val;        // [256][32] per-workgroup top-k candidates of the bigram sweep
+  int *cand_idx;
   const int32_t *next1;   // [vocab]
   int32_t *drafts;        // [k][w]
   int8_t *row_src;        // [k]

@@ -227,17 +227,27 @@ __global__ __launch_bounds__(1024) void ctx_match_kernel(const DraftArgs a) {
 // of contiguous memory, lane (i, g) accumulates row i over its quarter of every 32-element slice
 // and the four quarters are added by two shuffles.  fp32 accumulation.
 // ---------------------------------------------------------------------------------------------
+constexpr int kGemvBlocks = 256;     // workgroups of the bigram sweep; each keeps its own top-k candidates
+constexpr int kCandStride = 32;      // candidate slots per workgroup (k <= 32)
+
+__device__ __forceinline__ bool ranks_before(float v, int i, float ov, int oi) {   // (value desc, id asc)
+  return v > ov || (v == ov && i < oi);
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void bigram_gemv_kernel(const T *tok_emb, const T *unemb_t, const int32_t *hist, int n,
-                                                          int d, int vocab, float *z) {
-  extern __shared__ float e[];
+                                                          int d, int vocab, int ksel, float *z, float *cand_val,
+                                                          int *cand_idx) {
+  extern __shared__ float e[];                               // [d] embedding of x_last, then this block's scores
   const int x = hist[n - 1];
   for (int i = threadIdx.x; i < d; i += 256) e[i] = to_f32(tok_emb[(size_t)x * d + i]);
   __syncthreads();
-  const int lane = threadIdx.x & 63, li = lane & 15, g = lane >> 4;
-  const int wave = blockIdx.x * 4 + (threadIdx.x >> 6), n_waves = gridDim.x * 4;
+  const int lane = threadIdx.x & 63, li = lane & 15, g = lane >> 4, wave = threadIdx.x >> 6;
   const int n_steps = d / 32, n_groups = vocab / 16;
-  for (int grp = wave; grp < n_groups; grp += n_waves) {
+  const int gpb = (n_groups + gridDim.x - 1) / gridDim.x;   // 16-row groups per workgroup
+  const int g0 = blockIdx.x * gpb, g1 = min(n_groups, g0 + gpb);
+  float *zs = e + d;                                         // [gpb * 16]
+  for (int grp = g0 + wave; grp < g1; grp += 4) {
     const T *blk = tiled_block(unemb_t, grp, n_steps, lane);
     float acc = 0.0f;
     int s = 0;
@@ -257,7 +267,40 @@ __global__ __launch_bounds__(256) void bigram_gemv_kernel(const T *tok_emb, cons
     }
     acc += __shfl_xor(acc, 16);
     acc += __shfl_xor(acc, 32);
-    if (g == 0) z[grp * 16 + li] = acc;
+    if (g == 0) {
+      z[grp * 16 + li] = acc;
+      zs[(grp - g0) * 16 + li] = acc;
+    }
+  }
+  __syncthreads();
+  // this workgroup's ksel best scores, by (value desc, id asc): wave 0 pulls them out one by one; an entry
+  // is "still in" when it ranks strictly after the last one taken
+  if (wave == 0) {
+    const int cnt = max(0, g1 - g0) * 16;
+    float last_v = 0.0f;
+    int last_i = -1;
+    for (int r = 0; r < ksel; ++r) {
+      float bv = kNegBig;
+      int bi = 0x7fffffff;
+      for (int j = lane; j < cnt; j += 64) {
+        const float v = zs[j];
+        const int id = g0 * 16 + j;
+        if (r > 0 && !ranks_before(last_v, last_i, v, id)) continue;      // already taken
+        if (ranks_before(v, id, bv, bi)) { bv = v; bi = id; }
+      }
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) {
+        const float ov = __shfl_xor(bv, off);
+        const int oi = __shfl_xor(bi, off);
+        if (ranks_before(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+      }
+      if (lane == 0) {
+        cand_val[blockIdx.x * kCandStride + r] = bv;         // (kNegBig, INT_MAX) once the block ran out
+        cand_idx[blockIdx.x * kCandStride + r] = bi;
+      }
+      last_v = bv;
+      last_i = bi;
+    }
   }
 }
 
@@ -295,41 +338,48 @@ __global__ __launch_bounds__(1024) void topk_assemble_kernel(const DraftArgs a) 
   __shared__ float sel_v;
   __shared__ int sel_i;
   __shared__ int top[64];
+  constexpr int CPT = kGemvBlocks * kCandStride / 1024;     // candidate slots per thread
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n_ctx = *a.n_ctx;
   const int k_big = a.w >= 1 ? a.k - n_ctx : 0;
-  // this thread's best remaining candidate
-  float bv = kNegBig;
-  int bi = 0x7fffffff;
-  auto rescan = [&](float lim_v, int lim_i, bool limited) {
-    bv = kNegBig; bi = 0x7fffffff;
-    for (int v = tid; v < a.vocab; v += 1024) {
-      const float zv = a.z[v];
-      if (limited && !(zv < lim_v || (zv == lim_v && v > lim_i))) continue;   // already selected
-      if (zv > bv || (zv == bv && v < bi)) { bv = zv; bi = v; }
-    }
-  };
-  rescan(0.f, 0, false);
+  // the candidates every workgroup of the sweep kept (its own top-k): the global top-k is among them
+  float cv[CPT];
+  int ci[CPT];
+#pragma unroll
+  for (int j = 0; j < CPT; ++j) {
+    const int slot = tid + 1024 * j;
+    const bool used = (slot % kCandStride) < a.k && k_big > 0;
+    cv[j] = used ? a.cand_val[slot] : kNegBig;
+    ci[j] = used ? a.cand_idx[slot] : 0x7fffffff;
+  }
+  float last_v = 0.0f;
+  int last_i = -1;
   for (int r = 0; r < k_big; ++r) {
-    float cv = bv;
-    int ci = bi;
+    float bv = kNegBig;
+    int bi = 0x7fffffff;
+#pragma unroll
+    for (int j = 0; j < CPT; ++j) {
+      const bool in = r == 0 || ranks_before(last_v, last_i, cv[j], ci[j]);
+      if (in && ranks_before(cv[j], ci[j], bv, bi)) { bv = cv[j]; bi = ci[j]; }
+    }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
-      const float ov = __shfl_xor(cv, off);
-      const int oi = __shfl_xor(ci, off);
-      if (ov > cv || (ov == cv && oi < ci)) { cv = ov; ci = oi; }
+      const float ov = __shfl_xor(bv, off);
+      const int oi = __shfl_xor(bi, off);
+      if (ranks_before(ov, oi, bv, bi)) { bv = ov; bi = oi; }
     }
-    if (lane == 0) { wv[wave] = cv; wi[wave] = ci; }
+    if (lane == 0) { wv[wave] = bv; wi[wave] = bi; }
     __syncthreads();
     if (tid == 0) {
       float fv = wv[0];
       int fi = wi[0];
       for (int t = 1; t < 16; ++t)
-        if (wv[t] > fv || (wv[t] == fv && wi[t] < fi)) { fv = wv[t]; fi = wi[t]; }
+        if (ranks_before(wv[t], wi[t], fv, fi)) { fv = wv[t]; fi = wi[t]; }
       sel_v = fv; sel_i = fi; top[r] = fi;
     }
     __syncthreads();
-    if (bi == sel_i) rescan(sel_v, sel_i, true);           // only the owner of the winner looks again
+    last_v = sel_v;
+    last_i = sel_i;
     __syncthreads();
   }
   __syncthreads();
@@ -351,14 +401,14 @@ __global__ __launch_bounds__(1024) void topk_assemble_kernel(const DraftArgs a) 
 void launch_build_drafts(int dtype, const DraftArgs &a, hipStream_t s) {
   hipLaunchKernelGGL(ctx_match_kernel, dim3(1), dim3(1024), 0, s, a);
   if (a.w >= 1) {
-    const int blocks = 1024;
-    const size_t lds = (size_t)a.d * sizeof(float);
+    const int n_groups = a.vocab / 16, gpb = (n_groups + kGemvBlocks - 1) / kGemvBlocks;
+    const size_t lds = ((size_t)a.d + (size_t)gpb * 16) * sizeof(float);
     if (dtype == 1)
-      hipLaunchKernelGGL(bigram_gemv_kernel<bf16_t>, dim3(blocks), dim3(256), lds, s, (const bf16_t *)a.tok_emb,
-                         (const bf16_t *)a.unemb_t, a.hist, a.n, a.d, a.vocab, a.z);
+      hipLaunchKernelGGL(bigram_gemv_kernel<bf16_t>, dim3(kGemvBlocks), dim3(256), lds, s, (const bf16_t *)a.tok_emb,
+                         (const bf16_t *)a.unemb_t, a.hist, a.n, a.d, a.vocab, a.k, a.z, a.cand_val, a.cand_idx);
     else
-      hipLaunchKernelGGL(bigram_gemv_kernel<float>, dim3(blocks), dim3(256), lds, s, (const float *)a.tok_emb,
-                         (const float *)a.unemb_t, a.hist, a.n, a.d, a.vocab, a.z);
+      hipLaunchKernelGGL(bigram_gemv_kernel<float>, dim3(kGemvBlocks), dim3(256), lds, s, (const float *)a.tok_emb,
+                         (const float *)a.unemb_t, a.hist, a.n, a.d, a.vocab, a.k, a.z, a.cand_val, a.cand_idx);
   }
   hipLaunchKernelGGL(topk_assemble_kernel, dim3(1), dim3(1024), 0, s, a);
 }
@@ -376,35 +426,43 @@ __device__ __forceinline__ void wave_argmax(float &bv, int &bi) {
   }
 }
 
-__global__ __launch_bounds__(1024) void argmax_accept_kernel(const float *__restrict__ pmax_val,
-                                                             const int *__restrict__ pmax_idx, int tiles, int Mcap, int M,
-                                                             int k, int C, const int32_t *drafts, int32_t *res,
-                                                             int greedy_off) {
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  int32_t *greedy = res + greedy_off;
-  for (int m = wave; m < M; m += 16) {
-    float bv = kNegBig;
-    int bi = 0x7fffffff;
-    for (int t0 = lane; t0 < tiles; t0 += 256) {            // four independent loads in flight
-      float v[4];
-      int ix[4];
+// greedy[m] = argmax over the vocabulary of position m, from the per-tile maxima; one workgroup per position
+__global__ __launch_bounds__(256) void argmax_reduce_kernel(const float *__restrict__ pmax_val,
+                                                            const int *__restrict__ pmax_idx, int tiles, int Mcap,
+                                                            int32_t *greedy) {
+  __shared__ float wv[4];
+  __shared__ int wi[4];
+  const int m = blockIdx.x, tid = threadIdx.x;
+  float bv = kNegBig;
+  int bi = 0x7fffffff;
+  for (int t0 = tid; t0 < tiles; t0 += 1024) {              // four independent loads in flight
+    float v[4];
+    int ix[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int t = t0 + 64 * u;
-        v[u] = t < tiles ? pmax_val[(size_t)t * Mcap + m] : kNegBig;
-        ix[u] = t < tiles ? pmax_idx[(size_t)t * Mcap + m] : 0x7fffffff;
-      }
-#pragma unroll
-      for (int u = 0; u < 4; ++u)
-        if (v[u] > bv || (v[u] == bv && ix[u] < bi)) { bv = v[u]; bi = ix[u]; }
+    for (int u = 0; u < 4; ++u) {
+      const int t = t0 + 256 * u;
+      v[u] = t < tiles ? pmax_val[(size_t)t * Mcap + m] : kNegBig;
+      ix[u] = t < tiles ? pmax_idx[(size_t)t * Mcap + m] : 0x7fffffff;
     }
-    wave_argmax(bv, bi);
-    if (lane == 0) greedy[m] = bi;
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (v[u] > bv || (v[u] == bv && ix[u] < bi)) { bv = v[u]; bi = ix[u]; }
   }
+  wave_argmax(bv, bi);
+  if ((tid & 63) == 0) { wv[tid >> 6] = bv; wi[tid >> 6] = bi; }
   __syncthreads();
-  if (k <= 0) return;                                        // prefill / table mode: argmax only
+  if (tid == 0) {
+    for (int t = 1; t < 4; ++t)
+      if (wv[t] > bv || (wv[t] == bv && wi[t] < bi)) { bv = wv[t]; bi = wi[t]; }
+    greedy[m] = bi;
+  }
+}
+
+__global__ __launch_bounds__(64) void accept_kernel(int k, int C, const int32_t *drafts, int32_t *res, int greedy_off) {
+  const int tid = threadIdx.x;
+  const int32_t *greedy = res + greedy_off;
   const int w = C - 1;
-  for (int r = tid; r < k; r += 1024) {
+  for (int r = tid; r < k; r += 64) {
     int acc = 0;
     while (acc < w && drafts[r * w + acc] == greedy[r * C + acc]) ++acc;
     res[RES_ACCEPT + r] = acc;
@@ -424,30 +482,13 @@ __global__ __launch_bounds__(1024) void argmax_accept_kernel(const float *__rest
 
 void launch_argmax_accept(const float *pmax_val, const int *pmax_idx, int tiles, int Mcap, int M, int k, int C,
                           const int32_t *drafts, int32_t *res, int greedy_off, hipStream_t s) {
-  hipLaunchKernelGGL(argmax_accept_kernel, dim3(1), dim3(1024), 0, s, pmax_val, pmax_idx, tiles, Mcap, M, k, C, drafts,
-                     res, greedy_off);
-}
-
-__global__ __launch_bounds__(256) void next1_finish_kernel(const float *pmax_val, const int *pmax_idx, int tiles,
-                                                           int Mcap, int M, int32_t *out) {
-  const int lane = threadIdx.x & 63;
-  const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (m >= M) return;
-  float bv = kNegBig;
-  int bi = 0x7fffffff;
-  for (int t = lane; t < tiles; t += 64) {
-    const float v = pmax_val[(size_t)t * Mcap + m];
-    const int i = pmax_idx[(size_t)t * Mcap + m];
-    if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
-  }
-  wave_argmax(bv, bi);
-  if (lane == 0) out[m] = bi;
+  hipLaunchKernelGGL(argmax_reduce_kernel, dim3(M), dim3(256), 0, s, pmax_val, pmax_idx, tiles, Mcap, res + greedy_off);
+  if (k > 0) hipLaunchKernelGGL(accept_kernel, dim3(1), dim3(64), 0, s, k, C, drafts, res, greedy_off);
 }
 
 void launch_next1_finish(const float *pmax_val, const int *pmax_idx, int tiles, int Mcap, int M, int32_t *next1_out,
                          hipStream_t s) {
-  hipLaunchKernelGGL(next1_finish_kernel, dim3((M + 3) / 4), dim3(256), 0, s, pmax_val, pmax_idx, tiles, Mcap, M,
-                     next1_out);
+  hipLaunchKernelGGL(argmax_reduce_kernel, dim3(M), dim3(256), 0, s, pmax_val, pmax_idx, tiles, Mcap, next1_out);
 }
 
 // ---------------------------------------------------------------------------------------------
