@@ -318,7 +318,7 @@ ngg_status ngg_create(const ngg_model_desc *desc, const ngg_weights *weights, vo
   c->stream = (hipStream_t)hip_stream;
   c->esize = d.dtype == NGG_BF16 ? 2 : 4;
   c->Spad = (int)rup((size_t)d.max_seq + 1, 32);
-  c->Mcap = (int)rup((size_t)std::max(d.max_k * (d.max_w + 1), kPrefillChunk), 32);
+  c->Mcap = (int)rup((size_t)std::max(d.max_k * (d.max_w + 1), kPrefillChunk), 64);
   c->max_splits = 32;
   c->unembed_tiles = d.vocab / 32;
 

@@ -70,20 +70,21 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const AttnArgs a) {
     v_src[i] = dd * 32 + vc * PAD;
     v_dst[i] = dd * VROW + vc * PAD;
   }
-  u32x4 kst[PPT], vst[PPT];
-  auto stage_load = [&](int t) {
+  // two register stages: the tile after next is already on its way while the current one is used
+  u32x4 kst[2][PPT], vst[2][PPT];
+  auto stage_load = [&](u32x4 (&kr)[PPT], u32x4 (&vr)[PPT], int t) {
     const int k0 = min(key_begin + t * 32, last_tile_key);  // clamped: loads are unconditional
 #pragma unroll
     for (int i = 0; i < PPT; ++i) {
-      kst[i] = *reinterpret_cast<const u32x4 *>(kbase + (size_t)k0 * HD + k_src[i]);
-      vst[i] = *reinterpret_cast<const u32x4 *>(vbase + (size_t)k0 * HD + v_src[i]);
+      kr[i] = *reinterpret_cast<const u32x4 *>(kbase + (size_t)k0 * HD + k_src[i]);
+      vr[i] = *reinterpret_cast<const u32x4 *>(vbase + (size_t)k0 * HD + v_src[i]);
     }
   };
-  auto stage_store = [&](int buf) {
+  auto stage_store = [&](const u32x4 (&kr)[PPT], const u32x4 (&vr)[PPT], int buf) {
 #pragma unroll
     for (int i = 0; i < PPT; ++i) {
-      *reinterpret_cast<u32x4 *>(ks + buf * 32 * KROW + k_dst[i]) = kst[i];
-      *reinterpret_cast<u32x4 *>(vs + buf * HD * VROW + v_dst[i]) = vst[i];
+      *reinterpret_cast<u32x4 *>(ks + buf * 32 * KROW + k_dst[i]) = kr[i];
+      *reinterpret_cast<u32x4 *>(vs + buf * HD * VROW + v_dst[i]) = vr[i];
     }
   };
 
@@ -100,13 +101,8 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const AttnArgs a) {
 #pragma unroll
   for (int df = 0; df < DF; ++df) O[df] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  if (n_tiles > 0) stage_load(0);
-  for (int t = 0; t < n_tiles; ++t) {
-    const int buf = t & 1;
-    stage_store(buf);
-    __syncthreads();
-    stage_load(t + 1);
-    if (active) {
+  auto compute = [&](int t, int buf) {
+    if (active && t < n_tiles) {
       const int k0 = key_begin + t * 32;
       const T *kt = ks + buf * 32 * KROW + li * KROW + g * 8;
       const T *vt = vs + buf * HD * VROW + li * VROW + g * 8;
@@ -157,6 +153,19 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const AttnArgs a) {
         mma(O[df], load_frag(vt + df * 16 * VROW), Pf);
       }
     }
+  };
+
+  stage_load(kst[0], vst[0], 0);
+  stage_load(kst[1], vst[1], 1);
+  for (int t = 0; t < n_tiles; t += 2) {                    // barriers are uniform; the odd tail only loads
+    stage_store(kst[0], vst[0], 0);
+    __syncthreads();
+    stage_load(kst[0], vst[0], t + 2);
+    compute(t, 0);
+    stage_store(kst[1], vst[1], 1);
+    __syncthreads();
+    stage_load(kst[1], vst[1], t + 3);
+    compute(t + 1, 1);
   }
 
   const int m = m0 + li;

@@ -32,7 +32,8 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
   constexpr int ROWS = 16 * FM;
   constexpr int PIECES = ROWS * KC * (int)sizeof(T) / 16 / NT;    // 16-byte pieces per thread per chunk
   constexpr int PPR = KC * (int)sizeof(T) / 16;                   // pieces per row
-  constexpr int UC = (RING % SPW == 0) ? RING / SPW : 1;          // chunks per unrolled iteration
+  constexpr int UC0 = (RING % SPW == 0) ? RING / SPW : 1;
+  constexpr int UC = UC0 % 2 == 0 ? UC0 : 2 * UC0;                // chunks per unrolled iteration (even: two X stages)
   static_assert((UC * SPW) % RING == 0, "ring slots must be static after unrolling");
   static_assert(PIECES >= 1, "chunk too small for the workgroup");
 
@@ -82,30 +83,24 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
   const int c0 = (int)(((long)n_chunks * ks) / KS), c1 = (int)(((long)n_chunks * (ks + 1)) / KS);
 
   for (int m0 = 0; m0 < M; m0 += ROWS) {
-    // X staging: piece p = tid + NT*i covers row p / PPR, 16 bytes at column piece p % PPR
-    const T *xsrc[PIECES];
-    int xdst[PIECES];
-#pragma unroll
-    for (int i = 0; i < PIECES; ++i) {
-      const int p = tid + NT * i;
-      const int r = p / PPR, cp = p - r * PPR;
-      int m = m0 + r;
-      m = m < M ? m : M - 1;                 // rows past M repeat the last one; never stored
-      xsrc[i] = (const T *)a.X + (size_t)m * KC + cp * PAD;     // chunk c adds c * Mcap * KC
-      xdst[i] = r * LDX + cp * PAD;
-    }
-    // Every global load below is unconditional (addresses are clamped into valid memory instead of
-    // being guarded): with straight-line loads the compiler can wait for exactly the load it needs
-    // (s_waitcnt vmcnt(n)) instead of draining the whole prefetch ring at every chunk boundary.
-    u32x4 stage[PIECES];
-    auto stage_load = [&](int c) {
+    // X staging: piece p = tid + NT*i covers row p / PPR (= tid / PPR + i * NT / PPR), 16 bytes at column
+    // piece p % PPR.  Rows past M are read as they are (the buffers hold Mcap rows, a multiple of 64,
+    // of finite stale values) and never stored.
+    static_assert(NT % PPR == 0, "row stride of the staging pieces must be constant");
+    constexpr int RPI = NT / PPR;                          // rows between a thread's consecutive pieces
+    const T *xsrc0 = (const T *)a.X + (size_t)(m0 + tid / PPR) * KC + (tid % PPR) * PAD;   // chunk c adds c * Mcap * KC
+    const int xdst0 = (tid / PPR) * LDX + (tid % PPR) * PAD;
+    // X is fetched two chunks ahead into two register stages (an L2 hit takes longer than one chunk of
+    // MFMA work), then written to the LDS buffer of its chunk's parity.
+    u32x4 stage[2][PIECES];
+    auto stage_load = [&](u32x4 (&st)[PIECES], int c) {
       const int cl = c < n_chunks ? c : n_chunks - 1;      // activation buffers are padded to whole chunks
 #pragma unroll
-      for (int i = 0; i < PIECES; ++i) stage[i] = *reinterpret_cast<const u32x4 *>(xsrc[i] + (size_t)cl * a.Mcap * KC);
+      for (int i = 0; i < PIECES; ++i) st[i] = *reinterpret_cast<const u32x4 *>(xsrc0 + (size_t)cl * a.Mcap * KC + i * RPI * KC);
     };
-    auto stage_store = [&](int buf) {
+    auto stage_store = [&](const u32x4 (&st)[PIECES], int buf) {
 #pragma unroll
-      for (int i = 0; i < PIECES; ++i) *reinterpret_cast<u32x4 *>(xs + (size_t)buf * ROWS * LDX + xdst[i]) = stage[i];
+      for (int i = 0; i < PIECES; ++i) *reinterpret_cast<u32x4 *>(xs + (size_t)buf * ROWS * LDX + xdst0 + i * RPI * LDX) = st[i];
     };
 
     f32x4 acc[FN][FM];
@@ -114,34 +109,37 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
 #pragma unroll
       for (int fm = 0; fm < FM; ++fm) acc[f][fm] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // wave-step t is global step (c0 + t/SPW)*SPC + wk + WK*(t % SPW); steps past the end are clamped
-    // to the last one (loaded, never multiplied)
+    // wave-step t is global step (c0 + t/SPW)*SPC + wk + WK*(t % SPW); steps outside the matrix are
+    // clamped into it (loaded, never multiplied)
     Frag<T> ring[RING][FN];
     auto load_w = [&](Frag<T> (&slot)[FN], int t) {
-      int s = (c0 + t / SPW) * SPC + wk + WK * (t % SPW);
+      int s = c0 * SPC + (t / SPW) * SPC + wk + WK * (t % SPW);   // t >= 0 here
       s = s < n_steps ? s : n_steps - 1;
 #pragma unroll
       for (int f = 0; f < FN; ++f) slot[f] = load_frag_tiled(wblk[f] + (size_t)s * 512);
     };
-#pragma unroll
-    for (int u = 0; u < RING; ++u) load_w(ring[u], u);
-    stage_load(c0);
 
+    // The loop has no separate prologue: it starts one unrolled group early (ci = -UC) with the
+    // multiplications switched off, so the loads that fill the ring and the X stages are issued by the
+    // very instructions that refill them later.  Every trip then enters with the same set of loads
+    // outstanding, in the same order, and the compiler's s_waitcnt vmcnt(n) before each use is exact
+    // (with a prologue in another order it merged the two states and waited for nearly everything).
     const int n_iter = (c1 - c0 + UC - 1) / UC * UC;       // whole unrolled groups; extra chunks only load
-    for (int ci = 0; ci < n_iter; ci += UC) {
+    for (int ci = -UC; ci < n_iter; ci += UC) {
+      const bool warm = ci < 0;
 #pragma unroll
       for (int cc = 0; cc < UC; ++cc) {
         const int ch = c0 + ci + cc;
-        const int buf = (ci + cc) & 1;
-        stage_store(buf);
+        const int buf = cc & 1;                          // UC is even
+        if (!warm) stage_store(stage[cc & 1], buf);
         __syncthreads();
-        stage_load(ch + 1);
+        stage_load(stage[cc & 1], max(ch + 2, 0));
         const T *xb = xs + (size_t)buf * ROWS * LDX + li * LDX + g * 8;
 #pragma unroll
         for (int i = 0; i < SPW; ++i) {
           const int slot = (cc * SPW + i) % RING;        // constant after unrolling
           const int ls = wk + WK * i;                    // step inside the chunk
-          if (ch < c1 && ch * SPC + ls < n_steps) {      // uniform per wave; no global load inside
+          if (!warm && ch < c1 && ch * SPC + ls < n_steps) {      // uniform per wave; no global load inside
             Frag<T> xb_f[FM];
 #pragma unroll
             for (int fm = 0; fm < FM; ++fm) xb_f[fm] = load_frag(xb + fm * 16 * LDX + ls * 32);
@@ -150,7 +148,7 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
 #pragma unroll
               for (int fm = 0; fm < FM; ++fm) mma(acc[f][fm], ring[slot][f], xb_f[fm]);
           }
-          load_w(ring[slot], (ci + cc) * SPW + i + RING);
+          load_w(ring[slot], max((ci + cc) * SPW + i + RING, 0));
         }
       }
     }
