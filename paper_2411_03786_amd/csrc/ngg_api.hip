@@ -124,16 +124,7 @@ ngg_status forward(ngg_ctx *c, int R, int C, int P, bool from_hist, int w, bool 
     ProfScope ps(c, NGG_PROF_OTHER);
     launch_embed(dt, c->w.tok_emb, c->hist, c->drafts, c->block_tok, c->h, d.d_model, M, C, w, P, from_hist ? 1 : 0, s);
   }
-  // key spans: enough workgroups to fill 256 CUs, but spans of at least 256 keys so the partial
-  // outputs stay small next to the keys and values read
-  int n_splits = 0, span = 0;
-  if (P > 0) {
-    int want = (512 + d.n_heads - 1) / d.n_heads;
-    int by_len = (P + 255) / 256;
-    n_splits = std::max(1, std::min(std::min(want, by_len), c->max_splits));
-    span = (int)rup((size_t)(P + n_splits - 1) / n_splits, 32);
-    n_splits = (P + span - 1) / span;
-  }
+  const int n_splits = attention_splits(dt, d.head_dim, d.n_heads, M, P, c->max_splits);
   const size_t part_stride = (size_t)c->Mcap * d.d_model;
   const int ks_o = gemm_residual_splits(dt, d.d_model, dq), ks_down = gemm_residual_splits(dt, d.d_model, d.d_ffn);
   int pending = 0;                                   // residual partials the next RMSNorm has to add
@@ -162,7 +153,7 @@ ngg_status forward(ngg_ctx *c, int R, int C, int P, bool from_hist, int w, bool 
       a.kscr = kscr_l; a.vscr = vscr_l;
       a.part_o = c->part_o; a.part_ml = c->part_ml; a.out = c->attn;
       a.H = d.n_heads; a.Hkv = d.n_kv_heads; a.Mcap = c->Mcap; a.Spad = c->Spad; a.M = M; a.C = C; a.P = P;
-      a.n_splits = n_splits; a.span = span;
+      a.n_splits = n_splits;
       a.scale = 1.0f / std::sqrt((float)d.head_dim);
       launch_attention(dt, d.head_dim, a, s);
     }
@@ -318,7 +309,9 @@ ngg_status ngg_create(const ngg_model_desc *desc, const ngg_weights *weights, vo
   c->stream = (hipStream_t)hip_stream;
   c->esize = d.dtype == NGG_BF16 ? 2 : 4;
   c->Spad = (int)rup((size_t)d.max_seq + 1, 32);
+  // whole GEMM row tiles: 64 rows, or 128-row tiles once a block has more than 64 rows
   c->Mcap = (int)rup((size_t)std::max(d.max_k * (d.max_w + 1), kPrefillChunk), 64);
+  if (c->Mcap > 64) c->Mcap = (int)rup((size_t)c->Mcap, 128);
   c->max_splits = 32;
   c->unembed_tiles = d.vocab / 32;
 

@@ -1,162 +1,384 @@
 // Shared-prefix attention for the verify block.  Section 4.1 batches the k drafts by repeating
 // the context into k identical rows, and the "Limitations" paragraph names the redundant prefix
-// work as the method's cost; here the cached context is read ONCE for all k rows: a workgroup
-// owns (head, key span), and every block token (row r, column j) is a query against that span.
-// The block's own keys (row r, columns <= j) form one more "span" with a per-row causal mask.
-// Partial (max, sum, output) triples are merged by a second kernel in span order (deterministic).
+// work as the method's cost; here the cached context is read ONCE for all k rows: every block token
+// (row r, column j) is a query against the same cached keys, followed by the block's own keys (row
+// r, columns <= j: a per-row causal mask).  Per head, the cached tiles and the block's tiles form
+// one list that S workgroups split evenly; their partial (max, sum, output) triples are merged by a
+// second kernel in list order (deterministic).
 //
-// Layouts: keys [kv head][position][head_dim]; values in tiles of 32 positions, transposed inside
-// the tile, [kv head][position/32][head_dim][32]: a tile of 32 keys and its 32 values are two
-// contiguous regions, staged through LDS once per workgroup (double buffered) and read from there
-// by the four waves (one group of 16 queries each) as MFMA row operands.
+// Keys and values are kept in MFMA operand order (k_offset / v_offset in ngg_internal.h): a tile of
+// 32 positions is 32*hd contiguous elements, cut into 1 KB blocks that are each exactly one
+// wave-wide fragment load.  Two kernels use them:
+//  * attn_shared_kernel (more than 16 block tokens): the four waves of a workgroup own different
+//    groups of 16*QF queries and all need every tile, so the workgroup copies each tile into LDS once
+//    (a linear copy: the tile already is in fragment order, so every fragment read is conflict-free)
+//    and the waves read their MFMA operands from there.  No merge between waves.
+//  * attn_stream_kernel (up to 16 block tokens, the single-token decode step): one group of queries,
+//    so the four waves split the tiles instead and each tile goes from global memory straight into
+//    the registers of the one wave that needs it; LDS only carries the final merge of the four waves.
 #include "ngg_internal.h"
 
 namespace ngg {
 
-// element (position, dim) of a value tensor stored in tiles of 32 positions: [position/32][dim][32]
-template <int HD>
-__host__ __device__ __forceinline__ size_t v_offset(int pos, int dim) {
-  return ((size_t)(pos / 32) * HD + dim) * 32 + pos % 32;
+// Softmax arithmetic: the fp32 configuration uses expf on scores scaled by 1/sqrt(hd); the bf16
+// configuration keeps scores, running maxima and the stored partial maxima in the base-2 domain
+// (scores times log2(e)/sqrt(hd)) so that each probability is one subtraction and one v_exp_f32.
+template <typename T> struct Softmax;
+template <> struct Softmax<float> {
+  static __device__ __forceinline__ float factor(float scale) { return scale; }
+  static __device__ __forceinline__ float ex(float x) { return expf(x); }
+};
+template <> struct Softmax<bf16_t> {
+  static __device__ __forceinline__ float factor(float scale) { return scale * 1.44269504088896f; }
+  static __device__ __forceinline__ float ex(float x) { return __builtin_amdgcn_exp2f(x); }
+};
+
+// One 16-query fragment against one 32-key tile, after the scores: online softmax and P.V.
+// Sc: transposed scores (fragment f's row i is key 8*(i/4) + 4f + (i%4) of the tile, so this lane
+// holds the 8 consecutive keys k0 .. k0+7 of its query); keys outside [lo, hi] are masked unless the
+// whole tile is visible to every query (full).
+template <typename T, int DF, typename VFrag>
+__device__ __forceinline__ void softmax_pv(const f32x4 (&Sc)[2], float sfac, bool full, int k0, int lo, int hi,
+                                           float &mrun, float &lrun, f32x4 (&O)[DF], VFrag vfrag) {
+  float sv[8], p[8];
+  float mx = kNegBig, ps = 0.0f;
+  if (full) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      sv[e] = Sc[e >> 2][e & 3] * sfac;
+      mx = fmaxf(mx, sv[e]);
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const bool vis = k0 + e >= lo && k0 + e <= hi;
+      sv[e] = vis ? Sc[e >> 2][e & 3] * sfac : kNegBig;
+      mx = fmaxf(mx, sv[e]);
+    }
+  }
+  const float mnew = fmaxf(mrun, rows_max(mx));
+  const float alpha = Softmax<T>::ex(mrun - mnew);
+  if (full) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      p[e] = Softmax<T>::ex(sv[e] - mnew);
+      ps += p[e];
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      p[e] = sv[e] > 0.5f * kNegBig ? Softmax<T>::ex(sv[e] - mnew) : 0.0f;
+      ps += p[e];
+    }
+  }
+  lrun = lrun * alpha + rows_sum(ps);
+  // the output so far needs rescaling only if some query's maximum moved, and not on the first
+  // tile (the output is still zero); the maxima settle after a few tiles
+  const bool rescale = __ballot(mnew != mrun && mrun > 0.5f * kNegBig) != 0;
+  mrun = mnew;
+  Frag<T> Pf;
+  pack_frag(Pf, p);
+  if (rescale) {
+#pragma unroll
+    for (int df = 0; df < DF; ++df)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) O[df][r] *= alpha;
+  }
+#pragma unroll
+  for (int df = 0; df < DF; ++df) mma(O[df], vfrag(df), Pf);
 }
 
-template <typename T, int HD>
-__global__ __launch_bounds__(256) void attn_partial_kernel(const AttnArgs a) {
+// One workgroup = 4 waves that take the tiles of one (head, list slice) round-robin, each against
+// the same 16*QF queries.  With more than 16*QF block tokens, Z workgroups share a slice; the 1-D
+// grid is laid out so that those Z get consecutive slots of one XCD (workgroup b goes to XCD b % 8):
+// they run at about the same time on the same L2, and the slice comes from HBM once.
+template <typename T, int HD, int QF>
+__global__ __launch_bounds__(256) void attn_stream_kernel(const AttnArgs a, int Z, int n_units) {
   constexpr int DS = HD / 32;   // contraction slices of q.k
   constexpr int DF = HD / 16;   // 16-row groups of the transposed output
-  constexpr int PAD = 16 / (int)sizeof(T);
-  constexpr int KROW = HD + PAD, VROW = 32 + PAD;           // padded LDS rows: conflict-free fragment reads
-  constexpr int TILE_PIECES = 32 * HD * (int)sizeof(T) / 16;   // 16-byte pieces of a 32-key K (or V) tile
-  constexpr int PPT = (TILE_PIECES + 255) / 256;            // pieces per thread
-  constexpr int KPPR = HD * (int)sizeof(T) / 16;            // pieces per key row
-  constexpr int VPPR = 32 * (int)sizeof(T) / 16;            // pieces per dim row
-  const int split = blockIdx.x, h = blockIdx.y, mg = blockIdx.z;
+  constexpr int TILE = 32 * HD; // elements of a 32-position tile of keys (or values)
+  constexpr int NW = 4;         // waves
+  constexpr int GQ = 16 * QF;   // queries per workgroup
+  constexpr int DUMP = QF * DF * 4 + 2 * QF;   // floats per lane handed over in the merge
+  const int slot_b = blockIdx.x / 8, xcd = blockIdx.x % 8;
+  const int unit = (slot_b / Z) * 8 + xcd;                  // (head, slice) pair
+  if (unit >= n_units) return;                              // padding of the last row of 8
+  const int S = a.n_splits;
+  const int split = unit % S, h = unit / S;
   const int hkv = h / (a.H / a.Hkv);
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: tile indices and their branches stay uniform
   const int li = lane & 15, g = lane >> 4;
-  const bool suffix = split == a.n_splits;
-  const int M = a.M, C = a.C;
+  const int M = a.M, C = a.C, P = a.P;
+  const int q0 = (slot_b % Z) * GQ;                         // first query of this workgroup
+  const bool active = q0 < M;
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  T *ks = reinterpret_cast<T *>(smem);                      // [2][32][KROW], rows in fragment order
-  T *vs = ks + 2 * 32 * KROW;                               // [2][HD][VROW]
+  T *qs = reinterpret_cast<T *>(smem);                      // [QF][DS][64 lanes][8]: the queries as fragments
+  float *red = reinterpret_cast<float *>(smem + (size_t)QF * DS * 512 * sizeof(T));   // [4 waves][DUMP][64]
 
-  const T *kbase, *vbase;
-  int key_begin, key_end, last_tile_key;
-  if (!suffix) {
-    kbase = (const T *)a.kcache + (size_t)hkv * a.Spad * HD;
-    vbase = (const T *)a.vcache + (size_t)hkv * a.Spad * HD;
-    key_begin = split * a.span;
-    key_end = min(a.P, key_begin + a.span);
-  } else {                                                  // the block's own keys: only the rows this group of
-    kbase = (const T *)a.kscr + (size_t)hkv * a.Mcap * HD;  // 64 queries lives in
-    vbase = (const T *)a.vscr + (size_t)hkv * a.Mcap * HD;
-    const int q_lo = mg * 64, q_hi = min(M, q_lo + 64) - 1;
-    key_begin = ((q_lo / C) * C) / 32 * 32;
-    key_end = min(M, (q_hi / C + 1) * C);
-  }
-  const int n_tiles = (key_end - key_begin + 31) / 32;
-  last_tile_key = key_begin + (n_tiles - 1) * 32;
+  // ---- the tile list: NP cached tiles, then the NS tiles of the block's own keys that hold the draft
+  //      rows of this workgroup's queries; this workgroup takes list entries [t_begin, t_end) -----------
+  const int q_lo = min(q0, M - 1), q_hi = min(M, q0 + GQ) - 1;
+  const int NP = (P + 31) / 32;
+  const int sb = ((q_lo / C) * C) / 32;                     // first block tile
+  const int NS = (min(M, (q_hi / C + 1) * C) + 31) / 32 - sb;
+  const int TL = NP + NS;
+  const int t_begin = (int)((long)TL * split / S), t_end = (int)((long)TL * (split + 1) / S);
+  const int n_tiles = active ? t_end - t_begin : 0;
+  const T *kc = (const T *)a.kcache + (size_t)hkv * a.Spad * HD, *vc = (const T *)a.vcache + (size_t)hkv * a.Spad * HD;
+  const T *ksc = (const T *)a.kscr + (size_t)hkv * a.Mcap * HD, *vsc = (const T *)a.vscr + (size_t)hkv * a.Mcap * HD;
 
-  // staging: thread copies PPT pieces of the K tile and PPT pieces of the V tile
-  int k_src[PPT], k_dst[PPT], v_src[PPT], v_dst[PPT];
+  // this lane's queries (result columns), one per group of 16: visible block keys are [qlo, qhi]
+  int qlo[QF], qhi[QF];
+  float mrun[QF], lrun[QF];
+  f32x4 O[QF][DF];
 #pragma unroll
-  for (int i = 0; i < PPT; ++i) {
-    int p = tid + 256 * i;
-    p = p < TILE_PIECES ? p : TILE_PIECES - 1;              // duplicates write the same bytes
-    const int kk = p / KPPR, kc = p - kk * KPPR;            // key inside the tile, 16-byte column
-    k_src[i] = kk * HD + kc * PAD;
-    k_dst[i] = (((kk >> 2) & 1) * 16 + (kk >> 3) * 4 + (kk & 3)) * KROW + kc * PAD;   // key 8a+4f+b -> row 16f+4a+b
-    const int dd = p / VPPR, vc = p - dd * VPPR;
-    v_src[i] = dd * 32 + vc * PAD;
-    v_dst[i] = dd * VROW + vc * PAD;
+  for (int qf = 0; qf < QF; ++qf) {
+    const int mq = min(q0 + qf * 16 + li, M - 1);
+    qlo[qf] = (mq / C) * C;
+    qhi[qf] = mq;
+    mrun[qf] = kNegBig;
+    lrun[qf] = 0.0f;
+#pragma unroll
+    for (int df = 0; df < DF; ++df) O[qf][df] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
-  // two register stages: the tile after next is already on its way while the current one is used
+
+  // tile registers, two sets: K as 2 x DS fragments (rows = keys in the permuted order of
+  // kv_key_row), V as DF fragments (rows = dims, contraction = the tile's 32 keys)
+  Frag<T> kf[2][2][DS], vf[2][DF];
+  auto load_tile = [&](Frag<T> (&kr)[2][DS], Frag<T> (&vr)[DF], int t) {
+    const int ct = max(min(t_begin + t, t_end - 1), 0);     // clamped into the list: loads are unconditional
+    const bool own = ct >= NP;
+    const size_t off = (size_t)(own ? sb + ct - NP : ct) * TILE;
+    const T *kp = tiled_block((own ? ksc : kc) + off, 0, DS, lane);
+    const T *vp = tiled_block((own ? vsc : vc) + off, 0, 1, lane);
+#pragma unroll
+    for (int f = 0; f < 2; ++f)
+#pragma unroll
+      for (int ds = 0; ds < DS; ++ds) kr[f][ds] = load_frag_tiled(kp + (f * DS + ds) * 512);
+#pragma unroll
+    for (int df = 0; df < DF; ++df) vr[df] = load_frag_tiled(vp + df * 512);
+  };
+
+  const float sfac = Softmax<T>::factor(a.scale);
+  constexpr int QG = QF >= 2 ? 2 : 1;                       // query groups in flight together (independent MFMA chains)
+  auto compute = [&](const Frag<T> (&kr)[2][DS], const Frag<T> (&vr)[DF], int t) {
+    if (t < n_tiles) {                                      // uniform per wave
+      const int ct = t_begin + t;
+      const bool own = ct >= NP;
+      const int tile0 = (own ? sb + ct - NP : ct) * 32;
+      const int k0 = tile0 + 8 * g;                         // this lane's first key of the tile
+      const bool full = !own && tile0 + 32 <= P;            // every key visible to every query: no masks
+#pragma unroll
+      for (int q2 = 0; q2 < QF; q2 += QG) {
+        __asm__ volatile("" ::: "memory");                  // keep the query fragments in LDS: re-read them here
+        // scores, transposed: rows = keys, columns = queries.  Fragment f's row i is key
+        // 8*(i/4) + 4f + (i%4) of the tile, so this lane ends up with 8 consecutive keys.
+        f32x4 Sc[QG][2];
+#pragma unroll
+        for (int j = 0; j < QG; ++j)
+#pragma unroll
+          for (int f = 0; f < 2; ++f) Sc[j][f] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ds = 0; ds < DS; ++ds)
+#pragma unroll
+          for (int j = 0; j < QG; ++j) {
+            const Frag<T> qfrag = load_frag(qs + (size_t)(((q2 + j) * DS + ds) * 64 + lane) * 8);
+#pragma unroll
+            for (int f = 0; f < 2; ++f) mma(Sc[j][f], kr[f][ds], qfrag);
+          }
+#pragma unroll
+        for (int j = 0; j < QG; ++j) {
+          const int qf = q2 + j;
+          softmax_pv<T, DF>(Sc[j], sfac, full, k0, own ? qlo[qf] : 0, own ? qhi[qf] : P - 1, mrun[qf], lrun[qf], O[qf],
+                            [&](int df) { return vr[df]; });
+        }
+      }
+    }
+  };
+
+  load_tile(kf[0], vf[0], wv);                              // on its way while the queries are staged
+
+  // ---- queries into LDS, in operand order: entry (qf, ds, l) = query q0 + 16 qf + l%16, dims 32 ds + 8 (l/16) .. +8
+  for (int e = tid; e < QF * DS * 64; e += 64 * NW) {
+    const int l = e & 63, fd = e >> 6, qf = fd / DS, ds = fd - qf * DS;
+    const int mq = min(q0 + qf * 16 + (l & 15), M - 1);
+    const T *src = (const T *)a.q + ((size_t)h * a.Mcap + mq) * HD + ds * 32 + (l >> 4) * 8;
+    T *dst = qs + (size_t)e * 8;
+    if constexpr (sizeof(T) == 2) {
+      *reinterpret_cast<u32x4 *>(dst) = *reinterpret_cast<const u32x4 *>(src);
+    } else {
+      *reinterpret_cast<u32x4 *>(dst) = *reinterpret_cast<const u32x4 *>(src);
+      *reinterpret_cast<u32x4 *>(dst + 4) = *reinterpret_cast<const u32x4 *>(src + 4);
+    }
+  }
+  __syncthreads();
+
+  for (int t = wv; t < n_tiles; t += 2 * NW) {
+    load_tile(kf[1], vf[1], t + NW);
+    compute(kf[0], vf[0], t);
+    load_tile(kf[0], vf[0], t + 2 * NW);
+    compute(kf[1], vf[1], t + NW);
+  }
+
+  // ---- merge the four waves through LDS: every wave hands over its (max, sum, output) registers,
+  //      then wave w combines items w, w + 4, ... of the QF*DF output fragments, always adding the
+  //      waves in the order 0, 1, 2, 3, and stores them as this workgroup's partial -------------------
+  {
+    float *dst = red + (size_t)wv * DUMP * 64;
+#pragma unroll
+    for (int qf = 0; qf < QF; ++qf) {
+#pragma unroll
+      for (int df = 0; df < DF; ++df)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) dst[((qf * DF + df) * 4 + r) * 64 + lane] = O[qf][df][r];
+      dst[(QF * DF * 4 + 2 * qf) * 64 + lane] = mrun[qf];
+      dst[(QF * DF * 4 + 2 * qf + 1) * 64 + lane] = lrun[qf];
+    }
+  }
+  __syncthreads();
+  if (!active) return;
+  for (int item = wv; item < QF * DF; item += NW) {
+    const int qf = item / DF, df = item - qf * DF;
+    const int m = q0 + qf * 16 + li;
+    float mw[NW], mstar = kNegBig;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      mw[w] = red[((size_t)w * DUMP + QF * DF * 4 + 2 * qf) * 64 + lane];
+      mstar = fmaxf(mstar, mw[w]);
+    }
+    float l = 0.0f;
+    f32x4 o = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      const float wgt = Softmax<T>::ex(mw[w] - mstar);
+      l += red[((size_t)w * DUMP + QF * DF * 4 + 2 * qf + 1) * 64 + lane] * wgt;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) o[r] += red[((size_t)w * DUMP + item * 4 + r) * 64 + lane] * wgt;
+    }
+    // partial outputs keep the fragment order, [head][slice][16-query group][df][lane][4]: one store
+    // instruction of the wave writes 1 KB contiguously
+    const size_t blk = ((size_t)h * S + split) * (a.Mcap / 16) + (q0 / 16 + qf);
+    *reinterpret_cast<float4 *>(a.part_o + ((blk * DF + df) * 64 + lane) * 4) = float4{o[0], o[1], o[2], o[3]};
+    if (m < M && df == 0 && g == 0) {
+      const size_t slot = ((size_t)h * S + split) * a.Mcap + m;
+      a.part_ml[slot * 2 + 0] = mstar;
+      a.part_ml[slot * 2 + 1] = l;
+    }
+  }
+}
+
+// Workgroup = (head, list slice, group of 64*QF queries); wave w owns queries q0 + 16*QF*w .. and
+// reads every tile of the slice from the LDS copy.  Grid layout as in attn_stream_kernel.
+template <typename T, int HD, int QF>
+__global__ __launch_bounds__(256) void attn_shared_kernel(const AttnArgs a, int Z, int n_units) {
+  constexpr int DS = HD / 32, DF = HD / 16;
+  constexpr int TILE = 32 * HD;
+  constexpr int GQ = 64 * QF;                               // queries per workgroup
+  constexpr int PIECES = TILE * (int)sizeof(T) / 16;        // 16-byte pieces of a K (or V) tile
+  constexpr int PPT = (PIECES + 255) / 256;                 // pieces per thread
+  const int slot_b = blockIdx.x / 8, xcd = blockIdx.x % 8;
+  const int unit = (slot_b / Z) * 8 + xcd;
+  if (unit >= n_units) return;
+  const int S = a.n_splits;
+  const int split = unit % S, h = unit / S;
+  const int hkv = h / (a.H / a.Hkv);
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int li = lane & 15, g = lane >> 4;
+  const int M = a.M, C = a.C, P = a.P;
+  const int q0 = (slot_b % Z) * GQ;                         // first query of this workgroup (< M)
+  const int qw = q0 + wv * 16 * QF;                         // first query of this wave
+  const bool active = qw < M;
+
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  T *kl = reinterpret_cast<T *>(smem);                      // [2][TILE] key tiles
+  T *vl = kl + 2 * TILE;                                    // [2][TILE] value tiles
+
+  const int q_hi = min(M, q0 + GQ) - 1;
+  const int NP = (P + 31) / 32;
+  const int sb = ((q0 / C) * C) / 32;
+  const int NS = (min(M, (q_hi / C + 1) * C) + 31) / 32 - sb;
+  const int TL = NP + NS;
+  const int t_begin = (int)((long)TL * split / S), t_end = (int)((long)TL * (split + 1) / S);
+  const int n_tiles = t_end - t_begin;
+  const T *kc = (const T *)a.kcache + (size_t)hkv * a.Spad * HD, *vc = (const T *)a.vcache + (size_t)hkv * a.Spad * HD;
+  const T *ksc = (const T *)a.kscr + (size_t)hkv * a.Mcap * HD, *vsc = (const T *)a.vscr + (size_t)hkv * a.Mcap * HD;
+
+  // two register stages: the tile after next is on its way while the current one is used
   u32x4 kst[2][PPT], vst[2][PPT];
   auto stage_load = [&](u32x4 (&kr)[PPT], u32x4 (&vr)[PPT], int t) {
-    const int k0 = min(key_begin + t * 32, last_tile_key);  // clamped: loads are unconditional
+    const int ct = max(min(t_begin + t, t_end - 1), 0);     // clamped into the list: loads are unconditional
+    const bool own = ct >= NP;
+    const size_t off = (size_t)(own ? sb + ct - NP : ct) * TILE;
+    const T *kp = (own ? ksc : kc) + off, *vp = (own ? vsc : vc) + off;
 #pragma unroll
     for (int i = 0; i < PPT; ++i) {
-      kr[i] = *reinterpret_cast<const u32x4 *>(kbase + (size_t)k0 * HD + k_src[i]);
-      vr[i] = *reinterpret_cast<const u32x4 *>(vbase + (size_t)k0 * HD + v_src[i]);
+      const int pc = min(tid + 256 * i, PIECES - 1);        // surplus threads repeat the last piece
+      kr[i] = *reinterpret_cast<const u32x4 *>(kp + (size_t)pc * (16 / sizeof(T)));
+      vr[i] = *reinterpret_cast<const u32x4 *>(vp + (size_t)pc * (16 / sizeof(T)));
     }
   };
   auto stage_store = [&](const u32x4 (&kr)[PPT], const u32x4 (&vr)[PPT], int buf) {
 #pragma unroll
     for (int i = 0; i < PPT; ++i) {
-      *reinterpret_cast<u32x4 *>(ks + buf * 32 * KROW + k_dst[i]) = kr[i];
-      *reinterpret_cast<u32x4 *>(vs + buf * HD * VROW + v_dst[i]) = vr[i];
+      const int pc = min(tid + 256 * i, PIECES - 1);
+      *reinterpret_cast<u32x4 *>(kl + (size_t)buf * TILE + (size_t)pc * (16 / sizeof(T))) = kr[i];
+      *reinterpret_cast<u32x4 *>(vl + (size_t)buf * TILE + (size_t)pc * (16 / sizeof(T))) = vr[i];
     }
   };
-
-  const int mf = mg * 4 + wave;                             // this wave's group of 16 queries
-  const bool active = mf * 16 < M;
-  const int m0 = mf * 16;
-  const int mq = min(m0 + li, M - 1);                       // this lane's query (result column)
-  const int qrow = mq / C, qcol = mq - qrow * C;
-  Frag<T> Q[DS];
-#pragma unroll
-  for (int ds = 0; ds < DS; ++ds) Q[ds] = load_frag((const T *)a.q + ((size_t)h * a.Mcap + mq) * HD + ds * 32 + g * 8);
-  float mrun = kNegBig, lrun = 0.0f;
-  f32x4 O[DF];
-#pragma unroll
-  for (int df = 0; df < DF; ++df) O[df] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-  auto compute = [&](int t, int buf) {
-    if (active && t < n_tiles) {
-      const int k0 = key_begin + t * 32;
-      const T *kt = ks + buf * 32 * KROW + li * KROW + g * 8;
-      const T *vt = vs + buf * HD * VROW + li * VROW + g * 8;
-      // scores, transposed: rows = keys, columns = queries.  Fragment f's row i is key
-      // k0 + 8*(i/4) + 4f + (i%4), so this lane ends up with the 8 consecutive keys k0 + 8g .. +8.
-      f32x4 S[2];
-#pragma unroll
-      for (int f = 0; f < 2; ++f) {
-        S[f] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ds = 0; ds < DS; ++ds) mma(S[f], load_frag(kt + f * 16 * KROW + ds * 32), Q[ds]);
-      }
-      float sv[8];
-      bool vis[8];
-      float mx = kNegBig;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int key = k0 + 8 * g + e;
-        if (suffix) {
-          const int kr = key / C;
-          vis[e] = key < M && kr == qrow && (key - kr * C) <= qcol;
-        } else {
-          vis[e] = key < key_end;
-        }
-        sv[e] = vis[e] ? S[e >> 2][e & 3] * a.scale : kNegBig;
-        mx = fmaxf(mx, sv[e]);
-      }
-      mx = fmaxf(mx, __shfl_xor(mx, 16));
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float mnew = fmaxf(mrun, mx);
-      const float alpha = fast_exp<T>(mrun - mnew);
-      float p[8], ps = 0.0f;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        p[e] = vis[e] ? fast_exp<T>(sv[e] - mnew) : 0.0f;
-        ps += p[e];
-      }
-      ps += __shfl_xor(ps, 16);
-      ps += __shfl_xor(ps, 32);
-      lrun = lrun * alpha + ps;
-      mrun = mnew;
-      Frag<T> Pf;
-      pack_frag(Pf, p);
-#pragma unroll
-      for (int df = 0; df < DF; ++df) {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) O[df][r] *= alpha;
-        mma(O[df], load_frag(vt + df * 16 * VROW), Pf);
-      }
-    }
-  };
-
   stage_load(kst[0], vst[0], 0);
   stage_load(kst[1], vst[1], 1);
+
+  // this lane's queries (result columns), one per group of 16: visible block keys are [qlo, qhi]
+  int qlo[QF], qhi[QF];
+  float mrun[QF], lrun[QF];
+  Frag<T> Q[QF][DS];
+  f32x4 O[QF][DF];
+#pragma unroll
+  for (int qf = 0; qf < QF; ++qf) {
+    const int mq = min(qw + qf * 16 + li, M - 1);
+    qlo[qf] = (mq / C) * C;
+    qhi[qf] = mq;
+    mrun[qf] = kNegBig;
+    lrun[qf] = 0.0f;
+#pragma unroll
+    for (int ds = 0; ds < DS; ++ds) Q[qf][ds] = load_frag((const T *)a.q + ((size_t)h * a.Mcap + mq) * HD + ds * 32 + g * 8);
+#pragma unroll
+    for (int df = 0; df < DF; ++df) O[qf][df] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  const float sfac = Softmax<T>::factor(a.scale);
+  constexpr int LOFF = sizeof(T) == 2 ? 8 : 4;              // this lane's slice of a 1 KB (fp32: half-)block
+
+  auto compute = [&](int t, int buf) {
+    if (active && t < n_tiles) {                            // uniform per wave
+      const int ct = t_begin + t;
+      const bool own = ct >= NP;
+      const int tile0 = (own ? sb + ct - NP : ct) * 32;
+      const int k0 = tile0 + 8 * g;
+      const bool full = !own && tile0 + 32 <= P;
+      const T *kt = kl + (size_t)buf * TILE + lane * LOFF, *vt = vl + (size_t)buf * TILE + lane * LOFF;
+      f32x4 Sc[QF][2];
+#pragma unroll
+      for (int qf = 0; qf < QF; ++qf)
+#pragma unroll
+        for (int f = 0; f < 2; ++f) Sc[qf][f] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ds = 0; ds < DS; ++ds)
+#pragma unroll
+        for (int f = 0; f < 2; ++f) {
+          const Frag<T> kfrag = load_frag_tiled(kt + (f * DS + ds) * 512);
+#pragma unroll
+          for (int qf = 0; qf < QF; ++qf) mma(Sc[qf][f], kfrag, Q[qf][ds]);
+        }
+#pragma unroll
+      for (int qf = 0; qf < QF; ++qf)
+        softmax_pv<T, DF>(Sc[qf], sfac, full, k0, own ? qlo[qf] : 0, own ? qhi[qf] : P - 1, mrun[qf], lrun[qf], O[qf],
+                          [&](int df) { return load_frag_tiled(vt + df * 512); });
+    }
+  };
+
   for (int t = 0; t < n_tiles; t += 2) {                    // barriers are uniform; the odd tail only loads
     stage_store(kst[0], vst[0], 0);
     __syncthreads();
@@ -168,45 +390,109 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const AttnArgs a) {
     compute(t + 1, 1);
   }
 
-  const int m = m0 + li;
-  if (active && m < M) {
-    const size_t slot = ((size_t)h * (a.n_splits + 1) + split) * a.Mcap + m;
+  if (active) {
 #pragma unroll
-    for (int df = 0; df < DF; ++df) {
-      float4 v{O[df][0], O[df][1], O[df][2], O[df][3]};
-      *reinterpret_cast<float4 *>(a.part_o + slot * HD + df * 16 + 4 * g) = v;
-    }
-    if (g == 0) {
-      a.part_ml[slot * 2 + 0] = mrun;
-      a.part_ml[slot * 2 + 1] = lrun;
+    for (int qf = 0; qf < QF; ++qf) {
+      // partial outputs keep the fragment order, [head][slice][16-query group][df][lane][4]
+      const size_t blk = ((size_t)h * S + split) * (a.Mcap / 16) + (qw / 16 + qf);
+#pragma unroll
+      for (int df = 0; df < DF; ++df)
+        *reinterpret_cast<float4 *>(a.part_o + ((blk * DF + df) * 64 + lane) * 4) =
+            float4{O[qf][df][0], O[qf][df][1], O[qf][df][2], O[qf][df][3]};
+      const int m = qw + qf * 16 + li;
+      if (m < M && g == 0) {
+        const size_t slot = ((size_t)h * S + split) * a.Mcap + m;
+        a.part_ml[slot * 2 + 0] = mrun[qf];
+        a.part_ml[slot * 2 + 1] = lrun[qf];
+      }
     }
   }
 }
 
-// out[m][h*HD + d] = sum_s o_s[d] e^{m_s - m*} / sum_s l_s e^{m_s - m*}, spans taken in index order.
+// out[m][h*HD + d] = sum_s o_s[d] e^{m_s - m*} / sum_s l_s e^{m_s - m*}, slices taken in index order,
+// 8 at a time with a running maximum (one round of loads when there are at most 8 slices: the kernel
+// is a chain of memory latencies, nothing else).  One workgroup per (16-query group, head); a thread
+// owns one lane's 4 values of an output fragment (dims 16 df + 4 (lane/16) .. +4 of query lane%16).
 template <typename T, int HD>
-__global__ __launch_bounds__(HD) void attn_merge_kernel(const AttnArgs a) {
-  const int m = blockIdx.x, h = blockIdx.y, d = threadIdx.x;
-  const int S = a.n_splits + 1;
-  const size_t slot0 = (size_t)h * S * a.Mcap + m;
-  float mstar = kNegBig;
-  for (int s = 0; s < S; ++s) mstar = fmaxf(mstar, a.part_ml[(slot0 + (size_t)s * a.Mcap) * 2]);
-  float l = 0.0f, o = 0.0f;
-  for (int s = 0; s < S; ++s) {
-    const size_t slot = slot0 + (size_t)s * a.Mcap;
-    const float wgt = fast_exp<T>(a.part_ml[slot * 2] - mstar);
-    l += a.part_ml[slot * 2 + 1] * wgt;
-    o += a.part_o[slot * HD + d] * wgt;
+__global__ __launch_bounds__(256) void attn_merge_kernel(const AttnArgs a) {
+  constexpr int DF = HD / 16;
+  const int qb = blockIdx.x, h = blockIdx.y;
+  const int S = a.n_splits, MB = a.Mcap / 16;
+  for (int idx = threadIdx.x; idx < DF * 64; idx += 256) {
+    const int df = idx >> 6, lane = idx & 63;
+    const int m = qb * 16 + (lane & 15), d4 = df * 16 + 4 * (lane >> 4);
+    if (m >= a.M) continue;
+    const size_t slot0 = (size_t)h * S * a.Mcap + m;
+    float mrun = kNegBig, l = 0.0f;
+    float4 o{0.f, 0.f, 0.f, 0.f};
+    for (int s0 = 0; s0 < S; s0 += 8) {
+      float4 v[8];
+      float2 ml[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int sc = min(s0 + i, S - 1);
+        v[i] = *reinterpret_cast<const float4 *>(a.part_o + (((((size_t)h * S + sc) * MB + qb) * DF + df) * 64 + lane) * 4);
+        ml[i] = *reinterpret_cast<const float2 *>(a.part_ml + (slot0 + (size_t)sc * a.Mcap) * 2);
+      }
+      float mnew = mrun;
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        if (s0 + i < S) mnew = fmaxf(mnew, ml[i].x);
+      const float alpha = Softmax<T>::ex(mrun - mnew);
+      l *= alpha; o.x *= alpha; o.y *= alpha; o.z *= alpha; o.w *= alpha;
+      mrun = mnew;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        if (s0 + i < S) {
+          const float wgt = Softmax<T>::ex(ml[i].x - mrun);
+          l += ml[i].y * wgt;
+          o.x += v[i].x * wgt; o.y += v[i].y * wgt; o.z += v[i].z * wgt; o.w += v[i].w * wgt;
+        }
+      }
+    }
+    const float inv = 1.0f / l;
+    store4((T *)a.out + act_offset<T>(m, h * HD + d4, a.Mcap), o.x * inv, o.y * inv, o.z * inv, o.w * inv);
   }
-  ((T *)a.out)[act_offset<T>(m, h * HD + d, a.Mcap)] = from_f32<T>(o / l);
+}
+
+template <typename T, int HD, int QF>
+static void launch_stream(const AttnArgs &a, hipStream_t s) {
+  const size_t lds = (size_t)QF * (HD / 32) * 512 * sizeof(T) + (size_t)4 * (QF * (HD / 16) * 4 + 2 * QF) * 64 * sizeof(float);
+  const int Z = (a.M + 16 * QF - 1) / (16 * QF);
+  const int n_units = a.n_splits * a.H;
+  hipLaunchKernelGGL((attn_stream_kernel<T, HD, QF>), dim3((n_units + 7) / 8 * 8 * Z), dim3(256), lds, s, a, Z, n_units);
+}
+
+// query groups of 16 per wave in attn_shared_kernel: two once a block has more than 64 tokens,
+// where the registers hold them (fp32 fragments are twice as large)
+template <typename T, int HD> constexpr int attn_shared_qmax() { return sizeof(T) == 2 || HD <= 64 ? 2 : 1; }
+
+template <typename T, int HD, int QF>
+static void launch_shared(const AttnArgs &a, hipStream_t s) {
+  const size_t lds = (size_t)4 * 32 * HD * sizeof(T);
+  const int Z = (a.M + 64 * QF - 1) / (64 * QF);
+  const int n_units = a.n_splits * a.H;
+  hipLaunchKernelGGL((attn_shared_kernel<T, HD, QF>), dim3((n_units + 7) / 8 * 8 * Z), dim3(256), lds, s, a, Z, n_units);
 }
 
 template <typename T, int HD>
 static void launch_hd(const AttnArgs &a, hipStream_t s) {
-  constexpr int PAD = 16 / (int)sizeof(T);
-  const size_t lds = (size_t)2 * (32 * (HD + PAD) + HD * (32 + PAD)) * sizeof(T);
-  hipLaunchKernelGGL((attn_partial_kernel<T, HD>), dim3(a.n_splits + 1, a.H, (a.M + 63) / 64), dim3(256), lds, s, a);
-  hipLaunchKernelGGL((attn_merge_kernel<T, HD>), dim3(a.M, a.H), dim3(HD), 0, s, a);
+  if (a.M <= 16) launch_stream<T, HD, 1>(a, s);
+  else if (a.M <= 64 || attn_shared_qmax<T, HD>() == 1) launch_shared<T, HD, 1>(a, s);
+  else launch_shared<T, HD, attn_shared_qmax<T, HD>()>(a, s);
+  hipLaunchKernelGGL((attn_merge_kernel<T, HD>), dim3((a.M + 15) / 16, a.H), dim3(256), 0, s, a);
+}
+
+// Number of list slices per head: about one workgroup per CU in total, but at least 4 tiles per slice.
+int attention_splits(int dtype, int hd, int H, int M, int P, int max_splits) {
+  const int qmax = dtype == 1 || hd <= 64 ? 2 : 1;
+  const int per_wg = M <= 16 ? 16 : (M <= 64 ? 64 : 64 * qmax);
+  const int Z = (M + per_wg - 1) / per_wg;
+  const int tiles = (P + 31) / 32 + 1;
+  int s = 256 / (H * Z);
+  s = s < tiles / 4 ? s : tiles / 4;
+  s = s < max_splits ? s : max_splits;
+  return s < 1 ? 1 : s;
 }
 
 template <typename T>

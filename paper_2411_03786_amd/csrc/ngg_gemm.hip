@@ -21,6 +21,7 @@ namespace ngg {
 
 template <typename T, int EPI, int FM, int WN, int WK, int RING>
 __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArgs a) {
+  constexpr int XD = FM > 4 ? 1 : 2;         // X register stages (chunks fetched ahead); one when the tile is 128 rows
   static_assert(WN * WK == 4 || WN * WK == 8, "four or eight waves per workgroup");
   constexpr int NT = 64 * WN * WK;           // threads per workgroup
   constexpr int FN = 2;
@@ -90,9 +91,9 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
     constexpr int RPI = NT / PPR;                          // rows between a thread's consecutive pieces
     const T *xsrc0 = (const T *)a.X + (size_t)(m0 + tid / PPR) * KC + (tid % PPR) * PAD;   // chunk c adds c * Mcap * KC
     const int xdst0 = (tid / PPR) * LDX + (tid % PPR) * PAD;
-    // X is fetched two chunks ahead into two register stages (an L2 hit takes longer than one chunk of
+    // X is fetched XD chunks ahead into register stages (an L2 hit takes longer than one chunk of
     // MFMA work), then written to the LDS buffer of its chunk's parity.
-    u32x4 stage[2][PIECES];
+    u32x4 stage[XD][PIECES];
     auto stage_load = [&](u32x4 (&st)[PIECES], int c) {
       const int cl = c < n_chunks ? c : n_chunks - 1;      // activation buffers are padded to whole chunks
 #pragma unroll
@@ -131,9 +132,9 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
       for (int cc = 0; cc < UC; ++cc) {
         const int ch = c0 + ci + cc;
         const int buf = cc & 1;                          // UC is even
-        if (!warm) stage_store(stage[cc & 1], buf);
+        if (!warm) stage_store(stage[cc % XD], buf);
         __syncthreads();
-        stage_load(stage[cc & 1], max(ch + 2, 0));
+        stage_load(stage[cc % XD], max(ch + XD, 0));
         const T *xb = xs + (size_t)buf * ROWS * LDX + li * LDX + g * 8;
 #pragma unroll
         for (int i = 0; i < SPW; ++i) {
@@ -220,15 +221,21 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
                 lo[r] = x1 * cs[r] - x2 * sn[r];
                 hi[r] = x2 * cs[r] + x1 * sn[r];
               }
-              T *dst = (kind == 0 ? (T *)a.q : (T *)a.kscr) + ((size_t)head * a.Mcap + m) * a.hd + nbase[0] + 4 * g;
-              store4(dst, lo[0], lo[1], lo[2], lo[3]);
-              store4(dst + half, hi[0], hi[1], hi[2], hi[3]);
-            } else {                                         // v: tiles of 32 block positions, [m/32][dim][32]
-              T *dst = (T *)a.vscr + (size_t)head * a.Mcap * a.hd + (size_t)(m / 32) * a.hd * 32 + (m % 32);
+              if (kind == 0) {
+                T *dst = (T *)a.q + ((size_t)head * a.Mcap + m) * a.hd + nbase[0] + 4 * g;
+                store4(dst, lo[0], lo[1], lo[2], lo[3]);
+                store4(dst + half, hi[0], hi[1], hi[2], hi[3]);
+              } else {                                       // keys: tiles of 32 block positions in operand order
+                T *kh = (T *)a.kscr + (size_t)head * a.Mcap * a.hd;
+                store4(kh + k_offset(m, nbase[0] + 4 * g, a.hd, (int)sizeof(T)), lo[0], lo[1], lo[2], lo[3]);
+                store4(kh + k_offset(m, nbase[0] + 4 * g + half, a.hd, (int)sizeof(T)), hi[0], hi[1], hi[2], hi[3]);
+              }
+            } else {                                         // values: the transposed tiles
+              T *vh = (T *)a.vscr + (size_t)head * a.Mcap * a.hd;
 #pragma unroll
               for (int r = 0; r < 4; ++r) {
-                dst[(size_t)(nbase[0] + 4 * g + r) * 32] = from_f32<T>(acc[0][fm][r]);
-                dst[(size_t)(nbase[0] + 4 * g + half + r) * 32] = from_f32<T>(acc[1][fm][r]);
+                vh[v_offset(m, nbase[0] + 4 * g + r, a.hd, (int)sizeof(T))] = from_f32<T>(acc[0][fm][r]);
+                vh[v_offset(m, nbase[0] + 4 * g + half + r, a.hd, (int)sizeof(T))] = from_f32<T>(acc[1][fm][r]);
               }
             }
           }
@@ -269,6 +276,12 @@ void launch_gemm_cfg(const GemmArgs &a, int KS, hipStream_t s) {
   const size_t red = (size_t)(WK - 1) * WN * 2 * FM * 4 * 64 * sizeof(float);
   if (red > lds) lds = red;
   const int blocks = (a.n_groups + WN - 1) / WN;
+  if (lds > 64 * 1024) {                     // more than the default dynamic LDS limit: opt in once
+    static const hipError_t opted = hipFuncSetAttribute(
+        reinterpret_cast<const void *>(&gemm_skinny_kernel<T, EPI, FM, WN, WK, RING>),
+        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    (void)opted;
+  }
   hipLaunchKernelGGL((gemm_skinny_kernel<T, EPI, FM, WN, WK, RING>), dim3(blocks, KS), dim3(64 * WN * WK), lds, s, a);
 }
 
@@ -285,7 +298,8 @@ template <typename T, int EPI, int WN, int WK, int RING>
 static void launch_fm(const GemmArgs &a, int KS, hipStream_t s) {
   if (a.M <= 16) launch_gemm_cfg<T, EPI, 1, WN, WK, RING>(a, KS, s);
   else if (a.M <= 32) launch_gemm_cfg<T, EPI, 2, WN, WK, RING>(a, KS, s);
-  else launch_gemm_cfg<T, EPI, 4, WN, WK, RING>(a, KS, s);
+  else if (a.M <= 64) launch_gemm_cfg<T, EPI, 4, WN, WK, RING>(a, KS, s);
+  else launch_gemm_cfg<T, EPI, 8, WN, WK, RING>(a, KS, s);   // 128-row tiles; more rows loop over W again
 }
 
 // Split of the contraction across workgroups for the residual GEMMs (two waves share a pair of row

@@ -63,6 +63,19 @@ __device__ __forceinline__ Frag<float> load_frag_tiled(const float *p) {
   return f;
 }
 
+// Keys and values of one (layer, kv head) live in tiles of 32 positions, 32*hd elements each, both in
+// operand order.  A key tile is the [32 keys][hd] matrix with its rows permuted (key 8a + 4f + b of
+// the tile is row 16f + 4a + b: with that order the lane that holds a score fragment's column owns 8
+// consecutive keys, which is what the probabilities' operand layout needs); a value tile is the
+// transposed [hd][32 keys] matrix.
+__host__ __device__ __forceinline__ int kv_key_row(int kk) { return ((kk >> 2) & 1) * 16 + (kk >> 3) * 4 + (kk & 3); }
+__host__ __device__ __forceinline__ size_t k_offset(int pos, int dim, int hd, int elem_size) {
+  return (size_t)(pos / 32) * 32 * hd + tiled_offset(kv_key_row(pos % 32), dim, hd, elem_size);
+}
+__host__ __device__ __forceinline__ size_t v_offset(int pos, int dim, int hd, int elem_size) {
+  return (size_t)(pos / 32) * 32 * hd + tiled_offset(dim, pos % 32, 32, elem_size);
+}
+
 // Activation matrices that feed a GEMM (normalised hidden state, attention output, SwiGLU output)
 // are stored chunk-major: [K / KC][Mcap][KC] with KC = 256 (bf16) or 128 (fp32) contraction
 // elements, so that the slice of all block rows a workgroup stages per step of the GEMM is one
@@ -129,6 +142,27 @@ __device__ __forceinline__ void store4(float *dst, float a, float b, float c, fl
   *reinterpret_cast<float4 *>(dst) = float4{a, b, c, d};
 }
 
+// Maximum / sum over the four lanes l, l^16, l^32, l^48 (one lane per 16-lane row of the wave); every
+// lane gets the result.  The gfx950 row-swap instructions do this in the vector ALU (checked on the
+// device: permlane16_swap(x, x) yields rows [x0 x0 x2 x2] and [x1 x1 x3 x3], permlane32_swap(x, x) the
+// two halves [lo lo] and [hi hi]); a shuffle would go through the LDS pipeline and its latency.
+__device__ __forceinline__ float rows_max(float x) {
+  const unsigned u = __float_as_uint(x);
+  const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const float y = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  const unsigned v = __float_as_uint(y);
+  const auto b = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float rows_sum(float x) {
+  const unsigned u = __float_as_uint(x);
+  const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const float y = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+  const unsigned v = __float_as_uint(y);
+  const auto b = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+  return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
 template <typename T> __device__ __forceinline__ float fast_exp(float x);
 template <> __device__ __forceinline__ float fast_exp<float>(float x) { return expf(x); }
 template <> __device__ __forceinline__ float fast_exp<bf16_t>(float x) { return __expf(x); }
@@ -150,8 +184,8 @@ struct GemmArgs {
   void *act;              // chunk-major [N/KC][Mcap][KC] T  (N = d_ffn)
   // EPI_QKV
   void *q;                // [H][Mcap][hd] T
-  void *kscr;             // this layer's [Hkv][Mcap][hd] T
-  void *vscr;             // this layer's [Hkv][Mcap/32][hd][32] T (tiles of 32 positions, transposed inside)
+  void *kscr;             // this layer's block keys, [Hkv][Mcap/32] tiles (k_offset)
+  void *vscr;             // this layer's block values, [Hkv][Mcap/32] tiles (v_offset)
   int H, Hkv, hd, Mcap, C, P;   // m = row*C + col sits at position P + col
   const float *rope_cos, *rope_sin;   // [Spad][hd/2]
   // EPI_UNEMBED
@@ -164,14 +198,14 @@ constexpr int kMaxResidualSplits = 8;
 
 struct AttnArgs {
   const void *q;          // [H][Mcap][hd]
-  const void *kcache;     // this layer's [Hkv][Spad][hd]
-  const void *vcache;     // this layer's [Hkv][Spad/32][hd][32]
-  const void *kscr;       // this layer's [Hkv][Mcap][hd]
-  const void *vscr;       // this layer's [Hkv][Mcap/32][hd][32]
-  float *part_o;          // [H][n_splits+1][Mcap][hd]
-  float *part_ml;         // [H][n_splits+1][Mcap][2]
+  const void *kcache;     // this layer's cached keys, [Hkv][Spad/32] tiles of 32 positions (k_offset)
+  const void *vcache;     // this layer's cached values, same tiling (v_offset)
+  const void *kscr;       // this layer's block keys, [Hkv][Mcap/32] tiles
+  const void *vscr;       // this layer's block values, [Hkv][Mcap/32] tiles
+  float *part_o;          // [H][n_splits][Mcap/16][hd/16][64 lanes][4]: output fragments as the registers hold them
+  float *part_ml;         // [H][n_splits][Mcap][2]
   void *out;              // chunk-major [H*hd/KC][Mcap][KC] T
-  int H, Hkv, Mcap, Spad, M, C, P, n_splits, span;
+  int H, Hkv, Mcap, Spad, M, C, P, n_splits;   // n_splits: workgroups that share a head's list of key tiles
   float scale;
 };
 
@@ -180,6 +214,7 @@ struct AttnArgs {
 void launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t s);
 int gemm_residual_splits(int dtype, int N, int K);
 void launch_attention(int dtype, int hd, const AttnArgs &a, hipStream_t s);
+int attention_splits(int dtype, int hd, int H, int M, int P, int max_splits);
 
 void launch_embed(int dtype, const void *tok_emb, const int32_t *hist, const int32_t *drafts, int32_t *block_tok,
                   float *h, int d, int M, int C, int w, int hist_base, int from_hist, hipStream_t s);

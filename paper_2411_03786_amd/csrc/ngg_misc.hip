@@ -509,9 +509,9 @@ __global__ __launch_bounds__(256) void commit_kernel(T *kcache, T *vcache, const
   T *vc = vcache + lh * hd * Spad;
   for (int i = threadIdx.x; i < n_new * hd; i += 256) {
     const int j = i / hd, dd = i - j * hd;
-    const int src = row * C + j, dst = P + j;            // values live in tiles of 32 positions: [pos/32][dim][32]
-    kc[(size_t)dst * hd + dd] = ks[(size_t)src * hd + dd];
-    vc[((size_t)(dst / 32) * hd + dd) * 32 + dst % 32] = vs[((size_t)(src / 32) * hd + dd) * 32 + src % 32];
+    const int src = row * C + j, dst = P + j;            // both live in tiles of 32 positions, in operand order
+    kc[k_offset(dst, dd, hd, (int)sizeof(T))] = ks[k_offset(src, dd, hd, (int)sizeof(T))];
+    vc[v_offset(dst, dd, hd, (int)sizeof(T))] = vs[v_offset(src, dd, hd, (int)sizeof(T))];
   }
   if (res && layer == 0 && hkv == 0)
     for (int i = threadIdx.x; i < n_new; i += 256) hist[P + 1 + i] = res[RES_NEWTOK + i];

@@ -281,6 +281,19 @@ def test_cfg2_small_bf16_lockstep():
     assert rep.tolerated_argmax <= 0.1 * positions
 
 
+@pytest.mark.parametrize("k,w", [(16, 6), (32, 8), (13, 4)])
+def test_bf16_blocks_of_more_than_64_rows(k, w):
+    """Blocks of 65, 112 and 288 rows on the small bf16 widths (3 layers): the 128-row GEMM tiles,
+    the eight-wave attention workgroups and, at 288 rows, several passes over the weights."""
+    desc = si.reduced_layers(si.MODELS["small"], 3)
+    run = dict(si.RUNS["cfg2"], prompt_len=333, k=k, w=w, k_ctx_max=k, q_min=1, q_max=3, n_gen=30)
+    w_, prompt, model, ctx = _setup(desc, run)
+    rep = lockstep_run(ctx, model, prompt, 30, run, TOL["bf16"], max_steps=4)
+    ctx.close()
+    print("wide block:", k, w, rep)
+    assert rep.max_rel_logit_err <= 2e-2
+
+
 def test_7b_width_two_layer_twin_bf16_lockstep():
     """7B widths (d 4096, 32 heads of 128, FFN 14336, vocab 32000) with 2 layers so
     the oracle can run it: prompt 2048, k=10, w=5 -- the launch shapes of config 3."""
