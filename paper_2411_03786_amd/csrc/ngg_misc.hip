@@ -71,16 +71,36 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float *__restrict__ h, con
       gn[j] = float4{to_f32(gp[0]), to_f32(gp[1]), to_f32(gp[2]), to_f32(gp[3])};
     }
   }
-  for (int s = 0; s < n_part; ++s) {                      // residual add: partials in split order
-    float4 p[J];
+  if constexpr (J > 4) {                                  // wide rows: too many registers to fetch every split at once
+    for (int s = 0; s < n_part; ++s) {
 #pragma unroll
-    for (int j = 0; j < J; ++j) {
-      const int i4 = threadIdx.x + 256 * j;
-      p[j] = float4{0.f, 0.f, 0.f, 0.f};
-      if (i4 < d4) p[j] = *reinterpret_cast<const float4 *>(hpart + (size_t)s * part_stride + (size_t)m * d + 4 * i4);
+      for (int j = 0; j < J; ++j) {
+        const int i4 = threadIdx.x + 256 * j;
+        if (i4 < d4) {
+          const float4 p = *reinterpret_cast<const float4 *>(hpart + (size_t)s * part_stride + (size_t)m * d + 4 * i4);
+          v[j].x += p.x; v[j].y += p.y; v[j].z += p.z; v[j].w += p.w;
+        }
+      }
+    }
+  } else if (n_part > 0) {                                // residual add: partials in split order.  All splits
+    float4 p[kMaxResidualSplits][J];                      // are fetched at once (a loop over n_part would pay
+#pragma unroll                                            // one memory round trip per split); surplus slots
+    for (int s = 0; s < kMaxResidualSplits; ++s) {        // repeat the last split and are not added
+      const int sc = s < n_part ? s : n_part - 1;
+#pragma unroll
+      for (int j = 0; j < J; ++j) {
+        const int i4 = threadIdx.x + 256 * j;
+        p[s][j] = float4{0.f, 0.f, 0.f, 0.f};
+        if (i4 < d4) p[s][j] = *reinterpret_cast<const float4 *>(hpart + (size_t)sc * part_stride + (size_t)m * d + 4 * i4);
+      }
     }
 #pragma unroll
-    for (int j = 0; j < J; ++j) { v[j].x += p[j].x; v[j].y += p[j].y; v[j].z += p[j].z; v[j].w += p[j].w; }
+    for (int s = 0; s < kMaxResidualSplits; ++s) {
+      if (s < n_part) {
+#pragma unroll
+        for (int j = 0; j < J; ++j) { v[j].x += p[s][j].x; v[j].y += p[s][j].y; v[j].z += p[s][j].z; v[j].w += p[s][j].w; }
+      }
+    }
   }
   float ss = 0.0f;
 #pragma unroll
