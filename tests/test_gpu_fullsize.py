@@ -1,0 +1,123 @@
+"""The full 7B-shaped configuration (32 layers, prompt 2048, k=10, w=5) in the launch configuration
+bench.py times.  The oracle cannot run 32 layers of this width in test time, so this file checks
+what it can compute one by one at full size (bigram scores and ranks over the whole vocabulary,
+the next1 chain, the context matcher, acceptance and winner from the GPU's own greedy grid) and
+properties that hold at any size (repeatability, rows that share a prefix agree, a committed cache
+equals a fresh prefill of the longer sequence, speculative tokens equal plain greedy tokens up to
+the logit tolerance).  The layer arithmetic at these widths is compared with the oracle element by
+element in test_gpu_parity.py on the 2-layer twin."""
+import types
+
+import numpy as np
+import pytest
+
+import synth_inputs as si
+import oracle
+import paper_2411_03786_amd as ngg
+from lockstep import check_drafts, Report, TOL
+
+pytestmark = pytest.mark.gpu
+
+N_STEPS = 6
+
+
+@pytest.fixture(scope="module")
+def full():
+    import torch
+    run = si.RUNS["cfg3"]
+    m = si.MODELS[run["model"]]
+    dev_w = si.make_weights_device(m, seed=0)
+    prompt = si.make_prompt(run, m["vocab"], seed=1)
+    ctx = ngg.Context(m, dev_w, max_seq=len(prompt) + 256, max_k=run["k"], max_w=run["w"])
+    tok_emb = dev_w["tok_emb"].float().cpu().numpy()
+    unemb = dev_w["unemb"].float().cpu().numpy()
+    yield types.SimpleNamespace(run=run, m=m, dev_w=dev_w, prompt=prompt, ctx=ctx,
+                                bigram=oracle.Bigram(tok_emb, unemb), torch=torch)
+    ctx.close()
+
+
+def _margin_ok(logits, a, b, tol):
+    """Tokens a and b are a near-tie at this position: their logits differ by less than tol * scale."""
+    return abs(float(logits[a]) - float(logits[b])) < tol * float(np.max(np.abs(logits)))
+
+
+def test_full_size_steps_against_what_the_oracle_can_compute(full):
+    run, ctx, tol = full.run, full.ctx, TOL["bf16"]
+    k, w = run["k"], run["w"]
+    rep = Report()
+    ctx.prefill(full.prompt)
+    hist = list(ctx.get_tokens())
+    assert hist[:-1] == list(full.prompt) and 0 <= hist[-1] < full.m["vocab"]
+    spec_logits = []                                        # (position, logits of the committed row) for the last test
+    for step in range(N_STEPS):
+        st = types.SimpleNamespace(tokens=list(ctx.get_tokens()))
+        g_drafts, g_src, g_nctx = ctx.build_drafts(run)
+        check_drafts(g_drafts, g_src, g_nctx, st, full.bigram, run, tol, rep)      # matcher exact, bigram ranks within margin
+        res = ctx.verify_step(None, k, w, want_logits=True)
+        again = ctx.verify_step(None, k, w, want_logits=True)                      # same state: bit-identical
+        assert np.array_equal(res["logits"], again["logits"]) and np.array_equal(res["greedy"], again["greedy"])
+        lg = res["logits"]
+        assert np.all(np.isfinite(lg))
+        # greedy grid is the argmax of the logits the same call returns (ties to the lowest id)
+        assert np.array_equal(res["greedy"], np.argmax(lg, axis=-1))
+        # column 0 holds the same token at the same position in every row; rows that share a draft
+        # prefix see the same inputs up to that column (winner-tie reading): logits agree closely
+        scale = np.max(np.abs(lg), axis=-1)
+        for r in range(1, k):
+            same = 0
+            while same < w and g_drafts[r, same] == g_drafts[0, same]:
+                same += 1
+            for j in range(same + 1):
+                assert np.max(np.abs(lg[r, j] - lg[0, j])) <= 2e-3 * scale[0, j], (step, r, j)
+        # integer work on the GPU's own greedy grid: exact
+        a = oracle.accept_lengths(g_drafts, res["greedy"])
+        assert np.array_equal(res["accept_len"], a)
+        win, n_acc = oracle.select_winner(a)
+        assert (res["winner"], res["n_accept"], res["n_new"]) == (win, n_acc, n_acc + 1)
+        new = [int(t) for t in g_drafts[win, :n_acc]] + [int(res["greedy"][win, n_acc])]
+        assert list(res["new_tokens"]) == new
+        for j in range(n_acc + 1):
+            spec_logits.append(lg[win, j].copy())
+        assert ctx.commit() == len(new)
+        assert list(ctx.get_tokens()) == st.tokens + new
+        rep.steps += 1
+    print("full size:", rep)
+    full.spec_tokens = list(ctx.get_tokens())
+    full.spec_logits = spec_logits
+
+
+def test_committed_cache_equals_fresh_prefill_and_plain_greedy_agrees(full):
+    """A second context prefilled with prompt + the tokens committed above must give the same next
+    logits as the first one (whose cache was filled by commits of winner rows), and plain greedy
+    decoding from the prompt must produce the speculative run's tokens up to a near-tie."""
+    assert hasattr(full, "spec_tokens"), "runs after the step test"
+    tol = TOL["bf16"]
+    run, ctx = full.run, full.ctx
+    n_prompt = len(full.prompt)
+    ctx2 = ngg.Context(full.m, full.dev_w, max_seq=n_prompt + 256, max_k=1, max_w=0)
+    try:
+        # (1) cache consistency: same history, one cache from commits, one from prefill
+        hist = full.spec_tokens
+        ctx2.prefill(hist[:-1])
+        a = ctx.verify_step(None, 1, 0, want_logits=True)["logits"][0, 0]
+        ctx2_hist = list(ctx2.get_tokens())
+        b_first = ctx2_hist[-1]                     # greedy token after hist[:-1]: must be hist[-1] or a near-tie of it
+        b = None
+        if b_first == hist[-1]:
+            b = ctx2.verify_step(None, 1, 0, want_logits=True)["logits"][0, 0]
+            assert np.max(np.abs(a - b)) <= tol * np.max(np.abs(a))
+        else:
+            assert _margin_ok(full.spec_logits[len(hist) - n_prompt - 2], b_first, hist[-1], tol)
+        # (2) plain greedy from the prompt vs the speculative tokens
+        ctx2.prefill(full.prompt)
+        plain = list(ctx2.get_tokens())
+        assert plain[-1] == hist[n_prompt]          # same prefill kernels, same shapes: identical first token
+        for i in range(n_prompt + 1, len(hist)):
+            r = ctx2.verify_step(None, 1, 0, want_logits=True)
+            tok = int(r["new_tokens"][0])
+            if tok != hist[i]:
+                assert _margin_ok(r["logits"][0, 0], tok, hist[i], tol), f"position {i}: plain {tok} vs speculative {hist[i]}"
+                break                               # the runs part at a near-tie: nothing further to compare
+            ctx2.commit()
+    finally:
+        ctx2.close()

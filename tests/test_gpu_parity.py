@@ -304,3 +304,30 @@ def test_7b_width_two_layer_twin_bf16_lockstep():
     ctx.close()
     print("7b twin:", rep)
     assert rep.max_rel_logit_err <= 2e-2
+
+
+def test_7b_width_one_layer_twin_long_context_shape():
+    """The long-context configuration's draft shape (k=16, w=6: 112 block rows, query back-off q=3..1)
+    at 7B widths, one layer, prompt 1536: the 128-row GEMM tiles at K = 4096 / 14336 and the
+    two-query-group attention workgroups at head_dim 128."""
+    desc = si.reduced_layers(si.MODELS["7b"], 1)
+    run = dict(si.RUNS["cfg4"], prompt_len=1536, n_gen=20)
+    w, prompt, model, ctx = _setup(desc, run)
+    rep = lockstep_run(ctx, model, prompt, 20, run, TOL["bf16"], max_steps=3)
+    ctx.close()
+    print("7b one-layer twin, k=16 w=6:", rep)
+    assert rep.max_rel_logit_err <= 2e-2
+
+
+@pytest.mark.parametrize("k,w", [(10, 5), (32, 8)])
+def test_3b_width_one_layer_twin_large_vocabulary(k, w):
+    """The large-vocabulary configuration's widths (d 3072, 24 heads of 128, FFN 8192, vocab 128256),
+    one layer, prompt 512: bigram sweep, next1 table and argmax over 128256 rows; k=32, w=8 is the
+    largest block of its sweep (288 rows: three passes of 128-row tiles)."""
+    desc = si.reduced_layers(si.MODELS["3b"], 1)
+    run = dict(si.RUNS["cfg5"], prompt_len=512, k=k, w=w, k_ctx_max=k, n_gen=20)
+    w_, prompt, model, ctx = _setup(desc, run)
+    rep = lockstep_run(ctx, model, prompt, 20, run, TOL["bf16"], max_steps=2)
+    ctx.close()
+    print("3b one-layer twin:", k, w, rep)
+    assert rep.max_rel_logit_err <= 2e-2
