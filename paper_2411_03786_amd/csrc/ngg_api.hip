@@ -16,7 +16,7 @@ using namespace ngg;
 
 namespace {
 
-constexpr int kPrefillChunk = 64;
+constexpr int kPrefillChunk = 128;   // prompt tokens per forward pass of ngg_prefill: the largest GEMM row tile
 thread_local std::string g_create_error = "";
 
 struct ProfSpan { int cls; hipEvent_t e0, e1; };

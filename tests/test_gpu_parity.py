@@ -104,7 +104,7 @@ def test_block_shapes_including_more_than_64_rows(tiny, k, w):
     assert rep.tolerated_argmax == 0 and rep.max_rel_logit_err <= 1e-4
 
 
-@pytest.mark.parametrize("n_prompt", [1, 2, 63, 64, 65, 130])
+@pytest.mark.parametrize("n_prompt", [1, 2, 63, 64, 65, 127, 128, 129, 250])
 def test_prefill_chunk_boundaries(tiny, n_prompt):
     desc, run, _, _, model, ctx = tiny
     prompt = si.prompt_spans(desc["vocab"], n_prompt, 0.5, seed=7)
