@@ -148,6 +148,25 @@ ngg_status ngg_commit(ngg_ctx *ctx, int32_t max_new, int32_t *n_committed);
 ngg_status ngg_greedy_decode(ngg_ctx *ctx, const int32_t *prompt, int32_t n_prompt, int32_t n_gen,
                              const ngg_draft_cfg *cfg, int32_t *out_tokens, ngg_stats *stats);
 
+/* The paper's own model bigram as a precomputed table (Section 4.1, "Model
+ * bigram"; Appendix A builds the same lookup): p_M(. | x) is the next-token
+ * distribution of the WHOLE model on the one-token context x.  For every
+ * vocabulary entry x the library runs the decoder on [x] (Mcap contexts per
+ * pass, each attending to itself only, position 0) and keeps the top_k token
+ * ids by (logit desc, id asc) in a device table [vocab][top_k]; column 0 is
+ * the chained extension's lookup ("Extensions to (k, w) ... can also be stored
+ * as a O(1) lookup table").  Costs vocab / Mcap model calls, once.  Requires
+ * max_k <= top_k <= min(64, vocab).  Leaves the committed state as it was; a
+ * pending verify call can no longer be committed (NGG_ESTATE from ngg_commit). */
+ngg_status ngg_bigram_table_build(ngg_ctx *ctx, int32_t top_k);
+
+/* Where the bigram rows of ngg_build_drafts come from: NGG_BIGRAM_DIRECT (the
+ * default: one sweep of <unemb[v], tok_emb[x_last]> per step, chained through
+ * next1) or NGG_BIGRAM_TABLE (two lookups in the table above; NGG_ESTATE if it
+ * was not built).  The choice changes the drafts, never the committed tokens. */
+enum { NGG_BIGRAM_DIRECT = 0, NGG_BIGRAM_TABLE = 1 };
+ngg_status ngg_bigram_source(ngg_ctx *ctx, int32_t source);
+
 /* Committed token history: copies min(n, cap) tokens to dst (HOST), n to *n. */
 ngg_status ngg_get_tokens(const ngg_ctx *ctx, int32_t *dst, int32_t cap, int32_t *n);
 

@@ -105,6 +105,25 @@ class Bigram:
         return out
 
 
+class ModelBigram(Bigram):
+    """The paper's own bigram (Section 4.1, "Model bigram"): p_M(. | x) is the
+    next-token distribution of the WHOLE model on the one-token context x, so
+    scores(x) are the model's logits after running it on [x].  `logits_of(x)`
+    is that model call (e.g. lambda x: model.forward_full([x])[-1]); ranking,
+    chaining and the lazily filled top-1 lookup are those of Bigram."""
+
+    def __init__(self, logits_of):
+        self.logits_of = logits_of
+        self._scores = {}
+        self._next1 = {}
+
+    def scores(self, x: int):
+        x = int(x)
+        if x not in self._scores:
+            self._scores[x] = np.asarray(self.logits_of(x), dtype=np.float64)
+        return self._scores[x]
+
+
 # -- mixed strategy (Section 4.3) -----------------------------------------------
 
 def build_drafts(tokens, bigram: Bigram, k: int, w: int, k_ctx_max: int, q_min: int, q_max: int):

@@ -33,6 +33,9 @@ struct ngg_ctx {
   // device buffers
   int32_t *hist = nullptr, *drafts = nullptr, *block_tok = nullptr, *res = nullptr, *next1 = nullptr;
   int32_t *mlist = nullptr, *reps = nullptr, *ctx_rows = nullptr, *n_ctx = nullptr;
+  int32_t *bg_table = nullptr, *bg_tok = nullptr;   // full-model bigram table [vocab][bg_K]; token ids of one build pass
+  int bg_K = 0;
+  bool bg_use = false;             // bigram rows from the table instead of the U.E[x] sweep
   int8_t *row_src = nullptr;
   void *kcache = nullptr, *vcache = nullptr, *kscr = nullptr, *vscr = nullptr;
   float *h = nullptr, *hpart = nullptr, *part_o = nullptr, *part_ml = nullptr, *pmax_val = nullptr, *z = nullptr, *logits = nullptr;
@@ -114,7 +117,8 @@ ngg_status dev_alloc(ngg_ctx *c, P **p, size_t bytes, bool zero) {
 // One forward over a block of R rows x C columns sitting at positions P .. P+C-1 on a cached
 // context of P tokens (Section 3).  Leaves this block's keys/values in the scratch, and, when
 // `unembed` is set, the per-tile argmax partials (and optional logits) of every block position.
-ngg_status forward(ngg_ctx *c, int R, int C, int P, bool from_hist, int w, bool unembed, bool want_logits) {
+ngg_status forward(ngg_ctx *c, int R, int C, int P, bool from_hist, int w, bool unembed, bool want_logits,
+                   const int32_t *tok_src = nullptr) {   // tok_src: from_hist reads its tokens here instead of the history
   const ngg_model_desc &d = c->d;
   const int M = R * C;
   const int dt = d.dtype;
@@ -122,7 +126,8 @@ ngg_status forward(ngg_ctx *c, int R, int C, int P, bool from_hist, int w, bool 
   hipStream_t s = c->stream;
   {
     ProfScope ps(c, NGG_PROF_OTHER);
-    launch_embed(dt, c->w.tok_emb, c->hist, c->drafts, c->block_tok, c->h, d.d_model, M, C, w, P, from_hist ? 1 : 0, s);
+    launch_embed(dt, c->w.tok_emb, tok_src ? tok_src : c->hist, c->drafts, c->block_tok, c->h, d.d_model, M, C, w,
+                 tok_src ? 0 : P, from_hist ? 1 : 0, s);
   }
   const int n_splits = attention_splits(dt, d.head_dim, d.n_heads, M, P, c->max_splits);
   const size_t part_stride = (size_t)c->Mcap * d.d_model;
@@ -265,7 +270,7 @@ ngg_status ngg_destroy(ngg_ctx *c) {
   (void)hipStreamSynchronize(c->stream);
   void *bufs[] = {c->hist, c->drafts, c->block_tok, c->res, c->next1, c->mlist, c->reps, c->ctx_rows, c->n_ctx,
                   c->row_src, c->hpart, c->wtiled, c->cand_val, c->cand_idx, c->kcache, c->vcache, c->kscr, c->vscr, c->h, c->part_o, c->part_ml, c->pmax_val, c->z,
-                  c->logits, c->rope_cos, c->rope_sin, c->pmax_idx, c->xn, c->q, c->attn, c->act};
+                  c->logits, c->rope_cos, c->rope_sin, c->pmax_idx, c->xn, c->q, c->attn, c->act, c->bg_table, c->bg_tok};
   for (void *b : bufs)
     if (b) (void)hipFree(b);
   if (c->res_host) (void)hipHostFree(c->res_host);
@@ -423,6 +428,7 @@ ngg_status ngg_build_drafts(ngg_ctx *c, const ngg_draft_cfg *cfg, int32_t *draft
   if (cfg->k_ctx_max < 0 || cfg->q_min < 1 || cfg->q_max < cfg->q_min || cfg->q_max > 64)
     return fail(c, NGG_EINVAL, "ngg_build_drafts: need k_ctx_max >= 0 and 1 <= q_min <= q_max <= 64");
   if (cfg->k > c->d.vocab) return fail(c, NGG_EINVAL, "ngg_build_drafts: k exceeds the vocabulary");
+  if (c->bg_use && cfg->k > c->bg_K) return fail(c, NGG_ECAPACITY, "ngg_build_drafts: k=%d exceeds the %d ranks kept in the bigram table", cfg->k, c->bg_K);
   {
     ProfScope ps(c, NGG_PROF_DRAFTS);
     DraftArgs a{};
@@ -430,6 +436,7 @@ ngg_status ngg_build_drafts(ngg_ctx *c, const ngg_draft_cfg *cfg, int32_t *draft
     a.mlist = c->mlist; a.reps = c->reps; a.ctx_rows = c->ctx_rows; a.n_ctx = c->n_ctx;
     a.tok_emb = c->w.tok_emb; a.unemb_t = c->unemb_t; a.d = c->d.d_model; a.vocab = c->d.vocab; a.z = c->z; a.cand_val = c->cand_val; a.cand_idx = c->cand_idx; a.next1 = c->next1;
     a.drafts = c->drafts; a.row_src = c->row_src;
+    if (c->bg_use) { a.bg_table = c->bg_table; a.bg_K = c->bg_K; }
     launch_build_drafts(c->d.dtype, a, c->stream);
   }
   NGG_HIP(c, hipGetLastError());
@@ -588,6 +595,42 @@ ngg_status ngg_profile_read(ngg_ctx *c, double *ms, int64_t *launches) {
   return NGG_OK;
 }
 
+ngg_status ngg_bigram_table_build(ngg_ctx *c, int32_t top_k) {
+  if (!c) return NGG_EINVAL;
+  const ngg_model_desc &d = c->d;
+  if (top_k < 1 || top_k > 64 || top_k > d.vocab) return fail(c, NGG_EINVAL, "ngg_bigram_table_build: need 1 <= top_k <= min(64, vocab)");
+  if (top_k < d.max_k) return fail(c, NGG_EINVAL, "ngg_bigram_table_build: top_k=%d is below max_k=%d (a step may ask for max_k bigram rows)", top_k, d.max_k);
+  if (c->bg_table) { (void)hipFree(c->bg_table); c->bg_table = nullptr; c->bg_use = false; }
+  ngg_status st = dev_alloc(c, &c->bg_table, (size_t)d.vocab * top_k * 4, true);
+  if (st != NGG_OK) return st;
+  if (!c->bg_tok) { st = dev_alloc(c, &c->bg_tok, (size_t)c->Mcap * 4, true); if (st != NGG_OK) return st; }
+  st = ensure_logits(c);
+  if (st != NGG_OK) return st;
+  c->bg_K = top_k;
+  // p_M(. | x) for every token x: the whole model on the one-token context x.  Mcap contexts per
+  // pass: a block of Mcap rows of width 1 on an empty cache (a token attends to itself only).
+  c->have_verify = false;                              // the block scratch no longer holds the last verify call
+  for (int x0 = 0; x0 < d.vocab; x0 += c->Mcap) {
+    const int M = std::min(c->Mcap, d.vocab - x0);
+    launch_iota(c->bg_tok, x0, M, c->stream);
+    st = forward(c, M, 1, 0, true, 0, true, true, c->bg_tok);
+    if (st != NGG_OK) return st;
+    launch_row_topk(c->logits, M, d.vocab, top_k, c->bg_table + (size_t)x0 * top_k, c->stream);
+  }
+  NGG_HIP(c, hipGetLastError());
+  NGG_HIP(c, hipStreamSynchronize(c->stream));
+  return NGG_OK;
+}
+
+ngg_status ngg_bigram_source(ngg_ctx *c, int32_t source) {
+  if (!c) return NGG_EINVAL;
+  if (source != NGG_BIGRAM_DIRECT && source != NGG_BIGRAM_TABLE) return fail(c, NGG_EINVAL, "ngg_bigram_source: unknown source %d", source);
+  if (source == NGG_BIGRAM_TABLE && !c->bg_table) return fail(c, NGG_ESTATE, "ngg_bigram_source: no table (call ngg_bigram_table_build first)");
+  c->bg_use = source == NGG_BIGRAM_TABLE;
+  c->drafts_on_device = false;
+  return NGG_OK;
+}
+
 ngg_status ngg_debug_peek(ngg_ctx *c, const char *name, void *dst, int64_t cap, int64_t *bytes, int32_t *stride) {
   if (!c || !name || !bytes) return NGG_EINVAL;
   const ngg_model_desc &d = c->d;
@@ -598,6 +641,7 @@ ngg_status ngg_debug_peek(ngg_ctx *c, const char *name, void *dst, int64_t cap, 
   if (nm == "h") { src = c->h; sz = (size_t)c->Mcap * d.d_model * 4; }
   else if (nm == "z") { src = c->z; sz = (size_t)d.vocab * 4; }
   else if (nm == "next1") { src = c->next1; sz = (size_t)d.vocab * 4; }
+  else if (nm == "bg_table" && c->bg_table) { src = c->bg_table; sz = (size_t)d.vocab * c->bg_K * 4; }
   else if (nm == "hist") { src = c->hist; sz = (size_t)c->Spad * 4; }
   else if (nm == "block_tok") { src = c->block_tok; sz = (size_t)c->Mcap * 4; }
   else if (nm == "kcache") { src = c->kcache; sz = kv; }

@@ -238,10 +238,15 @@ struct DraftArgs {
   float *cand_val;        // [256][32] per-workgroup top-k candidates of the bigram sweep
   int *cand_idx;
   const int32_t *next1;   // [vocab]
+  const int32_t *bg_table; // [vocab][bg_K] full-model bigram table, or null: bigram rows come from the sweep
+  int bg_K;
   int32_t *drafts;        // [k][w]
   int8_t *row_src;        // [k]
 };
 void launch_build_drafts(int dtype, const DraftArgs &a, hipStream_t s);
+// out[m][0..K) = ids of the K largest logits of row m by (value desc, id asc); logits [M][V] fp32
+void launch_row_topk(const float *logits, int M, int V, int K, int32_t *out, hipStream_t s);
+void launch_iota(int32_t *dst, int first, int n, hipStream_t s);
 // copies src [N][K] (row-major) into rows row0 .. row0+N of the operand-order matrix dst
 void launch_tile_weights(int dtype, const void *src, void *dst, int N, int K, int row0, hipStream_t s);
 

@@ -418,8 +418,30 @@ __global__ __launch_bounds__(1024) void topk_assemble_kernel(const DraftArgs a) 
   }
 }
 
+// The same assembly when the bigram comes from the precomputed full-model table (Section 4.1:
+// the bigram and its extension are O(1) lookups): row i starts with the table's i-th ranked
+// successor of the last token and continues with each token's top-ranked successor.
+__global__ __launch_bounds__(64) void table_assemble_kernel(const DraftArgs a) {
+  const int r = threadIdx.x;
+  const int n_ctx = *a.n_ctx;
+  if (r >= a.k) return;
+  if (a.w < 1) { a.row_src[r] = 1; return; }
+  if (r < n_ctx) {
+    for (int t = 0; t < a.w; ++t) a.drafts[r * a.w + t] = a.ctx_rows[r * a.w + t];
+    a.row_src[r] = 0;
+  } else {
+    int t0 = a.bg_table[(size_t)a.hist[a.n - 1] * a.bg_K + (r - n_ctx)];
+    for (int t = 0; t < a.w; ++t) { a.drafts[r * a.w + t] = t0; t0 = a.bg_table[(size_t)t0 * a.bg_K]; }
+    a.row_src[r] = 1;
+  }
+}
+
 void launch_build_drafts(int dtype, const DraftArgs &a, hipStream_t s) {
   hipLaunchKernelGGL(ctx_match_kernel, dim3(1), dim3(1024), 0, s, a);
+  if (a.bg_table) {
+    hipLaunchKernelGGL(table_assemble_kernel, dim3(1), dim3(64), 0, s, a);
+    return;
+  }
   if (a.w >= 1) {
     const int n_groups = a.vocab / 16, gpb = (n_groups + kGemvBlocks - 1) / kGemvBlocks;
     const size_t lds = ((size_t)a.d + (size_t)gpb * 16) * sizeof(float);
@@ -509,6 +531,64 @@ void launch_argmax_accept(const float *pmax_val, const int *pmax_idx, int tiles,
 void launch_next1_finish(const float *pmax_val, const int *pmax_idx, int tiles, int Mcap, int M, int32_t *next1_out,
                          hipStream_t s) {
   hipLaunchKernelGGL(argmax_reduce_kernel, dim3(M), dim3(256), 0, s, pmax_val, pmax_idx, tiles, Mcap, next1_out);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Top-K token ids of each logits row by (value desc, id asc): K rounds of a workgroup-wide
+// selection, round i taking the best entry that ranks after round i-1's pick.  Used once per
+// vocabulary entry when the full-model bigram table is built, never on the step.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void row_topk_kernel(const float *__restrict__ logits, int V, int K, int32_t *__restrict__ out) {
+  __shared__ float wv[4];
+  __shared__ int wi[4];
+  __shared__ float sel_v;
+  __shared__ int sel_i;
+  const int m = blockIdx.x, tid = threadIdx.x;
+  const float *row = logits + (size_t)m * V;
+  float last_v = 0.0f;
+  int last_i = -1;
+  for (int r = 0; r < K; ++r) {
+    float bv = kNegBig;
+    int bi = 0x7fffffff;
+    for (int i = tid; i < V; i += 256) {
+      const float v = row[i];
+      const bool in = r == 0 || ranks_before(last_v, last_i, v, i);
+      if (in && ranks_before(v, i, bv, bi)) { bv = v; bi = i; }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+      const float ov = __shfl_xor(bv, off);
+      const int oi = __shfl_xor(bi, off);
+      if (ranks_before(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+    }
+    if ((tid & 63) == 0) { wv[tid >> 6] = bv; wi[tid >> 6] = bi; }
+    __syncthreads();
+    if (tid == 0) {
+      float fv = wv[0];
+      int fi = wi[0];
+      for (int t = 1; t < 4; ++t)
+        if (ranks_before(wv[t], wi[t], fv, fi)) { fv = wv[t]; fi = wi[t]; }
+      sel_v = fv; sel_i = fi;
+      out[(size_t)m * K + r] = fi;
+    }
+    __syncthreads();
+    last_v = sel_v;
+    last_i = sel_i;
+    __syncthreads();
+  }
+}
+
+void launch_row_topk(const float *logits, int M, int V, int K, int32_t *out, hipStream_t s) {
+  hipLaunchKernelGGL(row_topk_kernel, dim3(M), dim3(256), 0, s, logits, V, K, out);
+}
+
+__global__ void iota_kernel(int32_t *dst, int first, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) dst[i] = first + i;
+}
+
+void launch_iota(int32_t *dst, int first, int n, hipStream_t s) {
+  hipLaunchKernelGGL(iota_kernel, dim3((n + 255) / 256), dim3(256), 0, s, dst, first, n);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -64,11 +64,11 @@ def check_drafts(g_drafts, g_src, g_nctx, st, bigram, cfg, tol, rep):
             prev = g
 
 
-def run(ctx, model, prompt, n_gen, cfg, tol, check_logits=True, injected=None, max_steps=None):
+def run(ctx, model, prompt, n_gen, cfg, tol, check_logits=True, injected=None, max_steps=None, bigram=None):
     """Lock-step decode.  `injected(step, st) -> drafts or None` replaces the built
     drafts for some steps (coverage of every accepted length).  Returns a Report."""
     rep = Report()
-    bigram = oracle.Bigram(model.tok_emb, model.unemb)
+    bigram = bigram or oracle.Bigram(model.tok_emb, model.unemb)
     ctx.prefill(prompt)
     st = oracle.prefill(model, prompt)
     g_first = int(ctx.get_tokens()[-1])

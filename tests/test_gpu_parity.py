@@ -262,6 +262,68 @@ def test_damped_residual_variant_accepts_bigram_rows():
 
 
 # ---------------------------------------------------------------------------------------------
+# the paper's own bigram: the whole model on one-token contexts, as a precomputed table
+# ---------------------------------------------------------------------------------------------
+
+def _check_table_rows(table, mb, xs, tol):
+    """Rows of the GPU table against the oracle's ranking; ids may differ only at near-ties."""
+    K = table.shape[1]
+    swaps = 0
+    for x in xs:
+        z = mb.scores(int(x))
+        order = oracle.rank_ids(z, K)
+        for i in range(K):
+            g, o = int(table[x, i]), int(order[i])
+            if g != o:
+                assert abs(z[g] - z[o]) < tol * np.max(np.abs(z)), f"table[{x}][{i}]: GPU {g} vs oracle {o}"
+                swaps += 1
+    return swaps
+
+
+def test_full_model_bigram_table_fp32(tiny):
+    desc, run, _, prompt, model, ctx = tiny
+    with pytest.raises(ngg.NggError) as e:
+        ctx.bigram_source(1)                                   # no table yet
+    assert e.value.status == ngg.NGG_ESTATE
+    with pytest.raises(ngg.NggError) as e:
+        ctx.bigram_table_build(4)                              # fewer ranks than max_k rows
+    assert e.value.status == ngg.NGG_EINVAL
+    ctx.bigram_table_build(32)
+    table = ctx.debug_peek("bg_table", np.int32)[0].reshape(desc["vocab"], 32)
+    mb = oracle.ModelBigram(lambda x: model.forward_full([x])[-1])
+    assert _check_table_rows(table, mb, range(desc["vocab"]), TOL["f32"]) == 0     # every one-token context
+    ctx.bigram_source(1)
+    try:
+        rep = lockstep_run(ctx, model, prompt, 40, run, TOL["f32"], bigram=mb)
+        cfg = dict(k=16, w=6, k_ctx_max=4, q_min=1, q_max=3)
+        rep2 = lockstep_run(ctx, model, prompt, 20, cfg, TOL["f32"], bigram=mb, max_steps=4)
+    finally:
+        ctx.bigram_source(0)
+    print("table mode:", rep, rep2)
+    assert rep.tolerated_argmax == 0 and rep.tolerated_draft == 0 and rep2.tolerated_draft == 0
+    rep3 = lockstep_run(ctx, model, prompt, 12, run, TOL["f32"])                    # back on the direct path
+    assert rep3.tolerated_draft == 0
+
+
+def test_full_model_bigram_table_bf16():
+    """Small bf16 widths, 3 layers, vocabulary 32000: the table of all 32000 one-token contexts,
+    sampled rows against the oracle, then a few steps in table mode."""
+    desc = si.reduced_layers(si.MODELS["small"], 3)
+    run = dict(si.RUNS["cfg2"], prompt_len=200, n_gen=24)
+    w, prompt, model, ctx = _setup(desc, run)
+    ctx.bigram_table_build(run["k"])
+    table = ctx.debug_peek("bg_table", np.int32)[0].reshape(desc["vocab"], run["k"])
+    mb = oracle.ModelBigram(lambda x: model.forward_full([x])[-1])
+    xs = [0, 1, 31999] + [int(t) for t in np.random.default_rng(3).integers(0, desc["vocab"], 13)]
+    swaps = _check_table_rows(table, mb, xs, TOL["bf16"])
+    ctx.bigram_source(1)
+    rep = lockstep_run(ctx, model, prompt, 24, run, TOL["bf16"], bigram=mb, max_steps=4)
+    ctx.close()
+    print("bf16 table:", swaps, "near-tie swaps in", len(xs), "rows;", rep)
+    assert rep.max_rel_logit_err <= 2e-2
+
+
+# ---------------------------------------------------------------------------------------------
 # bf16 configurations
 # ---------------------------------------------------------------------------------------------
 

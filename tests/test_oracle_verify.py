@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 import synth_inputs as si
-from oracle import (Model, Bigram, prefill, verify_step, commit, accept_lengths, select_winner,
+from oracle import (Model, Bigram, ModelBigram, rank_ids, prefill, verify_step, commit, accept_lengths, select_winner,
                     greedy_plain, greedy_plain_cached, greedy_speculative, build_drafts)
 
 
@@ -133,6 +133,46 @@ def test_zero_output_projections_accept_the_whole_bigram_chain():
     assert list(res["accept_len"][1:]) == [0, 0, 0]               # ranks 2..4 start with a different token
     gen, stats = greedy_speculative(m, [10, 20, 30], 29, 4, 6, 0, 1, 1)
     assert stats["new_hist"][7] == stats["calls"] == 4            # 1 from prefill + 4 calls x 7 tokens
+
+
+def test_full_model_bigram_closed_form_and_ranks():
+    """Section 4.1's bigram is the whole model on a one-token context.  (1) With W_o = W_down = 0
+    and a random final gain g its scores have the closed form U . (g * E[x] / rms(E[x])): one key
+    means attention returns v, which the zero output projection discards.  (2) With gains of 1 the
+    scores are a positive multiple of the direct path's U . E[x], so both bigrams rank alike."""
+    desc = si.MODELS["tiny"]
+    w = si.make_weights(desc, seed=5, random_gains=True)
+    for lw in w["layers"]:
+        lw["wo"] = np.zeros_like(lw["wo"])
+        lw["w_down"] = np.zeros_like(lw["w_down"])
+    m = Model(desc, w)
+    mb = ModelBigram(lambda x: m.forward_full([x])[-1])
+    for x in (0, 7, 511):
+        e = np.asarray(w["tok_emb"][x], dtype=np.float64)
+        closed = np.asarray(w["unemb"], np.float64) @ (np.asarray(w["final_norm"], np.float64) * e /
+                                                       np.sqrt(np.mean(e * e) + desc["rms_eps"]))
+        assert np.allclose(mb.scores(x), closed, rtol=1e-12, atol=1e-12)
+        assert list(mb.topk(x, 5)) == list(rank_ids(closed, 5)) and mb.next1(x) == int(rank_ids(closed, 1)[0])
+    w1 = si.make_weights(desc, seed=5)
+    for lw in w1["layers"]:
+        lw["wo"] = np.zeros_like(lw["wo"])
+        lw["w_down"] = np.zeros_like(lw["w_down"])
+    m1 = Model(desc, w1)
+    mb1, direct = ModelBigram(lambda x: m1.forward_full([x])[-1]), Bigram(m1.tok_emb, m1.unemb)
+    for x in (3, 100):
+        assert list(mb1.topk(x, 16)) == list(direct.topk(x, 16))
+        assert mb1.rows(x, 3, 4) == direct.rows(x, 3, 4)
+
+
+def test_full_model_bigram_differs_from_direct_path_but_keeps_the_invariant(tiny):
+    """On a model with live layers the two bigrams draft differently; the committed tokens are
+    plain greedy either way (the method's invariant does not depend on the drafts)."""
+    desc, w, run, prompt, m, plain = tiny
+    mb = ModelBigram(lambda x: m.forward_full([x])[-1])
+    direct = Bigram(m.tok_emb, m.unemb)
+    assert any(list(mb.topk(x, 4)) != list(direct.topk(x, 4)) for x in range(0, 512, 37))
+    gen, stats = greedy_speculative(m, prompt, 24, run["k"], run["w"], run["k_ctx_max"], run["q_min"], run["q_max"], bigram=mb)
+    assert list(gen) == list(plain)
 
 
 def test_attention_cost_model_counts():
