@@ -243,12 +243,14 @@ __global__ __launch_bounds__(1024) void ctx_match_kernel(const DraftArgs a) {
 
 // ---------------------------------------------------------------------------------------------
 // Model bigram scores z[v] = <unemb[v], tok_emb[x_last]> (Section 4.1).  The output embedding is
-// read in operand order: a wave owns groups of 16 vocabulary rows, every load instruction is 1 KB
-// of contiguous memory, lane (i, g) accumulates row i over its quarter of every 32-element slice
-// and the four quarters are added by two shuffles.  fp32 accumulation.
+// read in operand order: a wave owns groups of 16 vocabulary rows and streams them as one flat
+// sequence of 1 KB fragment loads, a ring of 8 ahead; the contraction runs on MFMA with the
+// embedding of x_last as every column of the other operand (the matrix cores are idle anyway and
+// this keeps the vector ALU out of the way of the loads).  fp32 accumulation.
 // ---------------------------------------------------------------------------------------------
 constexpr int kGemvBlocks = 256;     // workgroups of the bigram sweep; each keeps its own top-k candidates
 constexpr int kCandStride = 32;      // candidate slots per workgroup (k <= 32)
+constexpr int kGemvRing = 8;
 
 __device__ __forceinline__ bool ranks_before(float v, int i, float ov, int oi) {   // (value desc, id asc)
   return v > ov || (v == ov && i < oi);
@@ -258,38 +260,51 @@ template <typename T>
 __global__ __launch_bounds__(256) void bigram_gemv_kernel(const T *tok_emb, const T *unemb_t, const int32_t *hist, int n,
                                                           int d, int vocab, int ksel, float *z, float *cand_val,
                                                           int *cand_idx) {
-  extern __shared__ float e[];                               // [d] embedding of x_last, then this block's scores
+  extern __shared__ __attribute__((aligned(16))) unsigned char gemv_smem[];
+  T *es = reinterpret_cast<T *>(gemv_smem);                  // [d] embedding of x_last
+  float *zs = reinterpret_cast<float *>(gemv_smem + (size_t)d * sizeof(T));   // this block's scores
   const int x = hist[n - 1];
-  for (int i = threadIdx.x; i < d; i += 256) e[i] = to_f32(tok_emb[(size_t)x * d + i]);
+  for (int i = threadIdx.x; i < d; i += 256) es[i] = tok_emb[(size_t)x * d + i];
   __syncthreads();
-  const int lane = threadIdx.x & 63, li = lane & 15, g = lane >> 4, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, li = lane & 15, g = lane >> 4;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n_steps = d / 32, n_groups = vocab / 16;
   const int gpb = (n_groups + gridDim.x - 1) / gridDim.x;   // 16-row groups per workgroup
   const int g0 = blockIdx.x * gpb, g1 = min(n_groups, g0 + gpb);
-  float *zs = e + d;                                         // [gpb * 16]
-  for (int grp = g0 + wave; grp < g1; grp += 4) {
-    const T *blk = tiled_block(unemb_t, grp, n_steps, lane);
-    float acc = 0.0f;
-    int s = 0;
-    for (; s + 4 <= n_steps; s += 4) {
-      Frag<T> f[4];
+  const int my_groups = g1 > g0 + wave ? (g1 - g0 - wave + 3) / 4 : 0;        // groups g0 + wave, + 4, ...
+  const int total = my_groups * n_steps;                    // this wave's fragment loads, as one sequence
+  int pg = 0, ps = 0;                                       // prefetch cursor: (group counter, step)
+  auto next_frag = [&]() {                                  // past the end it repeats an in-bounds load
+    const int grp = min(g0 + wave + 4 * pg, n_groups - 1);
+    const Frag<T> f = load_frag_tiled(tiled_block(unemb_t, grp, n_steps, lane) + (size_t)ps * 512);
+    if (pg < my_groups && ++ps == n_steps) { ps = 0; ++pg; }
+    return f;
+  };
+  Frag<T> ring[kGemvRing];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) f[u] = load_frag_tiled(blk + (size_t)(s + u) * 512);
+  for (int u = 0; u < kGemvRing; ++u) ring[u] = next_frag();
+  f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+  int s = 0, gi = 0;                                        // step inside the current group, group counter
+  for (int t0 = 0; t0 < total; t0 += kGemvRing) {
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
+    for (int u = 0; u < kGemvRing; ++u) {
+      if (t0 + u < total) {                                  // uniform per wave
+        mma(acc, ring[u], load_frag(es + s * 32 + g * 8));   // every column of the result is the same score
+        if (++s == n_steps) {                               // group done: column 0 holds its 16 scores
+          const int grp = g0 + wave + 4 * gi;
+          if (li == 0) {
 #pragma unroll
-        for (int t = 0; t < 8; ++t) acc += to_f32(f[u].v[t]) * e[(s + u) * 32 + g * 8 + t];
-    }
-    for (; s < n_steps; ++s) {
-      const Frag<T> f = load_frag_tiled(blk + (size_t)s * 512);
-#pragma unroll
-      for (int t = 0; t < 8; ++t) acc += to_f32(f.v[t]) * e[s * 32 + g * 8 + t];
-    }
-    acc += __shfl_xor(acc, 16);
-    acc += __shfl_xor(acc, 32);
-    if (g == 0) {
-      z[grp * 16 + li] = acc;
-      zs[(grp - g0) * 16 + li] = acc;
+            for (int r = 0; r < 4; ++r) {
+              z[grp * 16 + 4 * g + r] = acc[r];
+              zs[(grp - g0) * 16 + 4 * g + r] = acc[r];
+            }
+          }
+          acc = f32x4{0.f, 0.f, 0.f, 0.f};
+          s = 0;
+          ++gi;
+        }
+      }
+      ring[u] = next_frag();
     }
   }
   __syncthreads();
@@ -444,7 +459,7 @@ void launch_build_drafts(int dtype, const DraftArgs &a, hipStream_t s) {
   }
   if (a.w >= 1) {
     const int n_groups = a.vocab / 16, gpb = (n_groups + kGemvBlocks - 1) / kGemvBlocks;
-    const size_t lds = ((size_t)a.d + (size_t)gpb * 16) * sizeof(float);
+    const size_t lds = (size_t)a.d * (dtype == 1 ? 2 : 4) + (size_t)gpb * 16 * sizeof(float);
     if (dtype == 1)
       hipLaunchKernelGGL(bigram_gemv_kernel<bf16_t>, dim3(kGemvBlocks), dim3(256), lds, s, (const bf16_t *)a.tok_emb,
                          (const bf16_t *)a.unemb_t, a.hist, a.n, a.d, a.vocab, a.k, a.z, a.cand_val, a.cand_idx);
