@@ -239,12 +239,13 @@ ngg_status tile_all_weights(ngg_ctx *c) {
     const ngg_layer_weights &lw = c->layers[l];
     char *p = base + (size_t)l * e_layer * c->esize;
     char *qkv = p, *o = qkv + e_qkv * c->esize, *gu = o + e_o * c->esize, *down = gu + e_gu * c->esize;
-    launch_tile_weights(d.dtype, lw.wq, qkv, (int)dq, d.d_model, 0, c->stream);
-    launch_tile_weights(d.dtype, lw.wk, qkv, (int)dkv, d.d_model, (int)dq, c->stream);
-    launch_tile_weights(d.dtype, lw.wv, qkv, (int)dkv, d.d_model, (int)(dq + dkv), c->stream);
+    // q, k, v: every 16-row fragment holds 8 pairs (i, i + hd/2) of one head; gate/up: gate and up of 8 features
+    launch_tile_weights(d.dtype, lw.wq, qkv, (int)dq, d.d_model, 0, c->stream, 1, d.head_dim / 2);
+    launch_tile_weights(d.dtype, lw.wk, qkv, (int)dkv, d.d_model, (int)dq, c->stream, 1, d.head_dim / 2);
+    launch_tile_weights(d.dtype, lw.wv, qkv, (int)dkv, d.d_model, (int)(dq + dkv), c->stream, 1, d.head_dim / 2);
     launch_tile_weights(d.dtype, lw.wo, o, d.d_model, (int)dq, 0, c->stream);
-    launch_tile_weights(d.dtype, lw.w_gate, gu, d.d_ffn, d.d_model, 0, c->stream);
-    launch_tile_weights(d.dtype, lw.w_up, gu, d.d_ffn, d.d_model, d.d_ffn, c->stream);
+    launch_tile_weights(d.dtype, lw.w_gate, gu, d.d_ffn, d.d_model, 0, c->stream, 2);
+    launch_tile_weights(d.dtype, lw.w_up, gu, d.d_ffn, d.d_model, 0, c->stream, 3);
     launch_tile_weights(d.dtype, lw.w_down, down, d.d_model, d.d_ffn, 0, c->stream);
     c->lt[l] = {qkv, o, gu, down};
   }

@@ -19,12 +19,13 @@
 
 namespace ngg {
 
-template <typename T, int EPI, int FM, int WN, int WK, int RING>
+template <typename T, int EPI, int FM, int WN, int WK, int RING, int FN>
 __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArgs a) {
   constexpr int XD = FM > 4 ? 1 : 2;         // X register stages (chunks fetched ahead); one when the tile is 128 rows
   static_assert(WN * WK == 4 || WN * WK == 8, "four or eight waves per workgroup");
+  constexpr bool PAIRED = EPI == EPI_QKV || EPI == EPI_GATEUP;   // fragments that hold both halves of 8 output pairs
+  static_assert(PAIRED ? WN == 1 : FN == 2, "paired epilogues: one set of FN fragments per workgroup, waves split K");
   constexpr int NT = 64 * WN * WK;           // threads per workgroup
-  constexpr int FN = 2;
   constexpr int KC = KChunk<T>::value;
   constexpr int SPC = KC / 32;               // steps per chunk
   constexpr int SPW = SPC / WK;              // steps per wave per chunk
@@ -50,32 +51,22 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
   const bool group_live = group < n_groups;
   if (!group_live) group = n_groups - 1;     // idle waves still help staging X and hit every barrier
 
-  // ---- the two 16-row groups of W this wave owns (W is stored in operand order: see tile_weights) --
+  // ---- the 16-row fragments of W this wave owns (W is stored in operand order: see tile_weights) ----
+  // Residual and unembedding: group = 2 consecutive fragments.  q/k/v and gate/up: n_groups counts
+  // fragments, the workgroup owns FN consecutive ones, and each fragment holds rows 0..7 = the first
+  // members and rows 8..15 = the second members of 8 output pairs (rotary pairs (i, i + hd/2) of one
+  // head; gate and up of 8 FFN features), so one accumulator has both halves of every pair it needs.
   const int n_steps = K / 32;
-  const T *wblk[FN];                         // this lane's slice of the group's first 32-step block
-  int nbase[FN];
-  int head = 0, kind = 0;                    // EPI_QKV: kind 0 = q, 1 = k, 2 = v
-  if constexpr (EPI == EPI_QKV) {
-    const int tph = a.hd / 32;               // pair groups per head
-    const int hh = group / tph;              // head index over [q heads | k heads | v heads]
-    const int sub = group - hh * tph;
-    kind = hh < a.H ? 0 : (hh < a.H + a.Hkv ? 1 : 2);
-    head = kind == 0 ? hh : (kind == 1 ? hh - a.H : hh - a.H - a.Hkv);
+  const T *wblk[FN];                         // this lane's slice of the fragment's first 32-step block
+  int nbase[FN];                             // first output feature (residual, unembedding) / fragment index (paired)
+  bool frag_live[FN];
 #pragma unroll
-    for (int f = 0; f < FN; ++f) {
-      nbase[f] = f * (a.hd / 2) + sub * 16;  // element index inside the head: (i, i + hd/2) pairs
-      wblk[f] = tiled_block((const T *)a.W0, (hh * a.hd + nbase[f]) / 16, n_steps, lane);
-    }
-  } else if constexpr (EPI == EPI_GATEUP) {
-    nbase[0] = nbase[1] = group * 16;        // gate rows [0, N), up rows [N, 2N) of one tiled matrix
-    wblk[0] = tiled_block((const T *)a.W0, group, n_steps, lane);
-    wblk[1] = tiled_block((const T *)a.W0, a.N / 16 + group, n_steps, lane);
-  } else {
-#pragma unroll
-    for (int f = 0; f < FN; ++f) {
-      nbase[f] = (group * FN + f) * 16;
-      wblk[f] = tiled_block((const T *)a.W0, group * FN + f, n_steps, lane);
-    }
+  for (int f = 0; f < FN; ++f) {
+    int frag = PAIRED ? blockIdx.x * FN + f : group * FN + f;
+    frag_live[f] = PAIRED ? frag < n_groups : group_live;
+    if (PAIRED && !frag_live[f]) frag = n_groups - 1;      // the last workgroup repeats a fragment it does not store
+    nbase[f] = PAIRED ? frag : frag * 16;
+    wblk[f] = tiled_block((const T *)a.W0, frag, n_steps, lane);
   }
 
   // ---- this workgroup's range of chunks -----------------------------------------------------------
@@ -155,8 +146,87 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
     }
     __syncthreads();                                     // everyone is done with xs
 
+    // ---- q/k/v and gate/up: every wave hands its partial fragments over through LDS; wave wk then
+    //      sums items wk, wk + WK, ... of the FN x FM accumulator fragments (waves in the order 0 .. WK-1)
+    //      and runs their epilogue, one item at a time ------------------------------------------------------
+    if constexpr (PAIRED) {
+      // at most 4 column blocks of every fragment per round, so that the hand-over fits the LDS
+      constexpr int FMR = FM < 4 ? FM : 4, ROUNDS = FM / FMR;
+      float *red = reinterpret_cast<float *>(smem);      // [WK][FN*FMR][4][64]
+#pragma unroll
+      for (int rd = 0; rd < ROUNDS; ++rd) {
+      if (rd > 0) __syncthreads();                       // the previous round's items were all read
+#pragma unroll
+      for (int f = 0; f < FN; ++f)
+#pragma unroll
+        for (int fr = 0; fr < FMR; ++fr)
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            red[(((size_t)wk * FN * FMR + f * FMR + fr) * 4 + r) * 64 + lane] = acc[f][rd * FMR + fr][r];
+      __syncthreads();
+      for (int idx = wk; idx < FN * FMR; idx += WK) {
+        const int f = idx / FMR, fm = rd * FMR + (idx - f * FMR);
+        const int frag = blockIdx.x * FN + f;              // fragment index over the whole matrix
+        float v[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          v[r] = red[((size_t)idx * 4 + r) * 64 + lane];
+#pragma unroll
+          for (int o = 1; o < WK; ++o) v[r] += red[(((size_t)o * FN * FMR + idx) * 4 + r) * 64 + lane];
+        }
+        // lanes g < 2 hold rows 4g + r of the fragment (first members of the pairs), lanes g + 2 the
+        // second members of the same pairs
+        float x2[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) x2[r] = other_half(v[r]);
+        const int m = m0 + fm * 16 + li;
+        if (m < M && g < 2 && frag < n_groups) {
+          if constexpr (EPI == EPI_GATEUP) {
+            float o[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) o[r] = v[r] / (1.0f + expf(-v[r])) * x2[r];      // silu(gate) * up
+            store4((T *)a.act + act_offset<T>(m, frag * 8 + 4 * g, a.Mcap), o[0], o[1], o[2], o[3]);   // 4 features, one chunk
+          } else {
+            const int half = a.hd / 2, fph = a.hd / 16;    // fragments per head
+            const int hh = frag / fph, sub = frag - hh * fph;                 // head over [q heads | k heads | v heads]
+            const int kind = hh < a.H ? 0 : (hh < a.H + a.Hkv ? 1 : 2);
+            const int head = kind == 0 ? hh : (kind == 1 ? hh - a.H : hh - a.H - a.Hkv);
+            const int i0 = sub * 8 + 4 * g;                // dims i0 .. i0+3 and their partners i0 + half ..
+            if (kind < 2) {                                // rotary embedding on q and k
+              const int pos = a.P + (m % a.C);
+              const float *cs = a.rope_cos + (size_t)pos * half + i0;
+              const float *sn = a.rope_sin + (size_t)pos * half + i0;
+              float lo[4], hi[4];
+#pragma unroll
+              for (int r = 0; r < 4; ++r) {
+                lo[r] = v[r] * cs[r] - x2[r] * sn[r];
+                hi[r] = x2[r] * cs[r] + v[r] * sn[r];
+              }
+              if (kind == 0) {
+                T *dst = (T *)a.q + ((size_t)head * a.Mcap + m) * a.hd + i0;
+                store4(dst, lo[0], lo[1], lo[2], lo[3]);
+                store4(dst + half, hi[0], hi[1], hi[2], hi[3]);
+              } else {                                     // keys: tiles of 32 block positions in operand order
+                T *kh = (T *)a.kscr + (size_t)head * a.Mcap * a.hd;
+                store4(kh + k_offset(m, i0, a.hd, (int)sizeof(T)), lo[0], lo[1], lo[2], lo[3]);
+                store4(kh + k_offset(m, i0 + half, a.hd, (int)sizeof(T)), hi[0], hi[1], hi[2], hi[3]);
+              }
+            } else {                                       // values: the transposed tiles
+              T *vh = (T *)a.vscr + (size_t)head * a.Mcap * a.hd;
+#pragma unroll
+              for (int r = 0; r < 4; ++r) {
+                vh[v_offset(m, i0 + r, a.hd, (int)sizeof(T))] = from_f32<T>(v[r]);
+                vh[v_offset(m, i0 + half + r, a.hd, (int)sizeof(T))] = from_f32<T>(x2[r]);
+              }
+            }
+          }
+        }
+      }
+      }
+    }
+
     // ---- sum the WK waves that share a wn: wave (wn, 0) adds (wn, 1) .. (wn, WK-1) in that order ---
-    if constexpr (WK > 1) {
+    if constexpr (!PAIRED && WK > 1) {
       float *red = reinterpret_cast<float *>(smem);      // [(WK-1)][WN][FN*FM*4][64]
       if (wk > 0) {
         float *dst = red + (size_t)((wk - 1) * WN + wn) * (FN * FM * 4 * 64);
@@ -183,7 +253,7 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
 
     // ---- epilogue, waves (wn, 0): lane holds, per group f and column block fm, column
     //      m = m0 + fm*16 + li and output features nbase[f] + 4g .. +4 -----------------------------------
-    if (wk == 0 && group_live) {
+    if (!PAIRED && wk == 0 && group_live) {
 #pragma unroll
       for (int fm = 0; fm < FM; ++fm) {
         const int m = m0 + fm * 16 + li;
@@ -195,49 +265,6 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
             for (int f = 0; f < FN; ++f)
               *reinterpret_cast<float4 *>(dst + nbase[f] + 4 * g) =
                   float4{acc[f][fm][0], acc[f][fm][1], acc[f][fm][2], acc[f][fm][3]};
-          }
-        } else if constexpr (EPI == EPI_GATEUP) {
-          if (live) {
-            T *p = (T *)a.act + act_offset<T>(m, nbase[0] + 4 * g, a.Mcap);   // 4 features stay inside one chunk
-            float o[4];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              const float gt = acc[0][fm][r], up = acc[1][fm][r];
-              o[r] = gt / (1.0f + expf(-gt)) * up;                   // silu(gate) * up
-            }
-            store4(p, o[0], o[1], o[2], o[3]);
-          }
-        } else if constexpr (EPI == EPI_QKV) {
-          if (live) {
-            const int half = a.hd / 2;
-            float lo[4], hi[4];
-            if (kind < 2) {                                  // rotary embedding on q and k
-              const int pos = a.P + (m % a.C);
-              const float *cs = a.rope_cos + (size_t)pos * half + nbase[0] + 4 * g;
-              const float *sn = a.rope_sin + (size_t)pos * half + nbase[0] + 4 * g;
-#pragma unroll
-              for (int r = 0; r < 4; ++r) {
-                const float x1 = acc[0][fm][r], x2 = acc[1][fm][r];
-                lo[r] = x1 * cs[r] - x2 * sn[r];
-                hi[r] = x2 * cs[r] + x1 * sn[r];
-              }
-              if (kind == 0) {
-                T *dst = (T *)a.q + ((size_t)head * a.Mcap + m) * a.hd + nbase[0] + 4 * g;
-                store4(dst, lo[0], lo[1], lo[2], lo[3]);
-                store4(dst + half, hi[0], hi[1], hi[2], hi[3]);
-              } else {                                       // keys: tiles of 32 block positions in operand order
-                T *kh = (T *)a.kscr + (size_t)head * a.Mcap * a.hd;
-                store4(kh + k_offset(m, nbase[0] + 4 * g, a.hd, (int)sizeof(T)), lo[0], lo[1], lo[2], lo[3]);
-                store4(kh + k_offset(m, nbase[0] + 4 * g + half, a.hd, (int)sizeof(T)), hi[0], hi[1], hi[2], hi[3]);
-              }
-            } else {                                         // values: the transposed tiles
-              T *vh = (T *)a.vscr + (size_t)head * a.Mcap * a.hd;
-#pragma unroll
-              for (int r = 0; r < 4; ++r) {
-                vh[v_offset(m, nbase[0] + 4 * g + r, a.hd, (int)sizeof(T))] = from_f32<T>(acc[0][fm][r]);
-                vh[v_offset(m, nbase[0] + 4 * g + half + r, a.hd, (int)sizeof(T))] = from_f32<T>(acc[1][fm][r]);
-              }
-            }
           }
         } else {   // EPI_UNEMBED: optional logits, and this wave's best (value, id) per column
           float bv = kNegBig;
@@ -268,28 +295,29 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
   }
 }
 
-template <typename T, int EPI, int FM, int WN, int WK, int RING>
+template <typename T, int EPI, int FM, int WN, int WK, int RING, int FN = 2>
 void launch_gemm_cfg(const GemmArgs &a, int KS, hipStream_t s) {
   constexpr int KC = KChunk<T>::value;
   constexpr int PAD = 16 / (int)sizeof(T);
+  constexpr bool PAIRED = EPI == EPI_QKV || EPI == EPI_GATEUP;
   size_t lds = (size_t)2 * 16 * FM * (KC + PAD) * sizeof(T);
-  const size_t red = (size_t)(WK - 1) * WN * 2 * FM * 4 * 64 * sizeof(float);
+  const size_t red = (size_t)(PAIRED ? WK * (FM < 4 ? FM : 4) : (WK - 1) * WN * FM) * FN * 4 * 64 * sizeof(float);
   if (red > lds) lds = red;
-  const int blocks = (a.n_groups + WN - 1) / WN;
+  const int blocks = PAIRED ? (a.n_groups + FN - 1) / FN : (a.n_groups + WN - 1) / WN;
   if (lds > 64 * 1024) {                     // more than the default dynamic LDS limit: opt in once
     static const hipError_t opted = hipFuncSetAttribute(
-        reinterpret_cast<const void *>(&gemm_skinny_kernel<T, EPI, FM, WN, WK, RING>),
+        reinterpret_cast<const void *>(&gemm_skinny_kernel<T, EPI, FM, WN, WK, RING, FN>),
         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     (void)opted;
   }
-  hipLaunchKernelGGL((gemm_skinny_kernel<T, EPI, FM, WN, WK, RING>), dim3(blocks, KS), dim3(64 * WN * WK), lds, s, a);
+  hipLaunchKernelGGL((gemm_skinny_kernel<T, EPI, FM, WN, WK, RING, FN>), dim3(blocks, KS), dim3(64 * WN * WK), lds, s, a);
 }
 
-// pair groups (2 x 16 output features) of each epilogue
+// residual, unembedding: pairs of 16-row fragments; q/k/v and gate/up: 16-row fragments of 8 output pairs
 int gemm_groups(int epi, const GemmArgs &a) {
   switch (epi) {
-    case EPI_QKV: return (a.H + 2 * a.Hkv) * (a.hd / 32);
-    case EPI_GATEUP: return a.N / 16;
+    case EPI_QKV: return (a.H + 2 * a.Hkv) * (a.hd / 16);
+    case EPI_GATEUP: return a.N / 8;
     default: return a.N / 32;
   }
 }
@@ -300,6 +328,47 @@ static void launch_fm(const GemmArgs &a, int KS, hipStream_t s) {
   else if (a.M <= 32) launch_gemm_cfg<T, EPI, 2, WN, WK, RING>(a, KS, s);
   else if (a.M <= 64) launch_gemm_cfg<T, EPI, 4, WN, WK, RING>(a, KS, s);
   else launch_gemm_cfg<T, EPI, 8, WN, WK, RING>(a, KS, s);   // 128-row tiles; more rows loop over W again
+}
+
+// q/k/v and gate/up: one workgroup = FN fragments, its four waves split the steps of every chunk
+// (WN = 1, WK = 4).  FN is chosen so that the fragments spread evenly over the 256 CUs (7B shapes:
+// 768 q/k/v fragments = 3 per workgroup, 1792 gate/up fragments = 7 per workgroup, 256 workgroups
+// each); wide fragment sets keep a 2-deep ring (FN KB per slot and wave are in flight anyway).
+template <typename T, int EPI, int FM>
+static void launch_paired_fm(const GemmArgs &a, hipStream_t s) {
+  constexpr int FMAX = sizeof(T) == 4 ? 2 : (FM == 8 ? 7 : 8);   // accumulators: FN * FM * 4 registers; fp32 fragments: twice the ring
+  int fn = (a.n_groups + 255) / 256;
+  fn = fn < 1 ? 1 : (fn > FMAX ? FMAX : fn);
+  switch (fn) {
+    case 1: launch_gemm_cfg<T, EPI, FM, 1, 4, 4, 1>(a, 1, s); break;
+    case 2: launch_gemm_cfg<T, EPI, FM, 1, 4, 4, 2>(a, 1, s); break;
+    default:
+      if constexpr (FMAX >= 4) {
+        switch (fn) {
+          case 3: launch_gemm_cfg<T, EPI, FM, 1, 4, 2, 3>(a, 1, s); break;
+          case 4: launch_gemm_cfg<T, EPI, FM, 1, 4, 2, 4>(a, 1, s); break;
+          default:
+            if constexpr (FMAX >= 7) {
+              switch (fn) {
+                case 5: launch_gemm_cfg<T, EPI, FM, 1, 4, 2, 5>(a, 1, s); break;
+                case 6: launch_gemm_cfg<T, EPI, FM, 1, 4, 2, 6>(a, 1, s); break;
+                case 7: launch_gemm_cfg<T, EPI, FM, 1, 4, 2, 7>(a, 1, s); break;
+                default:
+                  if constexpr (FMAX >= 8) launch_gemm_cfg<T, EPI, FM, 1, 4, 2, 8>(a, 1, s);
+                  else launch_gemm_cfg<T, EPI, FM, 1, 4, 2, 7>(a, 1, s);
+              }
+            }
+        }
+      }
+  }
+}
+
+template <typename T, int EPI>
+static void launch_paired(const GemmArgs &a, hipStream_t s) {
+  if (a.M <= 16) launch_paired_fm<T, EPI, 1>(a, s);
+  else if (a.M <= 32) launch_paired_fm<T, EPI, 2>(a, s);
+  else if (a.M <= 64) launch_paired_fm<T, EPI, 4>(a, s);
+  else launch_paired_fm<T, EPI, 8>(a, s);
 }
 
 // Split of the contraction across workgroups for the residual GEMMs (two waves share a pair of row
@@ -314,19 +383,17 @@ int gemm_residual_splits(int dtype, int N, int K) {
   return ks < 1 ? 1 : ks;
 }
 
-// Workgroup shapes measured on MI355X at the 7B shapes (M = 60 and M = 1): wide tiles (WN = 4) where
-// there are enough row groups to give every CU a workgroup, otherwise two waves per pair of groups.
+// Workgroup shapes measured on MI355X at the 7B shapes (M = 60 and M = 1).  Unembedding: wide tiles
+// (WN = 4) where there are enough row groups to give every CU a workgroup, otherwise two waves per
+// pair of groups; residual GEMMs: WN = 2, WK = 2 with the contraction split across workgroups.
 template <typename T>
 static void launch_t(int epi, const GemmArgs &a_in, hipStream_t s) {
   GemmArgs a = a_in;
   a.n_groups = gemm_groups(epi, a);
   const bool wide = a.n_groups >= 4 * 200;
   switch (epi) {
-    case EPI_QKV: launch_fm<T, EPI_QKV, 2, 2, 4>(a, 1, s); break;
-    case EPI_GATEUP:
-      if (wide && a.M > 16) launch_fm<T, EPI_GATEUP, 4, 1, 4>(a, 1, s);
-      else launch_fm<T, EPI_GATEUP, 2, 2, 4>(a, 1, s);
-      break;
+    case EPI_QKV: launch_paired<T, EPI_QKV>(a, s); break;
+    case EPI_GATEUP: launch_paired<T, EPI_GATEUP>(a, s); break;
     case EPI_RESIDUAL: launch_fm<T, EPI_RESIDUAL, 2, 2, 4>(a, a.KS, s); break;
     default:
       if (wide) launch_fm<T, EPI_UNEMBED, 4, 1, 8>(a, 1, s);

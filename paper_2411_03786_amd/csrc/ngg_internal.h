@@ -163,6 +163,14 @@ __device__ __forceinline__ float rows_sum(float x) {
   return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
+// The value that the lane 32 lanes away holds.  In a 16x16 accumulator fragment lane (column, g) has
+// rows 4g .. 4g+3, so rows 0..7 (g < 2) meet rows 8..15 of the same column this way.
+__device__ __forceinline__ float other_half(float x) {
+  const unsigned u = __float_as_uint(x);
+  const auto b = __builtin_amdgcn_permlane32_swap(u, u, false, false);   // b[0] = [lo lo], b[1] = [hi hi]
+  return __uint_as_float((threadIdx.x & 32) ? b[0] : b[1]);
+}
+
 template <typename T> __device__ __forceinline__ float fast_exp(float x);
 template <> __device__ __forceinline__ float fast_exp<float>(float x) { return expf(x); }
 template <> __device__ __forceinline__ float fast_exp<bf16_t>(float x) { return __expf(x); }
@@ -176,7 +184,7 @@ struct GemmArgs {
   const void *X;          // activations, chunk-major [K/KC][Mcap][KC], element type T
   const void *W0;         // weight matrix in operand order (QKV: rows [q | k | v]; gate/up: rows [gate | up])
   int M, N, K;            // N = total logical output rows
-  int n_groups;           // pairs of 16-row groups (filled by the launcher)
+  int n_groups;           // residual, unembedding: pairs of 16-row fragments; q/k/v, gate/up: fragments (filled by the launcher)
   // EPI_RESIDUAL: split ks of KS stores its fp32 partial at hpart[ks][m][n]; the next RMSNorm adds them
   float *hpart;           // [KS][Mcap][N]
   int KS;
@@ -248,7 +256,11 @@ void launch_build_drafts(int dtype, const DraftArgs &a, hipStream_t s);
 void launch_row_topk(const float *logits, int M, int V, int K, int32_t *out, hipStream_t s);
 void launch_iota(int32_t *dst, int first, int n, hipStream_t s);
 // copies src [N][K] (row-major) into rows row0 .. row0+N of the operand-order matrix dst
-void launch_tile_weights(int dtype, const void *src, void *dst, int N, int K, int row0, hipStream_t s);
+// row_map: 0 = row n goes to row0 + n; 1 = rotary pairing inside blocks of 2*half rows (row i < half of a block goes
+// to 16*(i/8) + i%8, row half + i to 16*(i/8) + 8 + i%8); 2 / 3 = first / second member of interleaved 8-row halves
+// (row n goes to 16*(n/8) + n%8, plus 8 for the second member)
+void launch_tile_weights(int dtype, const void *src, void *dst, int N, int K, int row0, hipStream_t s, int row_map = 0,
+                         int half = 0);
 
 // result block layout (int32 words)
 enum { RES_WINNER = 0, RES_NACCEPT = 1, RES_NNEW = 2, RES_NCTX = 3, RES_NEWTOK = 8, RES_ACCEPT = 48 };

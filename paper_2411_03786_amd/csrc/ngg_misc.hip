@@ -339,15 +339,29 @@ __global__ __launch_bounds__(256) void bigram_gemv_kernel(const T *tok_emb, cons
   }
 }
 
-// One-off copy of a row-major matrix into operand order (see tiled_offset).
+// One-off copy of a row-major matrix into operand order (see tiled_offset).  Destination row of
+// source row n: row_map 0: row0 + n.  row_map 1 (q, k, v): inside every block of 2*half rows (a head)
+// row i < half goes to 16*(i/8) + i%8 and row half + i to 16*(i/8) + 8 + i%8, so a 16-row fragment
+// holds 8 rotary pairs (i, i + half).  row_map 2 / 3 (gate / up): row n goes to 16*(n/8) + n%8 (+ 8
+// for up), so a fragment holds gate and up of 8 features.
+__host__ __device__ inline int tile_dest_row(int n, int row_map, int half) {
+  if (row_map == 1) {
+    const int blk = n / (2 * half), i = n - blk * 2 * half;
+    const int second = i >= half ? 1 : 0, ii = i - second * half;
+    return blk * 2 * half + 16 * (ii / 8) + 8 * second + ii % 8;
+  }
+  if (row_map >= 2) return 16 * (n / 8) + 8 * (row_map - 2) + n % 8;
+  return n;
+}
+
 template <typename T>
-__global__ __launch_bounds__(256) void tile_weights_kernel(const T *src, T *dst, int N, int K, int row0) {
+__global__ __launch_bounds__(256) void tile_weights_kernel(const T *src, T *dst, int N, int K, int row0, int row_map, int half) {
   const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
   const int pieces = K / 8;
   if (idx >= (size_t)N * pieces) return;
   const int n = (int)(idx / pieces), k = (int)(idx % pieces) * 8;
   const T *p = src + (size_t)n * K + k;
-  T *q = dst + tiled_offset(row0 + n, k, K, (int)sizeof(T));
+  T *q = dst + tiled_offset(row0 + tile_dest_row(n, row_map, half), k, K, (int)sizeof(T));
   if constexpr (sizeof(T) == 2) {
     *reinterpret_cast<u32x4 *>(q) = *reinterpret_cast<const u32x4 *>(p);
   } else {
@@ -356,13 +370,13 @@ __global__ __launch_bounds__(256) void tile_weights_kernel(const T *src, T *dst,
   }
 }
 
-void launch_tile_weights(int dtype, const void *src, void *dst, int N, int K, int row0, hipStream_t s) {
+void launch_tile_weights(int dtype, const void *src, void *dst, int N, int K, int row0, hipStream_t s, int row_map, int half) {
   const size_t total = (size_t)N * (K / 8);
   const unsigned blocks = (unsigned)((total + 255) / 256);
   if (dtype == 1)
-    hipLaunchKernelGGL(tile_weights_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, (const bf16_t *)src, (bf16_t *)dst, N, K, row0);
+    hipLaunchKernelGGL(tile_weights_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, (const bf16_t *)src, (bf16_t *)dst, N, K, row0, row_map, half);
   else
-    hipLaunchKernelGGL(tile_weights_kernel<float>, dim3(blocks), dim3(256), 0, s, (const float *)src, (float *)dst, N, K, row0);
+    hipLaunchKernelGGL(tile_weights_kernel<float>, dim3(blocks), dim3(256), 0, s, (const float *)src, (float *)dst, N, K, row0, row_map, half);
 }
 
 // Top-(k - n_ctx) of z by (score desc, id asc), chained extension through next1, and assembly of
