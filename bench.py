@@ -198,12 +198,16 @@ def main():
     roof = None
     if dom_n:
         gb = gemm_bytes(m, "gemm_gateup")
+        # an event bracket also times the dispatch of the launch (rocprofv3's kernel durations in profiles/
+        # are about 3.5 us shorter); the bracket around an empty kernel is reported as context, not subtracted
+        bracket_us = ctx.profile_bracket_overhead()
         avg_us = dom_ms * 1e3 / dom_n
         ach = gb / (avg_us * 1e-6) / 1e9
         roof = {"kernel": "gemm_skinny_kernel<bf16, gate/up + SwiGLU epilogue>", "bound": "hbm", "achieved": ach,
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBPS,
                 "traffic": measured_traffic(args.workload),
-                "bytes_per_launch": gb, "avg_launch_us": avg_us, "launches": dom_n}
+                "bytes_per_launch": gb, "avg_launch_us": avg_us, "launches": dom_n,
+                "empty_kernel_bracket_us": bracket_us}
     out = {
         "metric": "accepted tokens/s at k x w (verify-step latency in ms_per_step; HBM GB/s vs peak in roofline)",
         "value": new_tokens / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

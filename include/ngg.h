@@ -186,6 +186,10 @@ enum {
 ngg_status ngg_profile_enable(ngg_ctx *ctx, int32_t class_mask);
 ngg_status ngg_profile_reset(ngg_ctx *ctx);
 ngg_status ngg_profile_read(ngg_ctx *ctx, double *ms /*[NGG_PROF_COUNT]*/, int64_t *launches /*[NGG_PROF_COUNT]*/);
+/* What a bracket of two events reads around an EMPTY kernel on the context's
+ * stream, in microseconds (mean of 64 brackets queued back to back): the part of every ngg_profile_read time
+ * that is the dispatch of the launch and the events themselves, not the kernel. */
+ngg_status ngg_profile_bracket_overhead(ngg_ctx *ctx, double *us);
 
 /* Debug aid for parity tests: copies an internal device buffer to dst (HOST), at most cap bytes,
  * and reports its full size in *bytes.  Names: "h" (residual stream, fp32 [M][d_model]), "z"

@@ -596,6 +596,30 @@ ngg_status ngg_profile_read(ngg_ctx *c, double *ms, int64_t *launches) {
   return NGG_OK;
 }
 
+ngg_status ngg_profile_bracket_overhead(ngg_ctx *c, double *us) {
+  if (!c || !us) return NGG_EINVAL;
+  // brackets queued back to back, as they are inside a step (a bracket on an idle stream also
+  // pays the wake-up of the queue); the first 8 warm up
+  constexpr int kReps = 64, kWarm = 8;
+  std::vector<hipEvent_t> ev(2 * (kReps + kWarm));
+  for (auto &e : ev) NGG_HIP(c, hipEventCreate(&e));
+  for (int i = 0; i < kReps + kWarm; ++i) {
+    NGG_HIP(c, hipEventRecord(ev[2 * i], c->stream));
+    launch_noop(c->stream);
+    NGG_HIP(c, hipEventRecord(ev[2 * i + 1], c->stream));
+  }
+  NGG_HIP(c, hipStreamSynchronize(c->stream));
+  double sum = 0.0;
+  for (int i = kWarm; i < kReps + kWarm; ++i) {
+    float t = 0.0f;
+    NGG_HIP(c, hipEventElapsedTime(&t, ev[2 * i], ev[2 * i + 1]));
+    sum += t;
+  }
+  for (auto &e : ev) (void)hipEventDestroy(e);
+  *us = sum * 1e3 / kReps;
+  return NGG_OK;
+}
+
 ngg_status ngg_bigram_table_build(ngg_ctx *c, int32_t top_k) {
   if (!c) return NGG_EINVAL;
   const ngg_model_desc &d = c->d;

@@ -616,6 +616,10 @@ __global__ void iota_kernel(int32_t *dst, int first, int n) {
   if (i < n) dst[i] = first + i;
 }
 
+__global__ void noop_kernel() {}
+
+void launch_noop(hipStream_t s) { hipLaunchKernelGGL(noop_kernel, dim3(1), dim3(64), 0, s); }
+
 void launch_iota(int32_t *dst, int first, int n, hipStream_t s) {
   hipLaunchKernelGGL(iota_kernel, dim3((n + 255) / 256), dim3(256), 0, s, dst, first, n);
 }
