@@ -483,14 +483,15 @@ static void launch_hd(const AttnArgs &a, hipStream_t s) {
   hipLaunchKernelGGL((attn_merge_kernel<T, HD>), dim3((a.M + 15) / 16, a.H), dim3(256), 0, s, a);
 }
 
-// Number of list slices per head: one workgroup per CU in total, two per CU once every slice still
-// has 16 tiles (long contexts), never fewer than 4 tiles per slice.
+// Number of list slices per head: one workgroup per CU in total; two per CU for blocks of more than
+// 64 tokens once every slice still has 16 tiles (measured at a 16K context: 74 -> 69 us; everywhere
+// else one per CU was as fast or faster); never fewer than 4 tiles per slice.
 int attention_splits(int dtype, int hd, int H, int M, int P, int max_splits) {
   const int qmax = dtype == 1 || hd <= 64 ? 2 : 1;
   const int per_wg = M <= 16 ? 16 : (M <= 64 ? 64 : 64 * qmax);
   const int Z = (M + per_wg - 1) / per_wg;
   const int tiles = (P + 31) / 32 + 1;
-  const int one = 256 / (H * Z), two = 512 / (H * Z);
+  const int one = 256 / (H * Z), two = M > 64 ? 512 / (H * Z) : one;
   int s = tiles / 16 > one ? tiles / 16 : one;
   s = s < two ? s : two;
   s = s < tiles / 4 ? s : tiles / 4;
