@@ -123,15 +123,22 @@ def greedy_speculative(model: Model, prompt, n_gen: int, k: int, w: int, k_ctx_m
     bigram = bigram or Bigram(model.tok_emb, model.unemb)
     st = prefill(model, prompt)
     n0 = len(prompt)
-    stats = dict(calls=0, new_hist=[0] * (w + 2), winner_src=[0, 0], ctx_rows=[])
+    # accept_hist / rank_hist / alloc_hist: the quantities of the ablation on strategies (Section 5.2)
+    stats = dict(calls=0, new_hist=[0] * (w + 2), winner_src=[0, 0], ctx_rows=[],
+                 accept_hist=[[0] * (w + 1), [0] * (w + 1)], rank_hist=[[0] * k, [0] * k], alloc_hist=[0] * (k + 1))
     while len(st.tokens) - n0 < n_gen:
         drafts, src, n_ctx = build_drafts(st.tokens, bigram, k, w, k_ctx_max, q_min, q_max)
         res = verify_step(model, st, drafts)
         n_new = commit(st, res, max_new=n_gen - (len(st.tokens) - n0))
         stats["calls"] += 1
         stats["new_hist"][n_new] += 1
-        stats["winner_src"][int(src[res["winner"]])] += 1
+        ws = int(src[res["winner"]])
+        stats["winner_src"][ws] += 1
         stats["ctx_rows"].append(n_ctx)
+        stats["accept_hist"][ws][res["n_accept"]] += 1
+        if res["n_accept"] > 0:
+            stats["rank_hist"][ws][res["winner"] - n_ctx if ws else res["winner"]] += 1
+        stats["alloc_hist"][n_ctx] += 1
     gen = st.tokens[n0:n0 + n_gen]
     stats["tokens_per_call"] = (len(gen) - 1) / max(1, stats["calls"])
     return gen, stats

@@ -55,7 +55,8 @@ class ngg_stats(C.Structure):
     _fields_ = [("calls", C.c_int64), ("tokens", C.c_int64), ("new_hist", C.c_int64 * 34),
                 ("winner_src", C.c_int64 * 2), ("ctx_rows", C.c_int64),
                 ("ms_prefill", C.c_double), ("ms_drafts", C.c_double), ("ms_verify", C.c_double),
-                ("ms_commit", C.c_double)]
+                ("ms_commit", C.c_double), ("accept_hist", (C.c_int64 * 34) * 2), ("rank_hist", (C.c_int64 * 32) * 2),
+                ("alloc_hist", C.c_int64 * 33)]
 
 
 _lib = None
@@ -221,7 +222,8 @@ class Context:
                                                _ptr(out), C.byref(st)))
         stats = dict(calls=st.calls, tokens=st.tokens, new_hist=list(st.new_hist), winner_src=list(st.winner_src),
                      ctx_rows=st.ctx_rows, ms_prefill=st.ms_prefill, ms_drafts=st.ms_drafts, ms_verify=st.ms_verify,
-                     ms_commit=st.ms_commit)
+                     ms_commit=st.ms_commit, accept_hist=[list(r) for r in st.accept_hist],
+                     rank_hist=[list(r) for r in st.rank_hist], alloc_hist=list(st.alloc_hist))
         return out, stats
 
     def profile_bracket_overhead(self):

@@ -552,8 +552,12 @@ ngg_status ngg_greedy_decode(ngg_ctx *c, const int32_t *prompt, int32_t n_prompt
     st.ms_drafts += t1 - t0; st.ms_verify += t2 - t1; st.ms_commit += t3 - t2;
     st.calls += 1;
     st.new_hist[n_new] += 1;
-    st.winner_src[src[vo.winner] ? 1 : 0] += 1;
+    const int ws = src[vo.winner] ? 1 : 0;
+    st.winner_src[ws] += 1;
     st.ctx_rows += n_ctx;
+    st.accept_hist[ws][vo.n_accept] += 1;
+    if (vo.n_accept > 0) st.rank_hist[ws][ws ? vo.winner - n_ctx : vo.winner] += 1;
+    st.alloc_hist[n_ctx] += 1;
   }
   NGG_HIP(c, hipStreamSynchronize(c->stream));
   st.tokens = n_gen;

@@ -34,7 +34,7 @@ def test_struct_sizes_match_the_header():
     assert C.sizeof(ngg.ngg_layer_weights) == 9 * 8
     assert C.sizeof(ngg.ngg_draft_cfg) == 5 * 4
     assert C.sizeof(ngg.ngg_verify_out) == 5 * 4 + 4 + 4 * 8          # 4 bytes of padding before the pointers
-    assert C.sizeof(ngg.ngg_stats) == 8 * (2 + 34 + 2 + 1) + 4 * 8
+    assert C.sizeof(ngg.ngg_stats) == 8 * (2 + 34 + 2 + 1) + 4 * 8 + 8 * (2 * 34 + 2 * 32 + 33)
 
 
 def _desc(**over):
@@ -78,6 +78,9 @@ def test_create_rejects_null_pointers(lib):
 def test_calls_on_a_null_context_fail_cleanly(lib):
     assert lib.ngg_prefill(None, None, 0) == ngg.NGG_EINVAL
     assert lib.ngg_commit(None, 1, None) == ngg.NGG_EINVAL
+    assert lib.ngg_bigram_table_build(None, 8) == ngg.NGG_EINVAL
+    assert lib.ngg_bigram_source(None, 0) == ngg.NGG_EINVAL
+    assert lib.ngg_profile_bracket_overhead(None, None) == ngg.NGG_EINVAL
     assert lib.ngg_destroy(None) == ngg.NGG_EINVAL
     assert lib.ngg_verify_step(None, None, 1, 0, None) == ngg.NGG_EINVAL
     assert isinstance(lib.ngg_last_error(None), bytes)

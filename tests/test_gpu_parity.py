@@ -50,6 +50,14 @@ def test_cfg1_matches_oracle_plain_greedy_and_gpu_plain_equals_speculative(tiny)
     assert list(got_spec) == want and list(got_plain) == want
     assert stats_p["calls"] == 39 and stats_p["new_hist"][1] == 39
     assert stats["calls"] < 39 and sum(i * c for i, c in enumerate(stats["new_hist"])) == 39
+    # the ablation quantities of Section 5.2 (accepted length and rank by strategy, rows per strategy)
+    _, o_stats = oracle.greedy_speculative(model, prompt, 40, run["k"], run["w"], run["k_ctx_max"], run["q_min"], run["q_max"])
+    assert stats["calls"] == o_stats["calls"] and stats["winner_src"] == o_stats["winner_src"]
+    for s_ in (0, 1):
+        assert stats["accept_hist"][s_][:run["w"] + 1] == o_stats["accept_hist"][s_]
+        assert stats["rank_hist"][s_][:run["k"]] == o_stats["rank_hist"][s_]
+    assert stats["alloc_hist"][:run["k"] + 1] == o_stats["alloc_hist"]
+    assert sum(stats["alloc_hist"]) == stats["calls"] == sum(map(sum, stats["accept_hist"]))
 
 
 def test_injected_drafts_every_accept_length(tiny):
