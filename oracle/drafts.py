@@ -124,6 +124,48 @@ class ModelBigram(Bigram):
         return self._scores[x]
 
 
+# -- model unigram (Section 4.1, "Unigram") -------------------------------------
+
+def unigram_distances(tok_emb, unemb):
+    """d(x) = || u_x - u_mean ||_V for every token x, where u_x is the output
+    embedding of x, u_mean the mean output embedding, and the norm comes from the
+    inner product <a, b>_V = sum over tokens y of (a . v_y)(b . v_y) with v_y the
+    input embeddings.  So d(x) is the Euclidean length of the vector
+    ((u_x - u_mean) . v_y)_y.  The paper's listing computes a different quantity
+    and returns nothing; the text's definition is the one followed here."""
+    e = np.asarray(tok_emb, dtype=np.float64)
+    u = np.asarray(unemb, dtype=np.float64)
+    centred = u - u.mean(axis=0, keepdims=True)
+    return np.sqrt(np.sum((centred @ e.T) ** 2, axis=1))
+
+
+class UnigramDrafts:
+    """Draft rows from the unigram p(x) ~ exp(-d(x)): row i starts with the token of
+    i-th smallest distance (ties to the lower id), whatever the context, and is
+    extended like a bigram row, by the chain of the bigram's top-1.  Offers the
+    interface build_drafts uses (rows) on top of an existing Bigram."""
+
+    def __init__(self, tok_emb, unemb, bigram):
+        self.d = unigram_distances(tok_emb, unemb)
+        self.order = rank_ids(-self.d, len(self.d))
+        self.bigram = bigram
+
+    def scores(self, x: int):
+        return self.bigram.scores(x)
+
+    def next1(self, x: int) -> int:
+        return self.bigram.next1(x)
+
+    def rows(self, x: int, k_big: int, w: int):
+        out = []
+        for t in self.order[:k_big]:
+            row = [int(t)]
+            while len(row) < w:
+                row.append(self.bigram.next1(row[-1]))
+            out.append(tuple(row[:w]))
+        return out
+
+
 # -- mixed strategy (Section 4.3) -----------------------------------------------
 
 def build_drafts(tokens, bigram: Bigram, k: int, w: int, k_ctx_max: int, q_min: int, q_max: int):

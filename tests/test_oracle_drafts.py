@@ -6,7 +6,8 @@ import numpy as np
 import pytest
 
 import synth_inputs as si
-from oracle import context_ngram_groups, context_rows, bigram_scores, rank_ids, Bigram, build_drafts
+from oracle import (context_ngram_groups, context_rows, bigram_scores, rank_ids, Bigram, build_drafts,
+                    unigram_distances, UnigramDrafts)
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "context_ngram_cases.txt")
 
@@ -183,3 +184,45 @@ def test_mixed_strategy_rows_and_sources():
     # w = 0: plain decoding, an empty batch
     d, src, n_ctx = build_drafts(x, b, k=1, w=0, k_ctx_max=1, q_min=1, q_max=1)
     assert d.shape == (1, 0) and n_ctx == 0
+
+
+def test_unigram_distance_brute_force_gram_form_and_special_cases():
+    """Section 4.1, "Unigram": d(x) = ||u_x - u_mean||_V.  Pins: the double loop over the definition's
+    sum, the Gram-matrix form (a^T (E^T E) a), invariance to a common shift of all output embeddings,
+    and orthonormal input embeddings (E^T E = I), where the distance is the plain Euclidean one."""
+    rng = np.random.default_rng(11)
+    V, d = 23, 6
+    e, u = rng.normal(size=(V, d)), rng.normal(size=(V, d))
+    got = unigram_distances(e, u)
+    mean = [sum(u[x][i] for x in range(V)) / V for i in range(d)]
+    for x in (0, 5, 22):
+        a = [u[x][i] - mean[i] for i in range(d)]
+        total = 0.0
+        for y in range(V):
+            dot = sum(a[i] * e[y][i] for i in range(d))
+            total += dot * dot
+        assert abs(got[x] - total ** 0.5) < 1e-12
+    c = u - u.mean(axis=0)
+    assert np.allclose(got ** 2, np.einsum("xi,ij,xj->x", c, e.T @ e, c), rtol=1e-12)
+    assert np.allclose(unigram_distances(e, u + rng.normal(size=(1, d))), got, rtol=1e-10)
+    q, _ = np.linalg.qr(rng.normal(size=(V, d)))             # V x d with orthonormal columns: E^T E = I
+    assert np.allclose(unigram_distances(q, u), np.linalg.norm(c, axis=1), rtol=1e-12)
+    # a token whose output embedding is the mean has distance 0 and ranks first
+    u2 = u.copy()
+    u2[7] = (u2.sum(axis=0) - u2[7]) / (V - 1)               # makes row 7 equal to the mean of all rows
+    assert abs(unigram_distances(e, u2)[7]) < 1e-12
+
+
+def test_unigram_rows_ignore_the_context_and_chain_like_bigram_rows():
+    desc = si.MODELS["tiny"]
+    w = si.make_weights(desc, seed=2)
+    b = Bigram(w["tok_emb"], w["unemb"])
+    ug = UnigramDrafts(w["tok_emb"], w["unemb"], b)
+    d = unigram_distances(w["tok_emb"], w["unemb"])
+    assert list(ug.order[:5]) == sorted(range(desc["vocab"]), key=lambda x: (d[x], x))[:5]
+    rows = ug.rows(123, 3, 4)
+    assert rows == ug.rows(7, 3, 4)                          # q = 0: no context token enters
+    for i, row in enumerate(rows):
+        assert row[0] == ug.order[i] and all(row[j + 1] == b.next1(row[j]) for j in range(3))
+    drafts, src, n_ctx = build_drafts([1, 2, 3, 1, 2, 3, 1, 2], ug, k=4, w=2, k_ctx_max=2, q_min=2, q_max=2)
+    assert n_ctx == 1 and tuple(drafts[0]) == (3, 1) and [tuple(r) for r in drafts[1:]] == ug.rows(2, 3, 2)
