@@ -164,11 +164,21 @@ ngg_status ngg_greedy_decode(ngg_ctx *ctx, const int32_t *prompt, int32_t n_prom
  * pending verify call can no longer be committed (NGG_ESTATE from ngg_commit). */
 ngg_status ngg_bigram_table_build(ngg_ctx *ctx, int32_t top_k);
 
-/* Where the bigram rows of ngg_build_drafts come from: NGG_BIGRAM_DIRECT (the
+/* The model unigram (Section 4.1, "Unigram"): p(x) ~ exp(-d(x)) with d(x) the
+ * distance of x's output embedding from the mean output embedding in the norm
+ * induced by the input embeddings, d(x)^2 = sum over tokens y of
+ * ((unemb[x] - mean) . tok_emb[y])^2.  Computes d for the whole vocabulary on
+ * the device (vocab / Mcap GEMM passes, once) and keeps the top_k nearest
+ * tokens (ties to the lower id).  Requires max_k <= top_k <= min(64, vocab). */
+ngg_status ngg_unigram_build(ngg_ctx *ctx, int32_t top_k);
+
+/* Where the model rows of ngg_build_drafts come from: NGG_BIGRAM_DIRECT (the
  * default: one sweep of <unemb[v], tok_emb[x_last]> per step, chained through
- * next1) or NGG_BIGRAM_TABLE (two lookups in the table above; NGG_ESTATE if it
- * was not built).  The choice changes the drafts, never the committed tokens. */
-enum { NGG_BIGRAM_DIRECT = 0, NGG_BIGRAM_TABLE = 1 };
+ * next1), NGG_BIGRAM_TABLE (two lookups in the full-model table; NGG_ESTATE if
+ * it was not built) or NGG_UNIGRAM (q = 0: row i starts with the i-th nearest
+ * unigram token whatever the context, then chains through next1; NGG_ESTATE if
+ * it was not built).  The choice changes the drafts, never the committed tokens. */
+enum { NGG_BIGRAM_DIRECT = 0, NGG_BIGRAM_TABLE = 1, NGG_UNIGRAM = 2 };
 ngg_status ngg_bigram_source(ngg_ctx *ctx, int32_t source);
 
 /* Committed token history: copies min(n, cap) tokens to dst (HOST), n to *n. */

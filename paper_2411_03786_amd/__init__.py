@@ -22,7 +22,7 @@ PROF_CLASSES = ("gemm_qkv", "gemm_o", "gemm_gateup", "gemm_down", "gemm_unembed"
 
 EXPORTS = ("ngg_create", "ngg_destroy", "ngg_prefill", "ngg_build_drafts", "ngg_verify_step", "ngg_commit",
            "ngg_greedy_decode", "ngg_get_tokens", "ngg_last_error", "ngg_profile_enable", "ngg_profile_reset",
-           "ngg_profile_read", "ngg_debug_peek", "ngg_bigram_table_build", "ngg_bigram_source", "ngg_profile_bracket_overhead")
+           "ngg_profile_read", "ngg_debug_peek", "ngg_bigram_table_build", "ngg_bigram_source", "ngg_profile_bracket_overhead", "ngg_unigram_build")
 
 
 class ngg_model_desc(C.Structure):
@@ -88,6 +88,7 @@ def load_library():
     lib.ngg_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     lib.ngg_debug_peek.argtypes = [vp, C.c_char_p, vp, C.c_int64, C.POINTER(C.c_int64), i32p]
     lib.ngg_bigram_table_build.argtypes = [vp, C.c_int32]
+    lib.ngg_unigram_build.argtypes = [vp, C.c_int32]
     lib.ngg_profile_bracket_overhead.argtypes = [vp, C.POINTER(C.c_double)]
     lib.ngg_bigram_source.argtypes = [vp, C.c_int32]
     for name in EXPORTS:
@@ -234,8 +235,11 @@ class Context:
     def bigram_table_build(self, top_k):
         self._check(self.lib.ngg_bigram_table_build(self.h, top_k))
 
+    def unigram_build(self, top_k):
+        self._check(self.lib.ngg_unigram_build(self.h, top_k))
+
     def bigram_source(self, source):
-        """0 = direct sweep per step (default), 1 = the precomputed full-model table."""
+        """0 = direct sweep per step (default), 1 = the precomputed full-model table, 2 = the unigram."""
         self._check(self.lib.ngg_bigram_source(self.h, source))
 
     def get_tokens(self):

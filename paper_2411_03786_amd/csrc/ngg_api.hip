@@ -36,6 +36,9 @@ struct ngg_ctx {
   int32_t *bg_table = nullptr, *bg_tok = nullptr;   // full-model bigram table [vocab][bg_K]; token ids of one build pass
   int bg_K = 0;
   bool bg_use = false;             // bigram rows from the table instead of the U.E[x] sweep
+  int32_t *uni_top = nullptr;      // tokens by ascending unigram distance, uni_K of them
+  int uni_K = 0;
+  bool uni_use = false;            // model rows start with the unigram's tokens
   int8_t *row_src = nullptr;
   void *kcache = nullptr, *vcache = nullptr, *kscr = nullptr, *vscr = nullptr;
   float *h = nullptr, *hpart = nullptr, *part_o = nullptr, *part_ml = nullptr, *pmax_val = nullptr, *z = nullptr, *logits = nullptr;
@@ -271,7 +274,7 @@ ngg_status ngg_destroy(ngg_ctx *c) {
   (void)hipStreamSynchronize(c->stream);
   void *bufs[] = {c->hist, c->drafts, c->block_tok, c->res, c->next1, c->mlist, c->reps, c->ctx_rows, c->n_ctx,
                   c->row_src, c->hpart, c->wtiled, c->cand_val, c->cand_idx, c->kcache, c->vcache, c->kscr, c->vscr, c->h, c->part_o, c->part_ml, c->pmax_val, c->z,
-                  c->logits, c->rope_cos, c->rope_sin, c->pmax_idx, c->xn, c->q, c->attn, c->act, c->bg_table, c->bg_tok};
+                  c->logits, c->rope_cos, c->rope_sin, c->pmax_idx, c->xn, c->q, c->attn, c->act, c->bg_table, c->bg_tok, c->uni_top};
   for (void *b : bufs)
     if (b) (void)hipFree(b);
   if (c->res_host) (void)hipHostFree(c->res_host);
@@ -430,6 +433,7 @@ ngg_status ngg_build_drafts(ngg_ctx *c, const ngg_draft_cfg *cfg, int32_t *draft
     return fail(c, NGG_EINVAL, "ngg_build_drafts: need k_ctx_max >= 0 and 1 <= q_min <= q_max <= 64");
   if (cfg->k > c->d.vocab) return fail(c, NGG_EINVAL, "ngg_build_drafts: k exceeds the vocabulary");
   if (c->bg_use && cfg->k > c->bg_K) return fail(c, NGG_ECAPACITY, "ngg_build_drafts: k=%d exceeds the %d ranks kept in the bigram table", cfg->k, c->bg_K);
+  if (c->uni_use && cfg->k > c->uni_K) return fail(c, NGG_ECAPACITY, "ngg_build_drafts: k=%d exceeds the %d unigram tokens kept", cfg->k, c->uni_K);
   {
     ProfScope ps(c, NGG_PROF_DRAFTS);
     DraftArgs a{};
@@ -438,6 +442,7 @@ ngg_status ngg_build_drafts(ngg_ctx *c, const ngg_draft_cfg *cfg, int32_t *draft
     a.tok_emb = c->w.tok_emb; a.unemb_t = c->unemb_t; a.d = c->d.d_model; a.vocab = c->d.vocab; a.z = c->z; a.cand_val = c->cand_val; a.cand_idx = c->cand_idx; a.next1 = c->next1;
     a.drafts = c->drafts; a.row_src = c->row_src;
     if (c->bg_use) { a.bg_table = c->bg_table; a.bg_K = c->bg_K; }
+    if (c->uni_use) a.uni_top = c->uni_top;
     launch_build_drafts(c->d.dtype, a, c->stream);
   }
   NGG_HIP(c, hipGetLastError());
@@ -651,11 +656,61 @@ ngg_status ngg_bigram_table_build(ngg_ctx *c, int32_t top_k) {
   return NGG_OK;
 }
 
+ngg_status ngg_unigram_build(ngg_ctx *c, int32_t top_k) {
+  if (!c) return NGG_EINVAL;
+  const ngg_model_desc &d = c->d;
+  if (top_k < 1 || top_k > 64 || top_k > d.vocab) return fail(c, NGG_EINVAL, "ngg_unigram_build: need 1 <= top_k <= min(64, vocab)");
+  if (top_k < d.max_k) return fail(c, NGG_EINVAL, "ngg_unigram_build: top_k=%d is below max_k=%d (a step may ask for max_k rows)", top_k, d.max_k);
+  if (c->uni_top) { (void)hipFree(c->uni_top); c->uni_top = nullptr; c->uni_use = false; }
+  ngg_status st = dev_alloc(c, &c->uni_top, (size_t)top_k * 4, true);
+  if (st != NGG_OK) return st;
+  st = ensure_logits(c);
+  if (st != NGG_OK) return st;
+  // scratch of this build only: the input embedding in operand order (the "weight" of the GEMM below),
+  // the mean output embedding, and the negated squared distance of every token
+  void *emb_t = nullptr;
+  float *mean = nullptr, *negd2 = nullptr;
+  st = dev_alloc(c, &emb_t, (size_t)d.vocab * d.d_model * c->esize, false);
+  if (st == NGG_OK) st = dev_alloc(c, &mean, (size_t)d.d_model * 4, false);
+  if (st == NGG_OK) st = dev_alloc(c, &negd2, (size_t)d.vocab * 4, false);
+  if (st == NGG_OK) {
+    launch_tile_weights(d.dtype, c->w.tok_emb, emb_t, d.vocab, d.d_model, 0, c->stream);
+    launch_column_mean(d.dtype, c->w.unemb, d.vocab, d.d_model, mean, c->stream);
+    c->have_verify = false;                            // the activation buffers are reused
+    // d(x)^2 = sum_y ((u_x - u_mean) . v_y)^2: rows u_x - u_mean through the GEMM against the input
+    // embedding, Mcap tokens per pass, then the sum of squares of every output row
+    for (int x0 = 0; x0 < d.vocab; x0 += c->Mcap) {
+      const int M = std::min(c->Mcap, d.vocab - x0);
+      launch_pack_rows(d.dtype, (const char *)c->w.unemb + (size_t)x0 * d.d_model * c->esize, c->xn, d.d_model, M, c->Mcap,
+                       c->stream, mean);
+      GemmArgs g{};
+      g.X = c->xn;
+      g.W0 = emb_t; g.M = M; g.N = d.vocab; g.K = d.d_model;
+      g.logits = c->logits; g.pmax_val = c->pmax_val; g.pmax_idx = c->pmax_idx; g.Mcap = c->Mcap;
+      launch_gemm(d.dtype, EPI_UNEMBED, g, c->stream);
+      launch_neg_row_sumsq(c->logits, M, d.vocab, negd2 + x0, c->stream);
+    }
+    launch_row_topk(negd2, 1, d.vocab, top_k, c->uni_top, c->stream);     // nearest first, ties to the lower id
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) st = fail(c, NGG_EHIP, "ngg_unigram_build: %s", hipGetErrorString(e));
+  }
+  if (emb_t) (void)hipFree(emb_t);
+  if (mean) (void)hipFree(mean);
+  if (negd2) (void)hipFree(negd2);
+  if (st != NGG_OK) return st;
+  c->uni_K = top_k;
+  return NGG_OK;
+}
+
 ngg_status ngg_bigram_source(ngg_ctx *c, int32_t source) {
   if (!c) return NGG_EINVAL;
-  if (source != NGG_BIGRAM_DIRECT && source != NGG_BIGRAM_TABLE) return fail(c, NGG_EINVAL, "ngg_bigram_source: unknown source %d", source);
+  if (source != NGG_BIGRAM_DIRECT && source != NGG_BIGRAM_TABLE && source != NGG_UNIGRAM)
+    return fail(c, NGG_EINVAL, "ngg_bigram_source: unknown source %d", source);
   if (source == NGG_BIGRAM_TABLE && !c->bg_table) return fail(c, NGG_ESTATE, "ngg_bigram_source: no table (call ngg_bigram_table_build first)");
+  if (source == NGG_UNIGRAM && !c->uni_top) return fail(c, NGG_ESTATE, "ngg_bigram_source: no unigram (call ngg_unigram_build first)");
   c->bg_use = source == NGG_BIGRAM_TABLE;
+  c->uni_use = source == NGG_UNIGRAM;
   c->drafts_on_device = false;
   return NGG_OK;
 }
@@ -671,6 +726,7 @@ ngg_status ngg_debug_peek(ngg_ctx *c, const char *name, void *dst, int64_t cap, 
   else if (nm == "z") { src = c->z; sz = (size_t)d.vocab * 4; }
   else if (nm == "next1") { src = c->next1; sz = (size_t)d.vocab * 4; }
   else if (nm == "bg_table" && c->bg_table) { src = c->bg_table; sz = (size_t)d.vocab * c->bg_K * 4; }
+  else if (nm == "uni_top" && c->uni_top) { src = c->uni_top; sz = (size_t)c->uni_K * 4; }
   else if (nm == "hist") { src = c->hist; sz = (size_t)c->Spad * 4; }
   else if (nm == "block_tok") { src = c->block_tok; sz = (size_t)c->Mcap * 4; }
   else if (nm == "kcache") { src = c->kcache; sz = kv; }

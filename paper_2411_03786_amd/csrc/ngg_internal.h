@@ -228,7 +228,9 @@ void launch_embed(int dtype, const void *tok_emb, const int32_t *hist, const int
                   float *h, int d, int M, int C, int w, int hist_base, int from_hist, hipStream_t s);
 // h[m] += sum of n_part partials (hpart[s][m], stride part_stride floats between splits), then
 // xn[m] = rmsnorm(h[m]) * gain, written chunk-major
-void launch_pack_rows(int dtype, const void *src, void *dst, int d, int M, int Mcap, hipStream_t s);
+void launch_pack_rows(int dtype, const void *src, void *dst, int d, int M, int Mcap, hipStream_t s, const float *centre = nullptr);
+void launch_column_mean(int dtype, const void *src, int N, int d, float *mean, hipStream_t s);
+void launch_neg_row_sumsq(const float *rows, int M, int V, float *out, hipStream_t s);
 void launch_rmsnorm(int dtype, float *h, const float *hpart, int n_part, size_t part_stride, const void *gain, void *xn,
                     int d, int M, int Mcap, float eps, hipStream_t s);
 
@@ -248,6 +250,7 @@ struct DraftArgs {
   const int32_t *next1;   // [vocab]
   const int32_t *bg_table; // [vocab][bg_K] full-model bigram table, or null: bigram rows come from the sweep
   int bg_K;
+  const int32_t *uni_top; // [>= k] tokens by ascending unigram distance, or null: first tokens come from the bigram
   int32_t *drafts;        // [k][w]
   int8_t *row_src;        // [k]
 };

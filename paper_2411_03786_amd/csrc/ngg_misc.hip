@@ -142,15 +142,49 @@ void launch_rmsnorm(int dtype, float *h, const float *hpart, int n_part, size_t 
   else launch_rmsnorm_t<float>(h, hpart, n_part, part_stride, gain, xn, d, M, Mcap, eps, s);
 }
 
-// rows of a row-major matrix -> chunk-major activation layout (used to feed embedding rows to the GEMM)
+// rows of a row-major matrix -> chunk-major activation layout (used to feed embedding rows to the GEMM);
+// `centre` (fp32 [d], may be null) is subtracted first
 template <typename T>
-__global__ __launch_bounds__(256) void pack_rows_kernel(const T *src, T *dst, int d, int Mcap) {
-  for (int i = threadIdx.x; i < d; i += 256) dst[act_offset<T>(blockIdx.x, i, Mcap)] = src[(size_t)blockIdx.x * d + i];
+__global__ __launch_bounds__(256) void pack_rows_kernel(const T *src, T *dst, int d, int Mcap, const float *centre) {
+  for (int i = threadIdx.x; i < d; i += 256) {
+    const T v = src[(size_t)blockIdx.x * d + i];
+    dst[act_offset<T>(blockIdx.x, i, Mcap)] = centre ? from_f32<T>(to_f32(v) - centre[i]) : v;
+  }
 }
 
-void launch_pack_rows(int dtype, const void *src, void *dst, int d, int M, int Mcap, hipStream_t s) {
-  if (dtype == 1) hipLaunchKernelGGL(pack_rows_kernel<bf16_t>, dim3(M), dim3(256), 0, s, (const bf16_t *)src, (bf16_t *)dst, d, Mcap);
-  else hipLaunchKernelGGL(pack_rows_kernel<float>, dim3(M), dim3(256), 0, s, (const float *)src, (float *)dst, d, Mcap);
+void launch_pack_rows(int dtype, const void *src, void *dst, int d, int M, int Mcap, hipStream_t s, const float *centre) {
+  if (dtype == 1) hipLaunchKernelGGL(pack_rows_kernel<bf16_t>, dim3(M), dim3(256), 0, s, (const bf16_t *)src, (bf16_t *)dst, d, Mcap, centre);
+  else hipLaunchKernelGGL(pack_rows_kernel<float>, dim3(M), dim3(256), 0, s, (const float *)src, (float *)dst, d, Mcap, centre);
+}
+
+// mean[i] = (1/N) sum over rows of src[n][i]: one workgroup per 256 columns, rows summed in index
+// order by every thread (deterministic); used once, for the mean output embedding of the unigram
+template <typename T>
+__global__ __launch_bounds__(256) void column_mean_kernel(const T *src, int N, int d, float *mean) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= d) return;
+  float acc = 0.0f;
+  for (int n = 0; n < N; ++n) acc += to_f32(src[(size_t)n * d + i]);
+  mean[i] = acc / (float)N;
+}
+
+void launch_column_mean(int dtype, const void *src, int N, int d, float *mean, hipStream_t s) {
+  if (dtype == 1) hipLaunchKernelGGL(column_mean_kernel<bf16_t>, dim3((d + 255) / 256), dim3(256), 0, s, (const bf16_t *)src, N, d, mean);
+  else hipLaunchKernelGGL(column_mean_kernel<float>, dim3((d + 255) / 256), dim3(256), 0, s, (const float *)src, N, d, mean);
+}
+
+// out[m] = -sum_v rows[m][v]^2 (the negated squared unigram distance: largest = nearest), one workgroup per row
+__global__ __launch_bounds__(256) void neg_row_sumsq_kernel(const float *__restrict__ rows, int V, float *__restrict__ out) {
+  __shared__ float sh[4];
+  const float *row = rows + (size_t)blockIdx.x * V;
+  float acc = 0.0f;
+  for (int i = threadIdx.x; i < V; i += 256) acc += row[i] * row[i];
+  acc = block_sum_256(acc, sh);
+  if (threadIdx.x == 0) out[blockIdx.x] = -acc;
+}
+
+void launch_neg_row_sumsq(const float *rows, int M, int V, float *out, hipStream_t s) {
+  hipLaunchKernelGGL(neg_row_sumsq_kernel, dim3(M), dim3(256), 0, s, rows, V, out);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -459,15 +493,20 @@ __global__ __launch_bounds__(64) void table_assemble_kernel(const DraftArgs a) {
     for (int t = 0; t < a.w; ++t) a.drafts[r * a.w + t] = a.ctx_rows[r * a.w + t];
     a.row_src[r] = 0;
   } else {
-    int t0 = a.bg_table[(size_t)a.hist[a.n - 1] * a.bg_K + (r - n_ctx)];
-    for (int t = 0; t < a.w; ++t) { a.drafts[r * a.w + t] = t0; t0 = a.bg_table[(size_t)t0 * a.bg_K]; }
+    // first token: the (r - n_ctx)-th ranked successor of the last token in the bigram table, or the
+    // (r - n_ctx)-th nearest token of the unigram (context-free); then each token's top-ranked successor
+    int t0 = a.uni_top ? a.uni_top[r - n_ctx] : a.bg_table[(size_t)a.hist[a.n - 1] * a.bg_K + (r - n_ctx)];
+    for (int t = 0; t < a.w; ++t) {
+      a.drafts[r * a.w + t] = t0;
+      t0 = a.bg_table ? a.bg_table[(size_t)t0 * a.bg_K] : a.next1[t0];
+    }
     a.row_src[r] = 1;
   }
 }
 
 void launch_build_drafts(int dtype, const DraftArgs &a, hipStream_t s) {
   hipLaunchKernelGGL(ctx_match_kernel, dim3(1), dim3(1024), 0, s, a);
-  if (a.bg_table) {
+  if (a.bg_table || a.uni_top) {
     hipLaunchKernelGGL(table_assemble_kernel, dim3(1), dim3(64), 0, s, a);
     return;
   }

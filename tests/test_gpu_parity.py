@@ -332,6 +332,57 @@ def test_full_model_bigram_table_bf16():
 
 
 # ---------------------------------------------------------------------------------------------
+# the model unigram (q = 0 drafts)
+# ---------------------------------------------------------------------------------------------
+
+def _check_unigram(top, d, tol):
+    """GPU ranking of the nearest tokens against the oracle's distances; swaps only between near-ties."""
+    order = oracle.rank_ids(-d, len(top))
+    swaps = 0
+    for g, o in zip(top, order):
+        if int(g) != int(o):
+            assert abs(d[int(g)] - d[int(o)]) < tol * np.max(d), f"unigram: GPU {g} vs oracle {o}"
+            swaps += 1
+    return swaps
+
+
+def test_unigram_drafts_fp32(tiny):
+    desc, run, w, prompt, model, ctx = tiny
+    with pytest.raises(ngg.NggError) as e:
+        ctx.bigram_source(2)                                   # not built yet
+    assert e.value.status == ngg.NGG_ESTATE
+    ctx.unigram_build(32)
+    top = ctx.debug_peek("uni_top", np.int32)[0]
+    ug = oracle.UnigramDrafts(w["tok_emb"], w["unemb"], oracle.Bigram(model.tok_emb, model.unemb))
+    assert _check_unigram(top, ug.d, TOL["f32"]) == 0
+    ctx.bigram_source(2)
+    try:
+        rep = lockstep_run(ctx, model, prompt, 30, run, TOL["f32"], bigram=ug)
+        rep2 = lockstep_run(ctx, model, prompt, 12, dict(k=16, w=6, k_ctx_max=3, q_min=1, q_max=3), TOL["f32"], bigram=ug, max_steps=3)
+    finally:
+        ctx.bigram_source(0)
+    print("unigram mode:", rep, rep2)
+    assert rep.tolerated_draft == 0 and rep2.tolerated_draft == 0 and rep.tolerated_argmax == 0
+
+
+def test_unigram_bf16_vocabulary_32000():
+    desc = si.reduced_layers(si.MODELS["small"], 2)
+    run = dict(si.RUNS["cfg2"], prompt_len=150, n_gen=16)
+    w, prompt, model, ctx = _setup(desc, run)
+    ctx.unigram_build(16)
+    top = ctx.debug_peek("uni_top", np.int32)[0]
+    ug = oracle.UnigramDrafts(w["tok_emb"], w["unemb"], oracle.Bigram(model.tok_emb, model.unemb))
+    swaps = _check_unigram(top, ug.d, TOL["bf16"])
+    ctx.bigram_source(2)
+    g_drafts, g_src, g_nctx = None, None, None
+    ctx.prefill(prompt)
+    g_drafts, g_src, g_nctx = ctx.build_drafts(run)
+    ctx.close()
+    print("bf16 unigram:", swaps, "near-tie swaps in 16;", list(top[:6]), "first draft tokens", list(g_drafts[g_nctx:, 0]))
+    assert list(g_drafts[g_nctx:, 0]) == [int(t) for t in top[:run["k"] - g_nctx]]      # rows start with the kept tokens, in order
+
+
+# ---------------------------------------------------------------------------------------------
 # bf16 configurations
 # ---------------------------------------------------------------------------------------------
 
