@@ -127,18 +127,32 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
         __syncthreads();
         stage_load(stage[cc % XD], max(ch + XD, 0));
         const T *xb = xs + (size_t)buf * ROWS * LDX + li * LDX + g * 8;
+        // X fragments are read from LDS one step ahead of the MFMAs that use them (unconditionally:
+        // during the warm-up group the buffer holds nothing yet and the values go unused)
+        constexpr bool XPRE = FM <= 4;                     // 128-row tiles have no registers to spare
+        Frag<T> xf[XPRE ? 2 : 1][FM];
+        if constexpr (XPRE) {
+#pragma unroll
+          for (int fm = 0; fm < FM; ++fm) xf[0][fm] = load_frag(xb + fm * 16 * LDX + wk * 32);
+        }
 #pragma unroll
         for (int i = 0; i < SPW; ++i) {
           const int slot = (cc * SPW + i) % RING;        // constant after unrolling
           const int ls = wk + WK * i;                    // step inside the chunk
-          if (!warm && ch < c1 && ch * SPC + ls < n_steps) {      // uniform per wave; no global load inside
-            Frag<T> xb_f[FM];
+          if constexpr (XPRE) {
+            if (i + 1 < SPW) {
 #pragma unroll
-            for (int fm = 0; fm < FM; ++fm) xb_f[fm] = load_frag(xb + fm * 16 * LDX + ls * 32);
+              for (int fm = 0; fm < FM; ++fm) xf[(i + 1) & 1][fm] = load_frag(xb + fm * 16 * LDX + (ls + WK) * 32);
+            }
+          } else {
+#pragma unroll
+            for (int fm = 0; fm < FM; ++fm) xf[0][fm] = load_frag(xb + fm * 16 * LDX + ls * 32);
+          }
+          if (!warm && ch < c1 && ch * SPC + ls < n_steps) {      // uniform per wave; no global load inside
 #pragma unroll
             for (int f = 0; f < FN; ++f)
 #pragma unroll
-              for (int fm = 0; fm < FM; ++fm) mma(acc[f][fm], ring[slot][f], xb_f[fm]);
+              for (int fm = 0; fm < FM; ++fm) mma(acc[f][fm], ring[slot][f], xf[XPRE ? (i & 1) : 0][fm]);
           }
           load_w(ring[slot], max((ci + cc) * SPW + i + RING, 0));
         }

@@ -1,7 +1,7 @@
 """Summarises the `kernels` view of a rocprofv3 result database (rocpd/sqlite): per-kernel count,
 average/min/max/total duration, and the gaps between consecutive kernels.
 
-  python -m paper_2411_03786_amd.prof_summary gpurun_out/prof/bench_results.db [rows]
+  python -m paper_2411_03786_amd.prof_summary <output dir>/bench_results.db [rows]
 """
 import sqlite3, sys, re
 db=sqlite3.connect(sys.argv[1]); cur=db.cursor()
