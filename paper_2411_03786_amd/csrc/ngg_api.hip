@@ -43,6 +43,7 @@ struct ngg_ctx {
   void *kcache = nullptr, *vcache = nullptr, *kscr = nullptr, *vscr = nullptr;
   float *h = nullptr, *hpart = nullptr, *part_o = nullptr, *part_ml = nullptr, *pmax_val = nullptr, *z = nullptr, *logits = nullptr;
   float *rope_cos = nullptr, *rope_sin = nullptr;
+  float *row_ss = nullptr;         // [Mcap][kNormSegs] sums of squares of the rows the last RMSNorm wrote
   int *pmax_idx = nullptr, *cand_idx = nullptr;
   float *cand_val = nullptr;
   void *xn = nullptr, *q = nullptr, *attn = nullptr, *act = nullptr;
@@ -135,13 +136,14 @@ ngg_status forward(ngg_ctx *c, int R, int C, int P, bool from_hist, int w, bool 
   const int n_splits = attention_splits(dt, d.head_dim, d.n_heads, M, P, c->max_splits);
   const size_t part_stride = (size_t)c->Mcap * d.d_model;
   const int ks_o = gemm_residual_splits(dt, d.d_model, dq), ks_down = gemm_residual_splits(dt, d.d_model, d.d_ffn);
+  const int ss_segs = rmsnorm_segments(d.d_model);
   int pending = 0;                                   // residual partials the next RMSNorm has to add
   for (int l = 0; l < d.n_layers; ++l) {
     const ngg_layer_weights &lw = c->layers[l];
     const size_t kv_layer = (size_t)l * d.n_kv_heads;
     char *kscr_l = (char *)c->kscr + kv_layer * c->Mcap * d.head_dim * c->esize;
     char *vscr_l = (char *)c->vscr + kv_layer * d.head_dim * c->Mcap * c->esize;
-    { ProfScope ps(c, NGG_PROF_NORM); launch_rmsnorm(dt, c->h, c->hpart, pending, part_stride, lw.attn_norm, c->xn, d.d_model, M, c->Mcap, d.rms_eps, s); }
+    { ProfScope ps(c, NGG_PROF_NORM); launch_rmsnorm(dt, c->h, c->hpart, pending, part_stride, lw.attn_norm, c->xn, d.d_model, M, c->Mcap, c->row_ss, s); }
     {
       ProfScope ps(c, NGG_PROF_GEMM_QKV);
       GemmArgs g{};
@@ -150,6 +152,7 @@ ngg_status forward(ngg_ctx *c, int R, int C, int P, bool from_hist, int w, bool 
       g.q = c->q; g.kscr = kscr_l; g.vscr = vscr_l;
       g.H = d.n_heads; g.Hkv = d.n_kv_heads; g.hd = d.head_dim; g.Mcap = c->Mcap; g.C = C; g.P = P;
       g.rope_cos = c->rope_cos; g.rope_sin = c->rope_sin;
+      g.row_ss = c->row_ss; g.ss_segs = ss_segs; g.ss_eps = d.rms_eps;
       launch_gemm(dt, EPI_QKV, g, s);
     }
     {
@@ -172,12 +175,13 @@ ngg_status forward(ngg_ctx *c, int R, int C, int P, bool from_hist, int w, bool 
       g.hpart = c->hpart; g.KS = ks_o; g.Mcap = c->Mcap;
       launch_gemm(dt, EPI_RESIDUAL, g, s);
     }
-    { ProfScope ps(c, NGG_PROF_NORM); launch_rmsnorm(dt, c->h, c->hpart, ks_o, part_stride, lw.mlp_norm, c->xn, d.d_model, M, c->Mcap, d.rms_eps, s); }
+    { ProfScope ps(c, NGG_PROF_NORM); launch_rmsnorm(dt, c->h, c->hpart, ks_o, part_stride, lw.mlp_norm, c->xn, d.d_model, M, c->Mcap, c->row_ss, s); }
     {
       ProfScope ps(c, NGG_PROF_GEMM_GATEUP);
       GemmArgs g{};
       g.X = c->xn; g.W0 = c->lt[l].wgu; g.M = M; g.N = d.d_ffn; g.K = d.d_model;
       g.act = c->act; g.Mcap = c->Mcap;
+      g.row_ss = c->row_ss; g.ss_segs = ss_segs; g.ss_eps = d.rms_eps;
       launch_gemm(dt, EPI_GATEUP, g, s);
     }
     {
@@ -190,12 +194,13 @@ ngg_status forward(ngg_ctx *c, int R, int C, int P, bool from_hist, int w, bool 
     pending = ks_down;
   }
   if (unembed) {
-    { ProfScope ps(c, NGG_PROF_NORM); launch_rmsnorm(dt, c->h, c->hpart, pending, part_stride, c->w.final_norm, c->xn, d.d_model, M, c->Mcap, d.rms_eps, s); }
+    { ProfScope ps(c, NGG_PROF_NORM); launch_rmsnorm(dt, c->h, c->hpart, pending, part_stride, c->w.final_norm, c->xn, d.d_model, M, c->Mcap, c->row_ss, s); }
     ProfScope ps(c, NGG_PROF_GEMM_UNEMBED);
     GemmArgs g{};
     g.X = c->xn; g.W0 = c->unemb_t; g.M = M; g.N = d.vocab; g.K = d.d_model;
     g.logits = want_logits ? c->logits : nullptr;
     g.pmax_val = c->pmax_val; g.pmax_idx = c->pmax_idx; g.Mcap = c->Mcap;
+    g.row_ss = c->row_ss; g.ss_segs = ss_segs; g.ss_eps = d.rms_eps;
     launch_gemm(dt, EPI_UNEMBED, g, s);
   }
   NGG_HIP(c, hipGetLastError());
@@ -274,7 +279,7 @@ ngg_status ngg_destroy(ngg_ctx *c) {
   (void)hipStreamSynchronize(c->stream);
   void *bufs[] = {c->hist, c->drafts, c->block_tok, c->res, c->next1, c->mlist, c->reps, c->ctx_rows, c->n_ctx,
                   c->row_src, c->hpart, c->wtiled, c->cand_val, c->cand_idx, c->kcache, c->vcache, c->kscr, c->vscr, c->h, c->part_o, c->part_ml, c->pmax_val, c->z,
-                  c->logits, c->rope_cos, c->rope_sin, c->pmax_idx, c->xn, c->q, c->attn, c->act, c->bg_table, c->bg_tok, c->uni_top};
+                  c->logits, c->rope_cos, c->rope_sin, c->pmax_idx, c->xn, c->q, c->attn, c->act, c->bg_table, c->bg_tok, c->uni_top, c->row_ss};
   for (void *b : bufs)
     if (b) (void)hipFree(b);
   if (c->res_host) (void)hipHostFree(c->res_host);
@@ -343,6 +348,7 @@ ngg_status ngg_create(const ngg_model_desc *desc, const ngg_weights *weights, vo
   TRY(dev_alloc(c, &c->kscr, kv_elems * c->Mcap * c->esize, true));
   TRY(dev_alloc(c, &c->vscr, kv_elems * c->Mcap * c->esize, true));
   TRY(dev_alloc(c, &c->h, (size_t)c->Mcap * d.d_model * 4, true));
+  TRY(dev_alloc(c, &c->row_ss, (size_t)c->Mcap * kNormSegs * 4, true));
   TRY(dev_alloc(c, &c->hpart, (size_t)kMaxResidualSplits * c->Mcap * d.d_model * 4, true));
   TRY(dev_alloc(c, &c->xn, act_elems(d.dtype, c->Mcap, d.d_model) * c->esize, true));
   TRY(dev_alloc(c, &c->q, (size_t)c->Mcap * dq * c->esize, true));

@@ -46,6 +46,16 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
   const int li = lane & 15, g = lane >> 4;
   const int wn = wave % WN, wk = wave / WN;
   const int K = a.K, M = a.M;
+  // When X holds h * gain, the RMSNorm kernel left the sums of squares of every row's segments
+  // (kNormSegs floats per row, unused ones zero); the epilogue turns them into 1 / rms.
+  static_assert(kNormSegs == 4, "one float4 per row");
+  auto row_ss_load = [&](int m) {                        // (f32x4, not float4: arrays of the HIP struct go to scratch)
+    if (!a.row_ss) return f32x4{0.f, 0.f, 0.f, 0.f};
+    return *reinterpret_cast<const f32x4 *>(a.row_ss + (size_t)(m < a.Mcap ? m : a.Mcap - 1) * kNormSegs);
+  };
+  auto row_scale = [&](const f32x4 &ss) {
+    return a.row_ss ? 1.0f / sqrtf((((ss[0] + ss[1]) + ss[2]) + ss[3]) / (float)K + a.ss_eps) : 1.0f;
+  };
   const int n_groups = a.n_groups;
   int group = blockIdx.x * WN + wn;
   const bool group_live = group < n_groups;
@@ -159,6 +169,10 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
       }
     }
     __syncthreads();                                     // everyone is done with xs
+    // 1 / rms of the pass's block rows, one per thread, left in LDS for the epilogues (fetched only now:
+    // the main loop keeps every vector register it can get)
+    float *rs_lds = reinterpret_cast<float *>(smem);     // [ROWS]; the hand-over buffers start behind it
+    if (tid < ROWS) rs_lds[tid] = row_scale(row_ss_load(m0 + tid));
 
     // ---- q/k/v and gate/up: every wave hands its partial fragments over through LDS; wave wk then
     //      sums items wk, wk + WK, ... of the FN x FM accumulator fragments (waves in the order 0 .. WK-1)
@@ -166,7 +180,7 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
     if constexpr (PAIRED) {
       // at most 4 column blocks of every fragment per round, so that the hand-over fits the LDS
       constexpr int FMR = FM < 4 ? FM : 4, ROUNDS = FM / FMR;
-      float *red = reinterpret_cast<float *>(smem);      // [WK][FN*FMR][4][64]
+      float *red = reinterpret_cast<float *>(smem) + ROWS;   // [WK][FN*FMR][4][64]
 #pragma unroll
       for (int rd = 0; rd < ROUNDS; ++rd) {
       if (rd > 0) __syncthreads();                       // the previous round's items were all read
@@ -190,10 +204,11 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
         }
         // lanes g < 2 hold rows 4g + r of the fragment (first members of the pairs), lanes g + 2 the
         // second members of the same pairs
+        const int m = m0 + fm * 16 + li;
+        const float rs = rs_lds[fm * 16 + li];
         float x2[4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) x2[r] = other_half(v[r]);
-        const int m = m0 + fm * 16 + li;
+        for (int r = 0; r < 4; ++r) { v[r] *= rs; x2[r] = other_half(v[r]); }
         if (m < M && g < 2 && frag < n_groups) {
           if constexpr (EPI == EPI_GATEUP) {
             float o[4];
@@ -240,8 +255,9 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
     }
 
     // ---- sum the WK waves that share a wn: wave (wn, 0) adds (wn, 1) .. (wn, WK-1) in that order ---
+    if constexpr (!PAIRED && WK == 1) __syncthreads();   // rs_lds is complete
     if constexpr (!PAIRED && WK > 1) {
-      float *red = reinterpret_cast<float *>(smem);      // [(WK-1)][WN][FN*FM*4][64]
+      float *red = reinterpret_cast<float *>(smem) + ROWS;   // [(WK-1)][WN][FN*FM*4][64]
       if (wk > 0) {
         float *dst = red + (size_t)((wk - 1) * WN + wn) * (FN * FM * 4 * 64);
 #pragma unroll
@@ -283,11 +299,12 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
         } else {   // EPI_UNEMBED: optional logits, and this wave's best (value, id) per column
           float bv = kNegBig;
           int bi = 0x7fffffff;
+          const float rs = rs_lds[fm * 16 + li];
 #pragma unroll
           for (int f = 0; f < FN; ++f)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-              const float v = acc[f][fm][r];
+              const float v = acc[f][fm][r] * rs;
               const int n = nbase[f] + 4 * g + r;
               if (a.logits && live) a.logits[(size_t)m * a.N + n] = v;
               if (v > bv) { bv = v; bi = n; }                 // ascending n: the first maximum stays
@@ -315,7 +332,8 @@ void launch_gemm_cfg(const GemmArgs &a, int KS, hipStream_t s) {
   constexpr int PAD = 16 / (int)sizeof(T);
   constexpr bool PAIRED = EPI == EPI_QKV || EPI == EPI_GATEUP;
   size_t lds = (size_t)2 * 16 * FM * (KC + PAD) * sizeof(T);
-  const size_t red = (size_t)(PAIRED ? WK * (FM < 4 ? FM : 4) : (WK - 1) * WN * FM) * FN * 4 * 64 * sizeof(float);
+  const size_t red = (size_t)(PAIRED ? WK * (FM < 4 ? FM : 4) : (WK - 1) * WN * FM) * FN * 4 * 64 * sizeof(float) +
+                     (size_t)16 * FM * sizeof(float);          // + one 1 / rms per block row of the pass
   if (red > lds) lds = red;
   const int blocks = PAIRED ? (a.n_groups + FN - 1) / FN : (a.n_groups + WN - 1) / WN;
   if (lds > 64 * 1024) {                     // more than the default dynamic LDS limit: opt in once
@@ -362,14 +380,17 @@ static void launch_paired_fm(const GemmArgs &a, hipStream_t s) {
           case 3: launch_gemm_cfg<T, EPI, FM, 1, 4, 2, 3>(a, 1, s); break;
           case 4: launch_gemm_cfg<T, EPI, FM, 1, 4, 2, 4>(a, 1, s); break;
           default:
-            if constexpr (FMAX >= 7) {
+            if constexpr (FMAX >= 6) {
               switch (fn) {
                 case 5: launch_gemm_cfg<T, EPI, FM, 1, 4, 2, 5>(a, 1, s); break;
                 case 6: launch_gemm_cfg<T, EPI, FM, 1, 4, 2, 6>(a, 1, s); break;
-                case 7: launch_gemm_cfg<T, EPI, FM, 1, 4, 2, 7>(a, 1, s); break;
                 default:
-                  if constexpr (FMAX >= 8) launch_gemm_cfg<T, EPI, FM, 1, 4, 2, 8>(a, 1, s);
-                  else launch_gemm_cfg<T, EPI, FM, 1, 4, 2, 7>(a, 1, s);
+                  if constexpr (FMAX >= 8) {
+                    if (fn == 7) launch_gemm_cfg<T, EPI, FM, 1, 4, 2, 7>(a, 1, s);
+                    else launch_gemm_cfg<T, EPI, FM, 1, 4, 2, 8>(a, 1, s);
+                  } else {
+                    launch_gemm_cfg<T, EPI, FM, 1, 4, 2, 7>(a, 1, s);   // 128-row tiles: 8 fragments no longer fit the registers
+                  }
               }
             }
         }

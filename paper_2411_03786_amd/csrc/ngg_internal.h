@@ -184,6 +184,11 @@ struct GemmArgs {
   const void *X;          // activations, chunk-major [K/KC][Mcap][KC], element type T
   const void *W0;         // weight matrix in operand order (QKV: rows [q | k | v]; gate/up: rows [gate | up])
   int M, N, K;            // N = total logical output rows
+  // q/k/v, gate/up, unembedding: X is h * gain; the epilogue multiplies row m by
+  // 1 / sqrt((row_ss[m][0] + .. + row_ss[m][ss_segs-1]) / K + ss_eps).  Null: X is used as it is.
+  const float *row_ss;
+  int ss_segs;
+  float ss_eps;
   int n_groups;           // residual, unembedding: pairs of 16-row fragments; q/k/v, gate/up: fragments (filled by the launcher)
   // EPI_RESIDUAL: split ks of KS stores its fp32 partial at hpart[ks][m][n]; the next RMSNorm adds them
   float *hpart;           // [KS][Mcap][N]
@@ -203,6 +208,7 @@ struct GemmArgs {
 };
 
 constexpr int kMaxResidualSplits = 8;
+constexpr int kNormSegs = 4;   // workgroups that may share a row of the RMSNorm; row_ss is [Mcap][kNormSegs]
 
 struct AttnArgs {
   const void *q;          // [H][Mcap][hd]
@@ -232,7 +238,8 @@ void launch_pack_rows(int dtype, const void *src, void *dst, int d, int M, int M
 void launch_column_mean(int dtype, const void *src, int N, int d, float *mean, hipStream_t s);
 void launch_neg_row_sumsq(const float *rows, int M, int V, float *out, hipStream_t s);
 void launch_rmsnorm(int dtype, float *h, const float *hpart, int n_part, size_t part_stride, const void *gain, void *xn,
-                    int d, int M, int Mcap, float eps, hipStream_t s);
+                    int d, int M, int Mcap, float *row_ss, hipStream_t s);
+int rmsnorm_segments(int d);
 
 struct DraftArgs {
   const int32_t *hist; int n;

@@ -37,7 +37,12 @@ void launch_embed(int dtype, const void *tok_emb, const int32_t *hist, const int
 }
 
 // ---------------------------------------------------------------------------------------------
-// RMSNorm: xn = h * rsqrt(mean(h^2) + eps) * gain, one workgroup per row.
+// RMSNorm, split in two: this kernel adds the residual partials, stores the new residual stream and
+// writes xg = h * gain (not yet divided by the root mean square) as the next GEMM's input, and the
+// sum of squares of its part of the row; the GEMM multiplies its accumulators by
+// 1 / sqrt(sum of squares / d + eps) in the epilogue (the GEMM is linear in its input rows).  That
+// lets `segs` workgroups share a row: a single workgroup per row left one CU to pull the whole row
+// and all its partials, with most CUs idle.
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ float block_sum_256(float v, float *sh) {
 #pragma unroll
@@ -49,15 +54,16 @@ __device__ __forceinline__ float block_sum_256(float v, float *sh) {
   return t;
 }
 
-// Every thread owns J groups of 4 consecutive features (group index tid + 256*j): all loads of the
-// row and of its residual partials are issued before anything is used, so the kernel costs one
-// memory round trip instead of one per feature.
+// Every thread owns J groups of 4 consecutive features of segment blockIdx.y (group index
+// tid + 256*j): all loads of the row and of its residual partials are issued before anything is
+// used, so the kernel costs one memory round trip instead of one per feature.
 template <typename T, int J>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(float *__restrict__ h, const float *__restrict__ hpart, int n_part,
                                                       size_t part_stride, const T *__restrict__ gain, T *__restrict__ xn,
-                                                      int d, int Mcap, float eps) {
+                                                      int d, int Mcap, float *__restrict__ row_ss) {
   __shared__ float sh[4];
-  const int m = blockIdx.x, d4 = d / 4;
+  const int m = blockIdx.x, segs = gridDim.y;
+  const int d4 = d / segs / 4, c4 = blockIdx.y * d4;       // float4 groups of this segment, first group
   float4 v[J];
   float4 gn[J];
 #pragma unroll
@@ -66,8 +72,8 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float *__restrict__ h, con
     v[j] = float4{0.f, 0.f, 0.f, 0.f};
     gn[j] = float4{0.f, 0.f, 0.f, 0.f};
     if (i4 < d4) {
-      v[j] = *reinterpret_cast<const float4 *>(h + (size_t)m * d + 4 * i4);
-      const T *gp = gain + 4 * i4;
+      v[j] = *reinterpret_cast<const float4 *>(h + (size_t)m * d + 4 * (c4 + i4));
+      const T *gp = gain + 4 * (c4 + i4);
       gn[j] = float4{to_f32(gp[0]), to_f32(gp[1]), to_f32(gp[2]), to_f32(gp[3])};
     }
   }
@@ -77,7 +83,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float *__restrict__ h, con
       for (int j = 0; j < J; ++j) {
         const int i4 = threadIdx.x + 256 * j;
         if (i4 < d4) {
-          const float4 p = *reinterpret_cast<const float4 *>(hpart + (size_t)s * part_stride + (size_t)m * d + 4 * i4);
+          const float4 p = *reinterpret_cast<const float4 *>(hpart + (size_t)s * part_stride + (size_t)m * d + 4 * (c4 + i4));
           v[j].x += p.x; v[j].y += p.y; v[j].z += p.z; v[j].w += p.w;
         }
       }
@@ -91,7 +97,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float *__restrict__ h, con
       for (int j = 0; j < J; ++j) {
         const int i4 = threadIdx.x + 256 * j;
         p[s][j] = float4{0.f, 0.f, 0.f, 0.f};
-        if (i4 < d4) p[s][j] = *reinterpret_cast<const float4 *>(hpart + (size_t)sc * part_stride + (size_t)m * d + 4 * i4);
+        if (i4 < d4) p[s][j] = *reinterpret_cast<const float4 *>(hpart + (size_t)sc * part_stride + (size_t)m * d + 4 * (c4 + i4));
       }
     }
 #pragma unroll
@@ -107,27 +113,32 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float *__restrict__ h, con
   for (int j = 0; j < J; ++j) {
     const int i4 = threadIdx.x + 256 * j;
     ss += v[j].x * v[j].x + v[j].y * v[j].y + v[j].z * v[j].z + v[j].w * v[j].w;
-    if (n_part > 0 && i4 < d4) *reinterpret_cast<float4 *>(h + (size_t)m * d + 4 * i4) = v[j];
-  }
-  ss = block_sum_256(ss, sh);
-  const float sc = 1.0f / sqrtf(ss / (float)d + eps);
-#pragma unroll
-  for (int j = 0; j < J; ++j) {
-    const int i4 = threadIdx.x + 256 * j;
     if (i4 < d4) {
-      T *o = xn + act_offset<T>(m, 4 * i4, Mcap);          // 4 features stay inside one chunk
-      store4(o, v[j].x * sc * gn[j].x, v[j].y * sc * gn[j].y, v[j].z * sc * gn[j].z, v[j].w * sc * gn[j].w);
+      if (n_part > 0) *reinterpret_cast<float4 *>(h + (size_t)m * d + 4 * (c4 + i4)) = v[j];
+      T *o = xn + act_offset<T>(m, 4 * (c4 + i4), Mcap);   // 4 features stay inside one chunk
+      store4(o, v[j].x * gn[j].x, v[j].y * gn[j].y, v[j].z * gn[j].z, v[j].w * gn[j].w);
     }
   }
+  ss = block_sum_256(ss, sh);
+  if (threadIdx.x == 0) row_ss[(size_t)m * kNormSegs + blockIdx.y] = ss;
+}
+
+// segments a row is split into: up to kNormSegs, each at least 1024 features wide
+int rmsnorm_segments(int d) {
+  int segs = d / 1024;
+  segs = segs < 1 ? 1 : (segs > kNormSegs ? kNormSegs : segs);
+  while (d % (segs * 4)) --segs;
+  return segs;
 }
 
 template <typename T>
 static void launch_rmsnorm_t(float *h, const float *hpart, int n_part, size_t part_stride, const void *gain, void *xn, int d,
-                             int M, int Mcap, float eps, hipStream_t s) {
-  const int j = (d / 4 + 255) / 256;
-#define NGG_NORM(J)                                                                                                  \
-  hipLaunchKernelGGL((rmsnorm_kernel<T, J>), dim3(M), dim3(256), 0, s, h, hpart, n_part, part_stride, (const T *)gain, \
-                     (T *)xn, d, Mcap, eps)
+                             int M, int Mcap, float *row_ss, hipStream_t s) {
+  const int segs = rmsnorm_segments(d);
+  const int j = (d / segs / 4 + 255) / 256;
+#define NGG_NORM(J)                                                                                                        \
+  hipLaunchKernelGGL((rmsnorm_kernel<T, J>), dim3(M, segs), dim3(256), 0, s, h, hpart, n_part, part_stride, (const T *)gain, \
+                     (T *)xn, d, Mcap, row_ss)
   if (j <= 1) NGG_NORM(1);
   else if (j <= 2) NGG_NORM(2);
   else if (j <= 4) NGG_NORM(4);
@@ -137,9 +148,9 @@ static void launch_rmsnorm_t(float *h, const float *hpart, int n_part, size_t pa
 }
 
 void launch_rmsnorm(int dtype, float *h, const float *hpart, int n_part, size_t part_stride, const void *gain, void *xn,
-                    int d, int M, int Mcap, float eps, hipStream_t s) {
-  if (dtype == 1) launch_rmsnorm_t<bf16_t>(h, hpart, n_part, part_stride, gain, xn, d, M, Mcap, eps, s);
-  else launch_rmsnorm_t<float>(h, hpart, n_part, part_stride, gain, xn, d, M, Mcap, eps, s);
+                    int d, int M, int Mcap, float *row_ss, hipStream_t s) {
+  if (dtype == 1) launch_rmsnorm_t<bf16_t>(h, hpart, n_part, part_stride, gain, xn, d, M, Mcap, row_ss, s);
+  else launch_rmsnorm_t<float>(h, hpart, n_part, part_stride, gain, xn, d, M, Mcap, row_ss, s);
 }
 
 // rows of a row-major matrix -> chunk-major activation layout (used to feed embedding rows to the GEMM);
