@@ -418,7 +418,9 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const AttnArgs a) {
   constexpr int DF = HD / 16;
   const int qb = blockIdx.x, h = blockIdx.y;
   const int S = a.n_splits, MB = a.Mcap / 16;
-  for (int idx = threadIdx.x; idx < DF * 64; idx += 256) {
+  // two workgroups per (16-query group, head), one per half of the output fragments: more CUs pull the partials
+  const int idx0 = blockIdx.z * (DF * 32), idx1 = idx0 + DF * 32;
+  for (int idx = idx0 + threadIdx.x; idx < idx1; idx += 256) {
     const int df = idx >> 6, lane = idx & 63;
     const int m = qb * 16 + (lane & 15), d4 = df * 16 + 4 * (lane >> 4);
     if (m >= a.M) continue;
@@ -480,7 +482,7 @@ static void launch_hd(const AttnArgs &a, hipStream_t s) {
   if (a.M <= 16) launch_stream<T, HD, 1>(a, s);
   else if (a.M <= 64 || attn_shared_qmax<T, HD>() == 1) launch_shared<T, HD, 1>(a, s);
   else launch_shared<T, HD, attn_shared_qmax<T, HD>()>(a, s);
-  hipLaunchKernelGGL((attn_merge_kernel<T, HD>), dim3((a.M + 15) / 16, a.H), dim3(256), 0, s, a);
+  hipLaunchKernelGGL((attn_merge_kernel<T, HD>), dim3((a.M + 15) / 16, a.H, 2), dim3(256), 0, s, a);
 }
 
 // Number of list slices per head: one workgroup per CU in total; two per CU for blocks of more than

@@ -23,7 +23,16 @@ __global__ __launch_bounds__(256) void embed_kernel(const T *tok_emb, const int3
   }
   if (threadIdx.x == 0) block_tok[m] = tok;
   const T *e = tok_emb + (size_t)tok * d;
-  for (int i = threadIdx.x; i < d; i += 256) h[(size_t)m * d + i] = to_f32(e[i]);
+  for (int i = 4 * threadIdx.x; i < d; i += 1024) {         // d is a multiple of 32: four elements per load
+    float4 v;
+    if constexpr (sizeof(T) == 2) {
+      const bf16x4 q = *reinterpret_cast<const bf16x4 *>(e + i);
+      v = float4{(float)q[0], (float)q[1], (float)q[2], (float)q[3]};
+    } else {
+      v = *reinterpret_cast<const float4 *>(e + i);
+    }
+    *reinterpret_cast<float4 *>(h + (size_t)m * d + i) = v;
+  }
 }
 
 void launch_embed(int dtype, const void *tok_emb, const int32_t *hist, const int32_t *drafts, int32_t *block_tok,
