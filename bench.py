@@ -158,11 +158,13 @@ def main():
         ctx.profile_enable(1 << ngg.PROF_CLASSES.index("gemm_gateup"))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    new_tokens = 0
-    for _ in range(args.steps):
-        new_tokens += step()
+    # exactly args.steps steps inside the library's own loop (ngg_decode_more: build_drafts, verify_step and
+    # commit back to back, one host sync per step for the accept result); the token budget is out of reach
+    toks, st = ctx.decode_more(args.steps * (w + 1) + w + 1, args.steps, run)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    assert st["calls"] == args.steps
+    new_tokens = len(toks)
     ctx.profile_enable(0)
     dom_ms, dom_n = (0.0, 0)
     if not args.no_kernel_events:
@@ -181,16 +183,13 @@ def main():
     breakdown = {name: {"ms_per_step": ms / 5, "launches_per_step": cnt / 5} for name, (ms, cnt) in prof.items() if cnt}
 
     # single-token decode step (k=1, w=0: one model call, no drafting) at the same context length
-    dec = []
-    for i in range(args.warmup + args.steps):
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        ctx.verify_step(None, 1, 0, fetch=False)
-        ctx.commit()
-        torch.cuda.synchronize()
-        if i >= args.warmup:
-            dec.append(time.perf_counter() - t1)
-    decode_ms = 1e3 * sum(dec) / len(dec)
+    ctx.decode_more(args.warmup, args.warmup, None) if args.warmup else None
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    _, st1 = ctx.decode_more(args.steps, args.steps, None)
+    torch.cuda.synchronize()
+    decode_ms = 1e3 * (time.perf_counter() - t1) / args.steps
+    assert st1["calls"] == args.steps
 
     M = k * (w + 1)
     step_bytes, _ = algorithmic_bytes(m, P_mid, M, with_bigram=not args.bigram_table)

@@ -152,6 +152,15 @@ ngg_status ngg_commit(ngg_ctx *ctx, int32_t max_new, int32_t *n_committed);
 ngg_status ngg_greedy_decode(ngg_ctx *ctx, const int32_t *prompt, int32_t n_prompt, int32_t n_gen,
                              const ngg_draft_cfg *cfg, int32_t *out_tokens, ngg_stats *stats);
 
+/* Continues from the committed state: (build_drafts, verify_step, commit) until
+ * n_gen more tokens were appended or max_calls verify calls were made, whichever
+ * comes first, without returning to the caller in between (a serving loop with
+ * no per-call host overhead).  cfg as in ngg_greedy_decode.  out_tokens: HOST
+ * [n_gen] or NULL; *n_out = tokens appended; stats cover these calls only
+ * (stats->tokens = tokens appended).  NGG_ESTATE before ngg_prefill. */
+ngg_status ngg_decode_more(ngg_ctx *ctx, int32_t n_gen, int32_t max_calls, const ngg_draft_cfg *cfg,
+                           int32_t *out_tokens, int32_t *n_out, ngg_stats *stats);
+
 /* The paper's own model bigram as a precomputed table (Section 4.1, "Model
  * bigram"; Appendix A builds the same lookup): p_M(. | x) is the next-token
  * distribution of the WHOLE model on the one-token context x.  For every

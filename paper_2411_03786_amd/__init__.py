@@ -22,7 +22,7 @@ PROF_CLASSES = ("gemm_qkv", "gemm_o", "gemm_gateup", "gemm_down", "gemm_unembed"
 
 EXPORTS = ("ngg_create", "ngg_destroy", "ngg_prefill", "ngg_build_drafts", "ngg_verify_step", "ngg_commit",
            "ngg_greedy_decode", "ngg_get_tokens", "ngg_last_error", "ngg_profile_enable", "ngg_profile_reset",
-           "ngg_profile_read", "ngg_debug_peek", "ngg_bigram_table_build", "ngg_bigram_source", "ngg_profile_bracket_overhead", "ngg_unigram_build")
+           "ngg_profile_read", "ngg_debug_peek", "ngg_bigram_table_build", "ngg_bigram_source", "ngg_profile_bracket_overhead", "ngg_unigram_build", "ngg_decode_more")
 
 
 class ngg_model_desc(C.Structure):
@@ -81,6 +81,7 @@ def load_library():
     lib.ngg_greedy_decode.argtypes = [vp, i32p, C.c_int32, C.c_int32, C.POINTER(ngg_draft_cfg), i32p,
                                       C.POINTER(ngg_stats)]
     lib.ngg_get_tokens.argtypes = [vp, i32p, C.c_int32, i32p]
+    lib.ngg_decode_more.argtypes = [vp, C.c_int32, C.c_int32, C.POINTER(ngg_draft_cfg), i32p, i32p, C.POINTER(ngg_stats)]
     lib.ngg_last_error.argtypes = [vp]
     lib.ngg_last_error.restype = C.c_char_p
     lib.ngg_profile_enable.argtypes = [vp, C.c_int32]
@@ -214,6 +215,13 @@ class Context:
         self._check(self.lib.ngg_commit(self.h, max_new, C.byref(n)))
         return n.value
 
+    @staticmethod
+    def _stats(st):
+        return dict(calls=st.calls, tokens=st.tokens, new_hist=list(st.new_hist), winner_src=list(st.winner_src),
+                    ctx_rows=st.ctx_rows, ms_prefill=st.ms_prefill, ms_drafts=st.ms_drafts, ms_verify=st.ms_verify,
+                    ms_commit=st.ms_commit, accept_hist=[list(r) for r in st.accept_hist],
+                    rank_hist=[list(r) for r in st.rank_hist], alloc_hist=list(st.alloc_hist))
+
     def greedy_decode(self, prompt, n_gen, cfg: dict | None):
         p = _i32(prompt)
         out = np.zeros(n_gen, dtype=np.int32)
@@ -221,11 +229,16 @@ class Context:
         c = None if cfg is None else ngg_draft_cfg(cfg["k"], cfg["w"], cfg["k_ctx_max"], cfg["q_min"], cfg["q_max"])
         self._check(self.lib.ngg_greedy_decode(self.h, _ptr(p), len(p), n_gen, C.byref(c) if c is not None else None,
                                                _ptr(out), C.byref(st)))
-        stats = dict(calls=st.calls, tokens=st.tokens, new_hist=list(st.new_hist), winner_src=list(st.winner_src),
-                     ctx_rows=st.ctx_rows, ms_prefill=st.ms_prefill, ms_drafts=st.ms_drafts, ms_verify=st.ms_verify,
-                     ms_commit=st.ms_commit, accept_hist=[list(r) for r in st.accept_hist],
-                     rank_hist=[list(r) for r in st.rank_hist], alloc_hist=list(st.alloc_hist))
-        return out, stats
+        return out, self._stats(st)
+
+    def decode_more(self, n_gen, max_calls, cfg: dict | None):
+        out = np.zeros(n_gen, dtype=np.int32)
+        n_out = C.c_int32(0)
+        st = ngg_stats()
+        c = None if cfg is None else ngg_draft_cfg(cfg["k"], cfg["w"], cfg["k_ctx_max"], cfg["q_min"], cfg["q_max"])
+        self._check(self.lib.ngg_decode_more(self.h, n_gen, max_calls, C.byref(c) if c is not None else None, _ptr(out),
+                                             C.byref(n_out), C.byref(st)))
+        return out[:n_out.value], self._stats(st)
 
     def profile_bracket_overhead(self):
         us = C.c_double(0.0)

@@ -412,7 +412,7 @@ ngg_status ngg_prefill(ngg_ctx *c, const int32_t *prompt, int32_t n_prompt) {
     if (st != NGG_OK) return st;
     ProfScope ps(c, NGG_PROF_ACCEPT_COMMIT);
     if (last)
-      launch_argmax_accept(c->pmax_val, c->pmax_idx, c->unembed_tiles, c->Mcap, C, 0, C, nullptr, c->res,
+      launch_argmax_accept(c->pmax_val, c->pmax_idx, c->unembed_tiles, c->Mcap, C, 0, C, nullptr, nullptr, nullptr, c->res,
                            res_greedy_off(d.max_k), c->stream);
     launch_commit(d.dtype, c->kcache, c->vcache, c->kscr, c->vscr, d.n_layers, d.n_kv_heads, d.head_dim, c->Spad,
                   c->Mcap, C, p0, nullptr, 0, C, C, c->hist, c->stream);
@@ -489,7 +489,8 @@ ngg_status ngg_verify_step(ngg_ctx *c, const int32_t *drafts, int32_t k, int32_t
   const int goff = res_greedy_off(d.max_k);
   {
     ProfScope ps(c, NGG_PROF_ACCEPT_COMMIT);
-    launch_argmax_accept(c->pmax_val, c->pmax_idx, c->unembed_tiles, c->Mcap, M, k, C, c->drafts, c->res, goff, c->stream);
+    launch_argmax_accept(c->pmax_val, c->pmax_idx, c->unembed_tiles, c->Mcap, M, k, C, c->drafts, c->row_src, c->n_ctx, c->res, goff,
+                         c->stream);
   }
   NGG_HIP(c, hipGetLastError());
   NGG_HIP(c, hipMemcpyAsync(c->res_host, c->res, (size_t)(goff + M) * 4, hipMemcpyDeviceToHost, c->stream));
@@ -529,27 +530,19 @@ ngg_status ngg_commit(ngg_ctx *c, int32_t max_new, int32_t *n_committed) {
   return NGG_OK;
 }
 
-ngg_status ngg_greedy_decode(ngg_ctx *c, const int32_t *prompt, int32_t n_prompt, int32_t n_gen, const ngg_draft_cfg *cfg,
-                             int32_t *out_tokens, ngg_stats *stats) {
-  if (!c) return NGG_EINVAL;
-  if (!out_tokens || n_gen < 1) return fail(c, NGG_EINVAL, "ngg_greedy_decode: need out_tokens and n_gen >= 1");
-  if ((long)n_prompt + n_gen > c->d.max_seq) return fail(c, NGG_ECAPACITY, "ngg_greedy_decode: %d + %d tokens exceed max_seq=%d", n_prompt, n_gen, c->d.max_seq);
-  ngg_draft_cfg plain{1, 0, 0, 1, 1};
-  if (!cfg) cfg = &plain;
-  ngg_stats st{};
-  double t0 = now_ms();
-  ngg_status rc = ngg_prefill(c, prompt, n_prompt);
-  if (rc != NGG_OK) return rc;
-  st.ms_prefill = now_ms() - t0;
-  std::vector<int8_t> src(cfg->k);
-  while (c->n - n_prompt < n_gen) {
+// (build_drafts, verify_step, commit) until n_gen tokens were appended after position n0 or max_calls
+// verify calls were made
+static ngg_status decode_loop(ngg_ctx *c, int n0, int n_gen, int64_t max_calls, const ngg_draft_cfg *cfg, ngg_stats &st) {
+  int64_t calls = 0;
+  while (c->n - n0 < n_gen && calls < max_calls) {
     // drafts wider than the remaining budget are pointless, and n + w must stay within max_seq
     ngg_draft_cfg step = *cfg;
-    const int left = n_gen - (c->n - n_prompt);
+    const int left = n_gen - (c->n - n0);
     step.w = std::min(step.w, std::max(0, std::min(left - 1, c->d.max_seq - c->n)));
-    int32_t n_ctx = 0;
-    t0 = now_ms();
-    rc = ngg_build_drafts(c, &step, nullptr, src.data(), &n_ctx);
+    double t0 = now_ms();
+    // nothing is fetched here, so the forward pass is queued while the drafts are still being built; the
+    // accept kernel hands the builder's row bookkeeping back with the result
+    ngg_status rc = ngg_build_drafts(c, &step, nullptr, nullptr, nullptr);
     if (rc != NGG_OK) return rc;
     double t1 = now_ms();
     ngg_verify_out vo{};
@@ -562,17 +555,56 @@ ngg_status ngg_greedy_decode(ngg_ctx *c, const int32_t *prompt, int32_t n_prompt
     double t3 = now_ms();
     st.ms_drafts += t1 - t0; st.ms_verify += t2 - t1; st.ms_commit += t3 - t2;
     st.calls += 1;
+    st.tokens += n_new;
     st.new_hist[n_new] += 1;
-    const int ws = src[vo.winner] ? 1 : 0;
+    const int n_ctx = c->res_host[RES_NCTX];
+    const int ws = c->res_host[RES_WINSRC] ? 1 : 0;
     st.winner_src[ws] += 1;
     st.ctx_rows += n_ctx;
     st.accept_hist[ws][vo.n_accept] += 1;
     if (vo.n_accept > 0) st.rank_hist[ws][ws ? vo.winner - n_ctx : vo.winner] += 1;
     st.alloc_hist[n_ctx] += 1;
+    ++calls;
   }
   NGG_HIP(c, hipStreamSynchronize(c->stream));
+  return NGG_OK;
+}
+
+ngg_status ngg_greedy_decode(ngg_ctx *c, const int32_t *prompt, int32_t n_prompt, int32_t n_gen, const ngg_draft_cfg *cfg,
+                             int32_t *out_tokens, ngg_stats *stats) {
+  if (!c) return NGG_EINVAL;
+  if (!out_tokens || n_gen < 1) return fail(c, NGG_EINVAL, "ngg_greedy_decode: need out_tokens and n_gen >= 1");
+  if ((long)n_prompt + n_gen > c->d.max_seq) return fail(c, NGG_ECAPACITY, "ngg_greedy_decode: %d + %d tokens exceed max_seq=%d", n_prompt, n_gen, c->d.max_seq);
+  ngg_draft_cfg plain{1, 0, 0, 1, 1};
+  if (!cfg) cfg = &plain;
+  ngg_stats st{};
+  double t0 = now_ms();
+  ngg_status rc = ngg_prefill(c, prompt, n_prompt);
+  if (rc != NGG_OK) return rc;
+  st.ms_prefill = now_ms() - t0;
+  rc = decode_loop(c, n_prompt, n_gen, INT64_MAX, cfg, st);
+  if (rc != NGG_OK) return rc;
   st.tokens = n_gen;
   memcpy(out_tokens, c->tokens.data() + n_prompt, (size_t)n_gen * 4);
+  if (stats) *stats = st;
+  return NGG_OK;
+}
+
+ngg_status ngg_decode_more(ngg_ctx *c, int32_t n_gen, int32_t max_calls, const ngg_draft_cfg *cfg, int32_t *out_tokens,
+                           int32_t *n_out, ngg_stats *stats) {
+  if (!c) return NGG_EINVAL;
+  if (c->n < 1) return fail(c, NGG_ESTATE, "ngg_decode_more: no context (call ngg_prefill first)");
+  if (n_gen < 1 || max_calls < 1) return fail(c, NGG_EINVAL, "ngg_decode_more: need n_gen >= 1 and max_calls >= 1");
+  if ((long)c->n + n_gen > c->d.max_seq) return fail(c, NGG_ECAPACITY, "ngg_decode_more: %d + %d tokens exceed max_seq=%d", c->n, n_gen, c->d.max_seq);
+  ngg_draft_cfg plain{1, 0, 0, 1, 1};
+  if (!cfg) cfg = &plain;
+  ngg_stats st{};
+  const int n0 = c->n;
+  ngg_status rc = decode_loop(c, n0, n_gen, max_calls, cfg, st);
+  if (rc != NGG_OK) return rc;
+  const int made = c->n - n0;
+  if (out_tokens) memcpy(out_tokens, c->tokens.data() + n0, (size_t)made * 4);
+  if (n_out) *n_out = made;
   if (stats) *stats = st;
   return NGG_OK;
 }

@@ -172,7 +172,9 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
     // 1 / rms of the pass's block rows, one per thread, left in LDS for the epilogues (fetched only now:
     // the main loop keeps every vector register it can get)
     float *rs_lds = reinterpret_cast<float *>(smem);     // [ROWS]; the hand-over buffers start behind it
-    if (tid < ROWS) rs_lds[tid] = row_scale(row_ss_load(m0 + tid));
+    if constexpr (!PAIRED) {
+      if (tid < ROWS) rs_lds[tid] = row_scale(row_ss_load(m0 + tid));
+    }
 
     // ---- q/k/v and gate/up: every wave hands its partial fragments over through LDS; wave wk then
     //      sums items wk, wk + WK, ... of the FN x FM accumulator fragments (waves in the order 0 .. WK-1)
@@ -180,32 +182,39 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
     if constexpr (PAIRED) {
       // at most 4 column blocks of every fragment per round, so that the hand-over fits the LDS
       constexpr int FMR = FM < 4 ? FM : 4, ROUNDS = FM / FMR;
-      float *red = reinterpret_cast<float *>(smem) + ROWS;   // [WK][FN*FMR][4][64]
+      constexpr int ITEMS = FN * FMR, IPW = (ITEMS + WK - 1) / WK;   // items per round, per wave
+      static_assert(WK % FMR == 0, "a wave's items of one round share their column block");
+      f32x4 *red = reinterpret_cast<f32x4 *>(smem + ROWS * sizeof(float));   // [WK][ITEMS][64] lanes x 4 registers
+      // item idx = f * FMR + fr covers column block rd * FMR + fr; wave wk takes idx = wk, wk + WK, ..., all of
+      // column block rd * FMR + wk % FMR: one 1 / rms per lane and round, fetched while the hand-over runs
+      f32x4 ss[ROUNDS];
+#pragma unroll
+      for (int rd = 0; rd < ROUNDS; ++rd) ss[rd] = row_ss_load(m0 + (rd * FMR + wk % FMR) * 16 + li);
 #pragma unroll
       for (int rd = 0; rd < ROUNDS; ++rd) {
       if (rd > 0) __syncthreads();                       // the previous round's items were all read
 #pragma unroll
       for (int f = 0; f < FN; ++f)
 #pragma unroll
-        for (int fr = 0; fr < FMR; ++fr)
-#pragma unroll
-          for (int r = 0; r < 4; ++r)
-            red[(((size_t)wk * FN * FMR + f * FMR + fr) * 4 + r) * 64 + lane] = acc[f][rd * FMR + fr][r];
+        for (int fr = 0; fr < FMR; ++fr) red[((size_t)wk * ITEMS + f * FMR + fr) * 64 + lane] = acc[f][rd * FMR + fr];
       __syncthreads();
-      for (int idx = wk; idx < FN * FMR; idx += WK) {
-        const int f = idx / FMR, fm = rd * FMR + (idx - f * FMR);
+      const int fm = rd * FMR + wk % FMR;
+      const int m = m0 + fm * 16 + li;
+      const float rs = row_scale(ss[rd]);
+#pragma unroll
+      for (int j = 0; j < IPW; ++j) {
+        const int idx = wk + WK * j;
+        if (idx >= ITEMS) break;
+        const int f = idx / FMR;
         const int frag = blockIdx.x * FN + f;              // fragment index over the whole matrix
+        f32x4 sum = red[(size_t)idx * 64 + lane];
+#pragma unroll
+        for (int o = 1; o < WK; ++o) sum += red[((size_t)o * ITEMS + idx) * 64 + lane];
         float v[4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          v[r] = red[((size_t)idx * 4 + r) * 64 + lane];
-#pragma unroll
-          for (int o = 1; o < WK; ++o) v[r] += red[(((size_t)o * FN * FMR + idx) * 4 + r) * 64 + lane];
-        }
+        for (int r = 0; r < 4; ++r) v[r] = sum[r];
         // lanes g < 2 hold rows 4g + r of the fragment (first members of the pairs), lanes g + 2 the
         // second members of the same pairs
-        const int m = m0 + fm * 16 + li;
-        const float rs = rs_lds[fm * 16 + li];
         float x2[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) { v[r] *= rs; x2[r] = other_half(v[r]); }
@@ -213,7 +222,7 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
           if constexpr (EPI == EPI_GATEUP) {
             float o[4];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) o[r] = v[r] / (1.0f + expf(-v[r])) * x2[r];      // silu(gate) * up
+            for (int r = 0; r < 4; ++r) o[r] = silu<T>(v[r]) * x2[r];
             store4((T *)a.act + act_offset<T>(m, frag * 8 + 4 * g, a.Mcap), o[0], o[1], o[2], o[3]);   // 4 features, one chunk
           } else {
             const int half = a.hd / 2, fph = a.hd / 16;    // fragments per head

@@ -171,9 +171,14 @@ __device__ __forceinline__ float other_half(float x) {
   return __uint_as_float((threadIdx.x & 32) ? b[0] : b[1]);
 }
 
-template <typename T> __device__ __forceinline__ float fast_exp(float x);
-template <> __device__ __forceinline__ float fast_exp<float>(float x) { return expf(x); }
-template <> __device__ __forceinline__ float fast_exp<bf16_t>(float x) { return __expf(x); }
+// x * sigmoid(x).  The bf16 configuration rounds the product to 8 mantissa bits anyway, so it takes
+// the hardware's base-2 exponential and reciprocal (about 1 ulp of fp32 each) in place of expf and
+// an IEEE division, which cost ten times the instructions; overflow of the exponential gives x * 0.
+template <typename T> __device__ __forceinline__ float silu(float x);
+template <> __device__ __forceinline__ float silu<float>(float x) { return x / (1.0f + expf(-x)); }
+template <> __device__ __forceinline__ float silu<bf16_t>(float x) {
+  return x * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * x));
+}
 
 // ---------------------------------------------------------------------------------------------
 // Launch descriptions (plain structs passed by value to the kernels).
@@ -274,11 +279,12 @@ void launch_tile_weights(int dtype, const void *src, void *dst, int N, int K, in
                          int half = 0);
 
 // result block layout (int32 words)
-enum { RES_WINNER = 0, RES_NACCEPT = 1, RES_NNEW = 2, RES_NCTX = 3, RES_NEWTOK = 8, RES_ACCEPT = 48 };
+enum { RES_WINNER = 0, RES_NACCEPT = 1, RES_NNEW = 2, RES_NCTX = 3, RES_WINSRC = 4, RES_NEWTOK = 8, RES_ACCEPT = 48 };
 inline int res_greedy_off(int max_k) { return RES_ACCEPT + ((max_k + 7) / 8) * 8; }
 
 void launch_argmax_accept(const float *pmax_val, const int *pmax_idx, int tiles, int Mcap, int M, int k, int C,
-                          const int32_t *drafts, int32_t *res, int greedy_off, hipStream_t s);
+                          const int32_t *drafts, const int8_t *row_src, const int32_t *n_ctx, int32_t *res, int greedy_off,
+                          hipStream_t s);
 void launch_commit(int dtype, void *kcache, void *vcache, const void *kscr, const void *vscr, int L, int Hkv, int hd,
                    int Spad, int Mcap, int C, int P, const int32_t *res, int fixed_row, int fixed_n, int max_new,
                    int32_t *hist, hipStream_t s);

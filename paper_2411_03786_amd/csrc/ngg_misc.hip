@@ -525,11 +525,13 @@ __global__ __launch_bounds__(64) void table_assemble_kernel(const DraftArgs a) {
 }
 
 void launch_build_drafts(int dtype, const DraftArgs &a, hipStream_t s) {
-  hipLaunchKernelGGL(ctx_match_kernel, dim3(1), dim3(1024), 0, s, a);
   if (a.bg_table || a.uni_top) {
+    hipLaunchKernelGGL(ctx_match_kernel, dim3(1), dim3(1024), 0, s, a);
     hipLaunchKernelGGL(table_assemble_kernel, dim3(1), dim3(64), 0, s, a);
     return;
   }
+  // the sweep first: it is the long kernel, and while it runs the host gets the short ones queued
+  // (a step starts with an idle queue, where every launch costs its full submission latency)
   if (a.w >= 1) {
     const int n_groups = a.vocab / 16, gpb = (n_groups + kGemvBlocks - 1) / kGemvBlocks;
     const size_t lds = (size_t)a.d * (dtype == 1 ? 2 : 4) + (size_t)gpb * 16 * sizeof(float);
@@ -540,6 +542,7 @@ void launch_build_drafts(int dtype, const DraftArgs &a, hipStream_t s) {
       hipLaunchKernelGGL(bigram_gemv_kernel<float>, dim3(kGemvBlocks), dim3(256), lds, s, (const float *)a.tok_emb,
                          (const float *)a.unemb_t, a.hist, a.n, a.d, a.vocab, a.k, a.z, a.cand_val, a.cand_idx);
   }
+  hipLaunchKernelGGL(ctx_match_kernel, dim3(1), dim3(1024), 0, s, a);
   hipLaunchKernelGGL(topk_assemble_kernel, dim3(1), dim3(1024), 0, s, a);
 }
 
@@ -588,7 +591,8 @@ __global__ __launch_bounds__(256) void argmax_reduce_kernel(const float *__restr
   }
 }
 
-__global__ __launch_bounds__(64) void accept_kernel(int k, int C, const int32_t *drafts, int32_t *res, int greedy_off) {
+__global__ __launch_bounds__(64) void accept_kernel(int k, int C, const int32_t *drafts, const int8_t *row_src,
+                                                    const int32_t *n_ctx, int32_t *res, int greedy_off) {
   const int tid = threadIdx.x;
   const int32_t *greedy = res + greedy_off;
   const int w = C - 1;
@@ -607,13 +611,17 @@ __global__ __launch_bounds__(64) void accept_kernel(int k, int C, const int32_t 
     res[RES_NNEW] = best + 1;
     for (int i = 0; i < best; ++i) res[RES_NEWTOK + i] = drafts[win * w + i];
     res[RES_NEWTOK + best] = greedy[win * C + best];
+    // what the draft builder left about these rows travels with the result
+    res[RES_NCTX] = *n_ctx;
+    res[RES_WINSRC] = row_src[win];
   }
 }
 
 void launch_argmax_accept(const float *pmax_val, const int *pmax_idx, int tiles, int Mcap, int M, int k, int C,
-                          const int32_t *drafts, int32_t *res, int greedy_off, hipStream_t s) {
+                          const int32_t *drafts, const int8_t *row_src, const int32_t *n_ctx, int32_t *res, int greedy_off,
+                          hipStream_t s) {
   hipLaunchKernelGGL(argmax_reduce_kernel, dim3(M), dim3(256), 0, s, pmax_val, pmax_idx, tiles, Mcap, res + greedy_off);
-  if (k > 0) hipLaunchKernelGGL(accept_kernel, dim3(1), dim3(64), 0, s, k, C, drafts, res, greedy_off);
+  if (k > 0) hipLaunchKernelGGL(accept_kernel, dim3(1), dim3(64), 0, s, k, C, drafts, row_src, n_ctx, res, greedy_off);
 }
 
 void launch_next1_finish(const float *pmax_val, const int *pmax_idx, int tiles, int Mcap, int M, int32_t *next1_out,

@@ -60,6 +60,39 @@ def test_cfg1_matches_oracle_plain_greedy_and_gpu_plain_equals_speculative(tiny)
     assert sum(stats["alloc_hist"]) == stats["calls"] == sum(map(sum, stats["accept_hist"]))
 
 
+def test_decode_more_in_pieces_equals_greedy_decode_and_the_oracle(tiny):
+    """The library-side loop resumed from the committed state: pieces of at most 3 verify calls, the token
+    budget shrinking as in one greedy_decode call, give its tokens and its statistics, and the oracle's."""
+    desc, run, w, prompt, model, ctx = tiny
+    want = oracle.greedy_plain_cached(model, prompt, 40)
+    _, whole = ctx.greedy_decode(prompt, 40, run)
+    ctx.prefill(prompt)                                   # appends the first token
+    toks, left, total = [int(ctx.get_tokens()[-1])], 39, None
+    while left > 0:
+        out, st = ctx.decode_more(left, 3, run)
+        assert 1 <= st["calls"] <= 3 and st["tokens"] == len(out) >= st["calls"]
+        toks += [int(t) for t in out]
+        left -= len(out)
+        if total is None:
+            total = st
+        else:
+            for key in ("calls", "ctx_rows"):
+                total[key] += st[key]
+            for key in ("new_hist", "winner_src", "alloc_hist"):
+                total[key] = [a + b for a, b in zip(total[key], st[key])]
+            for key in ("accept_hist", "rank_hist"):
+                total[key] = [[a + b for a, b in zip(ra, rb)] for ra, rb in zip(total[key], st[key])]
+    assert toks == want and list(ctx.get_tokens()) == list(prompt) + want
+    for key in ("calls", "ctx_rows", "new_hist", "winner_src", "alloc_hist", "accept_hist", "rank_hist"):
+        assert total[key] == whole[key], key
+    with pytest.raises(ngg.NggError) as e:
+        ctx.decode_more(0, 1, run)
+    assert e.value.status == ngg.NGG_EINVAL
+    with pytest.raises(ngg.NggError) as e:
+        ctx.decode_more(10 ** 6, 1, run)
+    assert e.value.status == ngg.NGG_ECAPACITY
+
+
 def test_injected_drafts_every_accept_length(tiny):
     desc, run, w, prompt, model, ctx = tiny
     V = desc["vocab"]
