@@ -208,6 +208,10 @@ enum {
 };
 ngg_status ngg_profile_enable(ngg_ctx *ctx, int32_t class_mask);
 ngg_status ngg_profile_reset(ngg_ctx *ctx);
+/* Brackets only one launch in every `every` of each enabled class (default 1 = all): a bracket costs
+ * about 5 us of stream time, so a whole step is timed with a sparse sample (an `every` coprime to the
+ * launches of the class per step walks through the layers). */
+ngg_status ngg_profile_sample(ngg_ctx *ctx, int32_t every);
 ngg_status ngg_profile_read(ngg_ctx *ctx, double *ms /*[NGG_PROF_COUNT]*/, int64_t *launches /*[NGG_PROF_COUNT]*/);
 /* What a bracket of two events reads around an EMPTY kernel on the context's
  * stream, in microseconds (mean of 64 brackets queued back to back): the part of every ngg_profile_read time

@@ -22,7 +22,7 @@ PROF_CLASSES = ("gemm_qkv", "gemm_o", "gemm_gateup", "gemm_down", "gemm_unembed"
 
 EXPORTS = ("ngg_create", "ngg_destroy", "ngg_prefill", "ngg_build_drafts", "ngg_verify_step", "ngg_commit",
            "ngg_greedy_decode", "ngg_get_tokens", "ngg_last_error", "ngg_profile_enable", "ngg_profile_reset",
-           "ngg_profile_read", "ngg_debug_peek", "ngg_bigram_table_build", "ngg_bigram_source", "ngg_profile_bracket_overhead", "ngg_unigram_build", "ngg_decode_more")
+           "ngg_profile_read", "ngg_debug_peek", "ngg_bigram_table_build", "ngg_bigram_source", "ngg_profile_bracket_overhead", "ngg_unigram_build", "ngg_decode_more", "ngg_profile_sample")
 
 
 class ngg_model_desc(C.Structure):
@@ -86,6 +86,7 @@ def load_library():
     lib.ngg_last_error.restype = C.c_char_p
     lib.ngg_profile_enable.argtypes = [vp, C.c_int32]
     lib.ngg_profile_reset.argtypes = [vp]
+    lib.ngg_profile_sample.argtypes = [vp, C.c_int32]
     lib.ngg_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     lib.ngg_debug_peek.argtypes = [vp, C.c_char_p, vp, C.c_int64, C.POINTER(C.c_int64), i32p]
     lib.ngg_bigram_table_build.argtypes = [vp, C.c_int32]
@@ -275,6 +276,9 @@ class Context:
 
     def profile_enable(self, class_mask=-1):
         self._check(self.lib.ngg_profile_enable(self.h, int(class_mask)))
+
+    def profile_sample(self, every=1):
+        self._check(self.lib.ngg_profile_sample(self.h, int(every)))
 
     def profile_reset(self):
         self._check(self.lib.ngg_profile_reset(self.h))

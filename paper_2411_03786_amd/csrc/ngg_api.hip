@@ -63,6 +63,8 @@ struct ngg_ctx {
   std::string err;
   // profiling
   int prof_mask = 0;               // bit i: record events around kernels of class i
+  int prof_every = 1;              // ... around one launch in every prof_every of a class
+  int64_t prof_seen[NGG_PROF_COUNT] = {};
   std::vector<ProfSpan> spans;
   std::vector<hipEvent_t> free_events;
 };
@@ -94,6 +96,7 @@ struct ProfScope {
   bool on;
   ProfScope(ngg_ctx *ctx, int cls) : c(ctx), on(((ctx->prof_mask >> cls) & 1) != 0) {
     if (!on) return;
+    if (c->prof_seen[cls]++ % c->prof_every != 0) { on = false; return; }
     sp.cls = cls;
     for (hipEvent_t *e : {&sp.e0, &sp.e1}) {
       if (!c->free_events.empty()) { *e = c->free_events.back(); c->free_events.pop_back(); }
@@ -622,11 +625,19 @@ ngg_status ngg_profile_enable(ngg_ctx *c, int32_t class_mask) {
   return NGG_OK;
 }
 
+ngg_status ngg_profile_sample(ngg_ctx *c, int32_t every) {
+  if (!c) return NGG_EINVAL;
+  if (every < 1) return fail(c, NGG_EINVAL, "ngg_profile_sample: every must be >= 1");
+  c->prof_every = every;
+  return NGG_OK;
+}
+
 ngg_status ngg_profile_reset(ngg_ctx *c) {
   if (!c) return NGG_EINVAL;
   NGG_HIP(c, hipStreamSynchronize(c->stream));
   for (auto &sp : c->spans) { c->free_events.push_back(sp.e0); c->free_events.push_back(sp.e1); }
   c->spans.clear();
+  for (auto &n : c->prof_seen) n = 0;
   return NGG_OK;
 }
 
