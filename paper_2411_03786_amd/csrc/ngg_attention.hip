@@ -156,9 +156,9 @@ __global__ __launch_bounds__(256) void attn_stream_kernel(const AttnArgs a, int 
 #pragma unroll
     for (int f = 0; f < 2; ++f)
 #pragma unroll
-      for (int ds = 0; ds < DS; ++ds) kr[f][ds] = load_frag_tiled(kp + (f * DS + ds) * 512);
+      for (int ds = 0; ds < DS; ++ds) kr[f][ds] = load_frag_stream(kp + (f * DS + ds) * 512);
 #pragma unroll
-    for (int df = 0; df < DF; ++df) vr[df] = load_frag_tiled(vp + df * 512);
+    for (int df = 0; df < DF; ++df) vr[df] = load_frag_stream(vp + df * 512);
   };
 
   const float sfac = Softmax<T>::factor(a.scale);

@@ -118,7 +118,7 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
       int s = c0 * SPC + (t / SPW) * SPC + wk + WK * (t % SPW);   // t >= 0 here
       s = s < n_steps ? s : n_steps - 1;
 #pragma unroll
-      for (int f = 0; f < FN; ++f) slot[f] = load_frag_tiled(wblk[f] + (size_t)s * 512);
+      for (int f = 0; f < FN; ++f) slot[f] = load_frag_stream(wblk[f] + (size_t)s * 512);
     };
 
     // The loop has no separate prologue: it starts one unrolled group early (ci = -UC) with the

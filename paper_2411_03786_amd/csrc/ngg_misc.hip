@@ -330,7 +330,7 @@ __global__ __launch_bounds__(256) void bigram_gemv_kernel(const T *tok_emb, cons
   int pg = 0, ps = 0;                                       // prefetch cursor: (group counter, step)
   auto next_frag = [&]() {                                  // past the end it repeats an in-bounds load
     const int grp = min(g0 + wave + 4 * pg, n_groups - 1);
-    const Frag<T> f = load_frag_tiled(tiled_block(unemb_t, grp, n_steps, lane) + (size_t)ps * 512);
+    const Frag<T> f = load_frag_stream(tiled_block(unemb_t, grp, n_steps, lane) + (size_t)ps * 512);
     if (pg < my_groups && ++ps == n_steps) { ps = 0; ++pg; }
     return f;
   };

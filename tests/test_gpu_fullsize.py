@@ -86,6 +86,22 @@ def test_full_size_steps_against_what_the_oracle_can_compute(full):
     full.spec_logits = spec_logits
 
 
+def test_library_loop_reproduces_the_stepwise_run(full):
+    """ngg_decode_more (the loop bench.py times) on a second context: the same kernels in the same shapes as
+    the step-by-step calls above, so the committed tokens are identical, not just close."""
+    assert hasattr(full, "spec_tokens"), "runs after the step test"
+    run = full.run
+    ctx2 = ngg.Context(full.m, full.dev_w, max_seq=len(full.prompt) + 256, max_k=run["k"], max_w=run["w"])
+    try:
+        ctx2.prefill(full.prompt)
+        out, st = ctx2.decode_more((N_STEPS + 1) * (run["w"] + 1), N_STEPS, run)
+        assert st["calls"] == N_STEPS and st["tokens"] == len(out)
+        assert list(ctx2.get_tokens()) == full.spec_tokens
+        assert sum(st["alloc_hist"]) == N_STEPS == sum(map(sum, st["accept_hist"]))
+    finally:
+        ctx2.close()
+
+
 def test_committed_cache_equals_fresh_prefill_and_plain_greedy_agrees(full):
     """A second context prefilled with prompt + the tokens committed above must give the same next
     logits as the first one (whose cache was filled by commits of winner rows), and plain greedy
