@@ -138,7 +138,7 @@ ngg_status forward(ngg_ctx *c, int R, int C, int P, bool from_hist, int w, bool 
   }
   const int n_splits = attention_splits(dt, d.head_dim, d.n_heads, M, P, c->max_splits);
   const size_t part_stride = (size_t)c->Mcap * d.d_model;
-  const int ks_o = gemm_residual_splits(dt, d.d_model, dq), ks_down = gemm_residual_splits(dt, d.d_model, d.d_ffn);
+  const int ks_o = gemm_residual_splits(dt, M, d.d_model, dq), ks_down = gemm_residual_splits(dt, M, d.d_model, d.d_ffn);
   const int ss_segs = rmsnorm_segments(d.d_model);
   int pending = 0;                                   // residual partials the next RMSNorm has to add
   for (int l = 0; l < d.n_layers; ++l) {

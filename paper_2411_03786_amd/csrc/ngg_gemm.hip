@@ -415,12 +415,19 @@ static void launch_paired(const GemmArgs &a, hipStream_t s) {
   else launch_paired_fm<T, EPI, 8>(a, s);
 }
 
-// Split of the contraction across workgroups for the residual GEMMs (two waves share a pair of row
-// groups, WN = 2): about one workgroup per CU, as long as each split keeps at least 2 chunks.
-int gemm_residual_splits(int dtype, int N, int K) {
+// Residual GEMMs: a workgroup takes 64 rows of W (WN = 2, its waves 2 x 2), or 32 rows with all four
+// waves splitting the steps (WN = 1) where that measured faster on MI355X: single-token steps, and the
+// square output projection (4096 x 4096: 11.0 against 11.7 us at 60 block rows, 8.2 against 9.5 at one;
+// down 4096 x 14336: 26.2 against 23.4 at 60 rows, 19.6 against 20.5 at one).  Narrower workgroups need
+// half the splits of the contraction, so the RMSNorm that follows adds half the partials.
+static bool residual_narrow(int M, int N, int K) { return M <= 16 || K <= N; }
+
+// Split of the contraction across workgroups for the residual GEMMs: about one workgroup per CU, as
+// long as each split keeps at least 2 chunks.
+int gemm_residual_splits(int dtype, int M, int N, int K) {
   const int kc = dtype == 1 ? KChunk<bf16_t>::value : KChunk<float>::value;
   const int n_chunks = (K + kc - 1) / kc;
-  const int blocks = (N / 32 + 1) / 2;
+  const int blocks = residual_narrow(M, N, K) ? N / 32 : (N / 32 + 1) / 2;
   int ks = (256 + blocks - 1) / blocks;
   ks = ks > kMaxResidualSplits ? kMaxResidualSplits : ks;
   while (ks > 1 && n_chunks / ks < 2) --ks;
@@ -429,7 +436,8 @@ int gemm_residual_splits(int dtype, int N, int K) {
 
 // Workgroup shapes measured on MI355X at the 7B shapes (M = 60 and M = 1).  Unembedding: wide tiles
 // (WN = 4) where there are enough row groups to give every CU a workgroup, otherwise two waves per
-// pair of groups; residual GEMMs: WN = 2, WK = 2 with the contraction split across workgroups.
+// pair of groups; residual GEMMs: WN x WK = 2 x 2 or 1 x 4 (residual_narrow) with the contraction split
+// across workgroups.
 template <typename T>
 static void launch_t(int epi, const GemmArgs &a_in, hipStream_t s) {
   GemmArgs a = a_in;
@@ -438,7 +446,10 @@ static void launch_t(int epi, const GemmArgs &a_in, hipStream_t s) {
   switch (epi) {
     case EPI_QKV: launch_paired<T, EPI_QKV>(a, s); break;
     case EPI_GATEUP: launch_paired<T, EPI_GATEUP>(a, s); break;
-    case EPI_RESIDUAL: launch_fm<T, EPI_RESIDUAL, 2, 2, 4>(a, a.KS, s); break;
+    case EPI_RESIDUAL:
+      if (residual_narrow(a.M, a.N, a.K)) launch_fm<T, EPI_RESIDUAL, 1, 4, 4>(a, a.KS, s);
+      else launch_fm<T, EPI_RESIDUAL, 2, 2, 4>(a, a.KS, s);
+      break;
     default:
       if (wide) launch_fm<T, EPI_UNEMBED, 4, 1, 8>(a, 1, s);
       else launch_fm<T, EPI_UNEMBED, 2, 2, 4>(a, 1, s);

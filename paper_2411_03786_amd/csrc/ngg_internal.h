@@ -248,7 +248,7 @@ struct AttnArgs {
 // launchers (host).  dtype: 0 = fp32, 1 = bf16.  Every launcher validates nothing: the API layer
 // checks shapes before calling.
 void launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t s);
-int gemm_residual_splits(int dtype, int N, int K);
+int gemm_residual_splits(int dtype, int M, int N, int K);
 void launch_attention(int dtype, int hd, const AttnArgs &a, hipStream_t s);
 int attention_splits(int dtype, int hd, int H, int M, int P, int max_splits);
 
