@@ -236,6 +236,39 @@ def test_degenerate_contexts_for_the_matcher():
         ctx.close()
 
 
+def test_profile_classes_count_launches_and_sampling(tiny):
+    """HIP-event brackets per kernel class: one span per launch (n_layers per layer kernel and model call),
+    one in every N with ngg_profile_sample, none when switched off; results are not affected."""
+    desc, run, w, prompt, model, ctx = tiny
+    L = desc["n_layers"]
+    ctx.prefill(prompt)
+    ref = ctx.verify_step(None, 1, 0)["new_tokens"]
+    ctx.profile_reset()
+    ctx.profile_enable(-1)
+    for _ in range(3):
+        assert list(ctx.verify_step(None, 1, 0)["new_tokens"]) == list(ref)
+    prof = ctx.profile_read()
+    for cls in ("gemm_qkv", "gemm_o", "gemm_gateup", "gemm_down", "attention"):
+        ms, cnt = prof[cls]
+        assert cnt == 3 * L and ms > 0.0, cls
+    assert prof["gemm_unembed"][1] == 3 and prof["norm"][1] == 3 * (2 * L + 1)
+    ctx.profile_reset()
+    ctx.profile_sample(L + 1)                            # one gate/up launch in every L + 1
+    ctx.profile_enable(1 << ngg.PROF_CLASSES.index("gemm_gateup"))
+    for _ in range(L + 1):
+        ctx.verify_step(None, 1, 0)
+    prof = ctx.profile_read()
+    assert prof["gemm_gateup"][1] == L and prof["gemm_qkv"][1] == 0
+    ctx.profile_enable(0)
+    ctx.profile_sample(1)
+    ctx.profile_reset()
+    ctx.verify_step(None, 1, 0)
+    assert all(cnt == 0 for _, cnt in ctx.profile_read().values())
+    assert ctx.profile_bracket_overhead() > 0.0
+    with pytest.raises(ngg.NggError):
+        ctx.profile_sample(0)
+
+
 def test_state_and_capacity_errors(tiny):
     desc, run, w, prompt, model, _ = tiny
     ctx = ngg.Context(desc, w, max_seq=140, max_k=4, max_w=3)
