@@ -435,35 +435,26 @@ void launch_tile_weights(int dtype, const void *src, void *dst, int N, int K, in
 
 // Top-(k - n_ctx) of z by (score desc, id asc), chained extension through next1, and assembly of
 // the k x w draft batch (Section 4.3: context rows first, the extended bigram fills the rest).
+// Selection in two levels without a barrier per rank: every wave ranks its own 512 candidate slots
+// (round r takes the best candidate that ranks after the wave's previous pick), then wave 0 ranks
+// the 16 waves' survivors the same way.
 __global__ __launch_bounds__(1024) void topk_assemble_kernel(const DraftArgs a) {
-  __shared__ float wv[16];
-  __shared__ int wi[16];
-  __shared__ float sel_v;
-  __shared__ int sel_i;
-  __shared__ int top[64];
+  constexpr int NWAVE = 16;
+  __shared__ float wv[NWAVE * kCandStride];
+  __shared__ int wi[NWAVE * kCandStride];
+  __shared__ int top[kCandStride];
   constexpr int CPT = kGemvBlocks * kCandStride / 1024;     // candidate slots per thread
+  constexpr int SPL = NWAVE * kCandStride / 64;             // survivor slots per lane of wave 0
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n_ctx = *a.n_ctx;
   const int k_big = a.w >= 1 ? a.k - n_ctx : 0;
-  // the candidates every workgroup of the sweep kept (its own top-k): the global top-k is among them
-  float cv[CPT];
-  int ci[CPT];
-#pragma unroll
-  for (int j = 0; j < CPT; ++j) {
-    const int slot = tid + 1024 * j;
-    const bool used = (slot % kCandStride) < a.k && k_big > 0;
-    cv[j] = used ? a.cand_val[slot] : kNegBig;
-    ci[j] = used ? a.cand_idx[slot] : 0x7fffffff;
-  }
-  float last_v = 0.0f;
-  int last_i = -1;
-  for (int r = 0; r < k_big; ++r) {
-    float bv = kNegBig;
-    int bi = 0x7fffffff;
-#pragma unroll
-    for (int j = 0; j < CPT; ++j) {
-      const bool in = r == 0 || ranks_before(last_v, last_i, cv[j], ci[j]);
-      if (in && ranks_before(cv[j], ci[j], bv, bi)) { bv = cv[j]; bi = ci[j]; }
+  // best of n values per lane that rank after (last_v, last_i), over the wave
+  auto wave_pick = [&](const float *v, const int *id, int n, bool first, float last_v, int last_i, float &bv, int &bi) {
+    bv = kNegBig;
+    bi = 0x7fffffff;
+    for (int j = 0; j < n; ++j) {
+      const bool in = first || ranks_before(last_v, last_i, v[j], id[j]);
+      if (in && ranks_before(v[j], id[j], bv, bi)) { bv = v[j]; bi = id[j]; }
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
@@ -471,19 +462,50 @@ __global__ __launch_bounds__(1024) void topk_assemble_kernel(const DraftArgs a) 
       const int oi = __shfl_xor(bi, off);
       if (ranks_before(ov, oi, bv, bi)) { bv = ov; bi = oi; }
     }
-    if (lane == 0) { wv[wave] = bv; wi[wave] = bi; }
-    __syncthreads();
-    if (tid == 0) {
-      float fv = wv[0];
-      int fi = wi[0];
-      for (int t = 1; t < 16; ++t)
-        if (ranks_before(wv[t], wi[t], fv, fi)) { fv = wv[t]; fi = wi[t]; }
-      sel_v = fv; sel_i = fi; top[r] = fi;
+  };
+  if (k_big > 0) {
+    // the candidates every workgroup of the sweep kept (its own top-k): the global top-k is among them
+    float cv[CPT];
+    int ci[CPT];
+#pragma unroll
+    for (int j = 0; j < CPT; ++j) {
+      const int slot = tid + 1024 * j;
+      const bool used = (slot % kCandStride) < a.k;
+      cv[j] = used ? a.cand_val[slot] : kNegBig;
+      ci[j] = used ? a.cand_idx[slot] : 0x7fffffff;
     }
-    __syncthreads();
-    last_v = sel_v;
-    last_i = sel_i;
-    __syncthreads();
+    float last_v = 0.0f;
+    int last_i = -1;
+    for (int r = 0; r < k_big; ++r) {
+      float bv;
+      int bi;
+      wave_pick(cv, ci, CPT, r == 0, last_v, last_i, bv, bi);
+      last_v = bv;
+      last_i = bi;
+      if (lane == 0) { wv[wave * kCandStride + r] = bv; wi[wave * kCandStride + r] = bi; }
+    }
+  }
+  __syncthreads();
+  if (wave == 0 && k_big > 0) {
+    float sv[SPL];
+    int si[SPL];
+#pragma unroll
+    for (int j = 0; j < SPL; ++j) {
+      const int e = lane + 64 * j;
+      const bool used = (e % kCandStride) < k_big;
+      sv[j] = used ? wv[e] : kNegBig;
+      si[j] = used ? wi[e] : 0x7fffffff;
+    }
+    float last_v = 0.0f;
+    int last_i = -1;
+    for (int r = 0; r < k_big; ++r) {
+      float bv;
+      int bi;
+      wave_pick(sv, si, SPL, r == 0, last_v, last_i, bv, bi);
+      last_v = bv;
+      last_i = bi;
+      if (lane == 0) top[r] = bi;
+    }
   }
   __syncthreads();
   if (tid < a.k && a.w >= 1) {
@@ -493,7 +515,10 @@ __global__ __launch_bounds__(1024) void topk_assemble_kernel(const DraftArgs a) 
       a.row_src[r] = 0;
     } else {
       int t0 = top[r - n_ctx];
-      for (int t = 0; t < a.w; ++t) { a.drafts[r * a.w + t] = t0; t0 = a.next1[t0]; }
+      for (int t = 0; t < a.w; ++t) {
+        a.drafts[r * a.w + t] = t0;
+        if (t + 1 < a.w) t0 = a.next1[t0];              // w - 1 dependent lookups
+      }
       a.row_src[r] = 1;
     }
   } else if (tid < a.k) {
