@@ -101,7 +101,9 @@ typedef struct {
   int64_t new_hist[34];   /* new_hist[i] = calls that appended i tokens (i <= max_w+1 <= 33) */
   int64_t winner_src[2];  /* calls won by a context row / by a bigram row */
   int64_t ctx_rows;       /* context rows found, summed over calls */
-  double ms_prefill, ms_drafts, ms_verify, ms_commit; /* host wall time per phase, including syncs */
+  double ms_prefill, ms_drafts, ms_verify, ms_commit; /* host wall time per phase; the drafts are not waited for,
+                                                         so ms_verify (which ends with the step's one
+                                                         synchronisation) holds their device time too */
   /* the quantities of the paper's ablation on strategies (Section 5.2), index 0 = context rows, 1 = bigram rows */
   int64_t accept_hist[2][34];  /* [s][a]: calls whose winning row came from strategy s and had a drafted tokens accepted */
   int64_t rank_hist[2][32];    /* [s][r]: calls with an accepted draft whose winning row was the r-th row of strategy s */

@@ -5,7 +5,8 @@
 // W rows are the MFMA "row" operand.  The library keeps its own copy of every weight matrix in
 // operand order (16 rows x 32 contraction elements per 1 KB block, lane-major), so one load
 // instruction of a wave reads 1 KB of contiguous memory, a wave streams one contiguous region, and
-// the data goes from global memory straight into MFMA registers, prefetched RING steps ahead.  X rows are the "column" operand: the workgroup stages X[:, chunk] in LDS (double
+// the data goes from global memory straight into MFMA registers (non-temporal loads: read once),
+// prefetched RING steps ahead.  X rows are the "column" operand: the workgroup stages X[:, chunk] in LDS (double
 // buffered, rows padded by 16 bytes so the 16 lanes of a quarter-wave hit distinct banks) and all
 // waves read their fragments from there.  A workgroup has 4 waves arranged WN x WK: WN waves own
 // different pairs of 16-row groups of W, WK waves split the steps of a chunk and are summed through
