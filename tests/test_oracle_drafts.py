@@ -92,6 +92,52 @@ def test_matcher_on_synthetic_prompts_matches_brute_force():
     assert hits > 20                                         # the copied spans do produce matches
 
 
+def _library_groups(x, q, w):
+    """The matcher through torch's library routines: sliding windows (unfold), rows equal to the query,
+    distinct continuations with their counts (unique over rows).  The order of equal counts is not
+    defined this way (Appendix B of the paper ranks with a top-k over the counts), so the caller
+    compares only where the counts are distinct."""
+    import torch
+    t = torch.tensor(x, dtype=torch.int64)
+    if len(x) < q + w:
+        return []
+    win = t.unfold(0, q + w, 1)                              # [n - q - w + 1][q + w]
+    hit = (win[:, :q] == t[len(x) - q:]).all(dim=1)
+    cont = win[hit][:, q:]
+    if cont.shape[0] == 0:
+        return []
+    uniq, counts = torch.unique(cont, dim=0, return_counts=True)
+    order = torch.argsort(counts, descending=True, stable=True)
+    return [(tuple(int(v) for v in uniq[i]), int(counts[i])) for i in order]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_matcher_agrees_with_unfold_unique_counts_where_counts_are_distinct(seed):
+    """Streams built from a few motifs repeated a different number of times each, so that no two
+    continuations of the final query share a count: there the library's ranking is unambiguous."""
+    rng = np.random.default_rng(100 + seed)
+    q, w = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+    query = [int(v) for v in rng.integers(0, 5, size=q)]
+    conts, x = set(), []
+    n_motifs = int(rng.integers(2, 5))
+    while len(conts) < n_motifs:
+        conts.add(tuple(int(v) for v in rng.integers(5, 12, size=w)))     # continuation tokens never look like a query token
+    pieces = []
+    for reps, c in enumerate(sorted(conts), start=1):       # motif number i occurs i times: distinct counts
+        pieces += [query + list(c)] * reps
+    for i in rng.permutation(len(pieces)):
+        x += pieces[i] + [int(v) for v in rng.integers(12, 20, size=int(rng.integers(0, 3)))]   # filler that matches nothing
+    x += query
+    got = context_ngram_groups(x, q, w)
+    lib = _library_groups(x, q, w)
+    assert len({c for _, c in lib}) == len(lib) == n_motifs  # the construction worked: distinct counts
+    assert [(g[0], g[1]) for g in got] == lib
+    # the oracle's third field is the last start of each continuation
+    for cont, cnt, last in got:
+        starts = [i for i in range(len(x) - q - w + 1) if x[i:i + q] == query and tuple(x[i + q:i + q + w]) == cont]
+        assert len(starts) == cnt and last == max(starts)
+
+
 def test_context_rows_backoff_cap_and_dedup():
     x = [1, 2, 3, 9, 9, 2, 3, 8, 8, 7, 3, 6, 6, 1, 2, 3]
     # q=3 ("1 2 3") -> 9 9 ; q=2 ("2 3") -> 8 8 (later), 9 9 (dup) ; q=1 ("3") -> 6 6, 8 8 (dup), 9 9 (dup)
