@@ -236,6 +236,34 @@ def test_degenerate_contexts_for_the_matcher():
         ctx.close()
 
 
+def test_row_permutation_and_duplicate_rows(tiny):
+    """Rows are independent given the shared prefix: a duplicate row gets the same logits as its original,
+    permuting the rows permutes the results, and the committed tokens do not change (the winner is the
+    first of the best rows in either order)."""
+    desc, run, w, prompt, model, ctx = tiny
+    truth = oracle.greedy_plain_cached(model, prompt, 8)
+    ctx.prefill(prompt)
+    assert int(ctx.get_tokens()[-1]) == truth[0]
+    rng = np.random.default_rng(11)
+    d = rng.integers(0, desc["vocab"], size=(4, 3)).astype(np.int32)
+    d[1] = truth[1:4]                                     # the true continuation: accepted whole
+    d[2, :2] = truth[1:3]                                 # right for two tokens, then wrong
+    d[2, 2] = (truth[3] + 1) % desc["vocab"]
+    d[3] = d[1]                                           # duplicate of the best row
+    a = ctx.verify_step(d, want_logits=True)
+    assert list(a["accept_len"])[1:] == [3, 2, 3] and a["winner"] == 1 and list(a["new_tokens"]) == truth[1:5]
+    scale = np.max(np.abs(a["logits"]))
+    assert np.max(np.abs(a["logits"][3] - a["logits"][1])) <= 1e-5 * scale
+    assert np.array_equal(a["greedy"][3], a["greedy"][1])
+    # rows 1 and 2 share two draft tokens: the same inputs up to column 2
+    assert np.max(np.abs(a["logits"][2, :3] - a["logits"][1, :3])) <= 1e-5 * scale
+    perm = [3, 2, 0, 1]
+    b = ctx.verify_step(d[perm], want_logits=True)
+    assert np.max(np.abs(b["logits"] - a["logits"][perm])) <= 1e-5 * scale
+    assert np.array_equal(b["greedy"], a["greedy"][perm]) and list(b["accept_len"]) == list(a["accept_len"][perm])
+    assert b["winner"] == 0 and list(b["new_tokens"]) == list(a["new_tokens"])
+
+
 def test_profile_classes_count_launches_and_sampling(tiny):
     """HIP-event brackets per kernel class: one span per launch (n_layers per layer kernel and model call),
     one in every N with ngg_profile_sample, none when switched off; results are not affected."""
