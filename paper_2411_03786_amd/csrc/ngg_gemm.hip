@@ -173,44 +173,43 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
     // 1 / rms of the pass's block rows, one per thread, left in LDS for the epilogues (fetched only now:
     // the main loop keeps every vector register it can get)
     float *rs_lds = reinterpret_cast<float *>(smem);     // [ROWS]; the hand-over buffers start behind it
-    if constexpr (!PAIRED) {
-      if (tid < ROWS) rs_lds[tid] = row_scale(row_ss_load(m0 + tid));
-    }
+    if (tid < ROWS) rs_lds[tid] = row_scale(row_ss_load(m0 + tid));
 
     // ---- q/k/v and gate/up: every wave hands its partial fragments over through LDS; wave wk then
     //      sums items wk, wk + WK, ... of the FN x FM accumulator fragments (waves in the order 0 .. WK-1)
     //      and runs their epilogue, one item at a time ------------------------------------------------------
     if constexpr (PAIRED) {
-      // at most 4 column blocks of every fragment per round, so that the hand-over fits the LDS
-      constexpr int FMR = FM < 4 ? FM : 4, ROUNDS = FM / FMR;
-      constexpr int ITEMS = FN * FMR, IPW = (ITEMS + WK - 1) / WK;   // items per round, per wave
-      static_assert(WK % FMR == 0, "a wave's items of one round share their column block");
-      f32x4 *red = reinterpret_cast<f32x4 *>(smem + ROWS * sizeof(float));   // [WK][ITEMS][64] lanes x 4 registers
-      // item idx = f * FMR + fr covers column block rd * FMR + fr; wave wk takes idx = wk, wk + WK, ..., all of
-      // column block rd * FMR + wk % FMR: one 1 / rms per lane and round, fetched while the hand-over runs
-      f32x4 ss[ROUNDS];
-#pragma unroll
-      for (int rd = 0; rd < ROUNDS; ++rd) ss[rd] = row_ss_load(m0 + (rd * FMR + wk % FMR) * 16 + li);
+      // at most 4 column blocks of every fragment per round, so that the hand-over fits the LDS; the last
+      // round of a tile of 5, 6 or 7 column blocks is shorter
+      constexpr int FMR = FM < 4 ? FM : 4, ROUNDS = (FM + FMR - 1) / FMR;
+      constexpr int IPW = (FN * FMR + WK - 1) / WK;        // items per round and wave, at most
+      f32x4 *red = reinterpret_cast<f32x4 *>(smem + ROWS * sizeof(float));   // [WK][FN * cnt][64] lanes x 4 registers
 #pragma unroll
       for (int rd = 0; rd < ROUNDS; ++rd) {
+      const int cnt = (rd + 1) * FMR <= FM ? FMR : FM - rd * FMR;    // column blocks of this round (constant after unrolling)
+      const int items = FN * cnt;                          // item idx = f * cnt + fr covers column block rd * FMR + fr
       if (rd > 0) __syncthreads();                       // the previous round's items were all read
 #pragma unroll
       for (int f = 0; f < FN; ++f)
 #pragma unroll
-        for (int fr = 0; fr < FMR; ++fr) red[((size_t)wk * ITEMS + f * FMR + fr) * 64 + lane] = acc[f][rd * FMR + fr];
-      __syncthreads();
-      const int fm = rd * FMR + wk % FMR;
-      const int m = m0 + fm * 16 + li;
-      const float rs = row_scale(ss[rd]);
-#pragma unroll
+        for (int fr = 0; fr < FMR; ++fr)
+          if (fr < cnt) red[((size_t)wk * items + f * cnt + fr) * 64 + lane] = acc[f][rd * FMR + (fr < cnt ? fr : 0)];
+      __syncthreads();                                   // also: rs_lds is complete
+      // unrolled where the items are short (SwiGLU) or few: the q/k/v item (rotary tables, three kinds of
+      // stores) times 8 would not fit the registers
+      constexpr int UNR = (EPI == EPI_GATEUP || IPW <= 3) ? IPW : 1;
+#pragma unroll UNR
       for (int j = 0; j < IPW; ++j) {
         const int idx = wk + WK * j;
-        if (idx >= ITEMS) break;
-        const int f = idx / FMR;
+        if (idx >= items) break;
+        const int f = idx / cnt;
+        const int fm = rd * FMR + (idx - f * cnt);
+        const int m = m0 + fm * 16 + li;
+        const float rs = rs_lds[fm * 16 + li];
         const int frag = blockIdx.x * FN + f;              // fragment index over the whole matrix
         f32x4 sum = red[(size_t)idx * 64 + lane];
 #pragma unroll
-        for (int o = 1; o < WK; ++o) sum += red[((size_t)o * ITEMS + idx) * 64 + lane];
+        for (int o = 1; o < WK; ++o) sum += red[((size_t)o * items + idx) * 64 + lane];
         float v[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) v[r] = sum[r];
@@ -364,12 +363,23 @@ int gemm_groups(int epi, const GemmArgs &a) {
   }
 }
 
+// The row tile holds the block's rows in 16-row column blocks of the MFMA: as many as the block needs, up
+// to 8 (128 rows; more rows take another pass over W).  Every extra column block costs activation traffic
+// from L2, LDS reads and MFMA work, so a 40-row block runs on 3 of them, not 4.
+static int gemm_row_blocks(int M) { return M >= 128 ? 8 : (M + 15) / 16; }
+
 template <typename T, int EPI, int WN, int WK, int RING>
 static void launch_fm(const GemmArgs &a, int KS, hipStream_t s) {
-  if (a.M <= 16) launch_gemm_cfg<T, EPI, 1, WN, WK, RING>(a, KS, s);
-  else if (a.M <= 32) launch_gemm_cfg<T, EPI, 2, WN, WK, RING>(a, KS, s);
-  else if (a.M <= 64) launch_gemm_cfg<T, EPI, 4, WN, WK, RING>(a, KS, s);
-  else launch_gemm_cfg<T, EPI, 8, WN, WK, RING>(a, KS, s);   // 128-row tiles; more rows loop over W again
+  switch (gemm_row_blocks(a.M)) {                            // 16-row column blocks of the tile
+    case 1: launch_gemm_cfg<T, EPI, 1, WN, WK, RING>(a, KS, s); break;
+    case 2: launch_gemm_cfg<T, EPI, 2, WN, WK, RING>(a, KS, s); break;
+    case 3: launch_gemm_cfg<T, EPI, 3, WN, WK, RING>(a, KS, s); break;
+    case 4: launch_gemm_cfg<T, EPI, 4, WN, WK, RING>(a, KS, s); break;
+    case 5: launch_gemm_cfg<T, EPI, 5, WN, WK, RING>(a, KS, s); break;
+    case 6: launch_gemm_cfg<T, EPI, 6, WN, WK, RING>(a, KS, s); break;
+    case 7: launch_gemm_cfg<T, EPI, 7, WN, WK, RING>(a, KS, s); break;
+    default: launch_gemm_cfg<T, EPI, 8, WN, WK, RING>(a, KS, s);   // 128-row tiles; more rows loop over W again
+  }
 }
 
 // q/k/v and gate/up: one workgroup = FN fragments, its four waves split the steps of every chunk
@@ -410,10 +420,16 @@ static void launch_paired_fm(const GemmArgs &a, hipStream_t s) {
 
 template <typename T, int EPI>
 static void launch_paired(const GemmArgs &a, hipStream_t s) {
-  if (a.M <= 16) launch_paired_fm<T, EPI, 1>(a, s);
-  else if (a.M <= 32) launch_paired_fm<T, EPI, 2>(a, s);
-  else if (a.M <= 64) launch_paired_fm<T, EPI, 4>(a, s);
-  else launch_paired_fm<T, EPI, 8>(a, s);
+  switch (gemm_row_blocks(a.M)) {
+    case 1: launch_paired_fm<T, EPI, 1>(a, s); break;
+    case 2: launch_paired_fm<T, EPI, 2>(a, s); break;
+    case 3: launch_paired_fm<T, EPI, 3>(a, s); break;
+    case 4: launch_paired_fm<T, EPI, 4>(a, s); break;
+    case 5: launch_paired_fm<T, EPI, 5>(a, s); break;
+    case 6: launch_paired_fm<T, EPI, 6>(a, s); break;
+    case 7: launch_paired_fm<T, EPI, 7>(a, s); break;
+    default: launch_paired_fm<T, EPI, 8>(a, s);
+  }
 }
 
 // Residual GEMMs: a workgroup takes 64 rows of W (WN = 2, its waves 2 x 2), or 32 rows with all four

@@ -137,7 +137,8 @@ def test_bigram_scores_and_next1_table(tiny):
             assert s[b.next1(x)] - s[next1[x]] < 1e-5 * np.max(np.abs(s))
 
 
-@pytest.mark.parametrize("k,w", [(1, 0), (1, 8), (16, 6), (32, 8), (3, 1)])
+# 1, 9, 112, 288, 6, 40, 65 and 96 block rows: GEMM row tiles of 1, 7, 8 (several passes), 3, 5 and 6 column blocks
+@pytest.mark.parametrize("k,w", [(1, 0), (1, 8), (16, 6), (32, 8), (3, 1), (8, 4), (13, 4), (12, 7)])
 def test_block_shapes_including_more_than_64_rows(tiny, k, w):
     desc, run, _, prompt, model, ctx = tiny
     cfg = dict(k=k, w=w, k_ctx_max=k, q_min=1, q_max=3)
@@ -496,10 +497,11 @@ def test_cfg2_small_bf16_lockstep():
     assert rep.tolerated_argmax <= 0.1 * positions
 
 
-@pytest.mark.parametrize("k,w", [(16, 6), (32, 8), (13, 4)])
+@pytest.mark.parametrize("k,w", [(16, 6), (32, 8), (13, 4), (12, 7)])
 def test_bf16_blocks_of_more_than_64_rows(k, w):
-    """Blocks of 65, 112 and 288 rows on the small bf16 widths (3 layers): the 128-row GEMM tiles,
-    the eight-wave attention workgroups and, at 288 rows, several passes over the weights."""
+    """Blocks of 112, 288, 65 and 96 rows on the small bf16 widths (3 layers): GEMM row tiles of 7, 8, 5
+    and 6 column blocks, the attention workgroups with two query groups per wave and, at 288 rows,
+    several passes over the weights."""
     desc = si.reduced_layers(si.MODELS["small"], 3)
     run = dict(si.RUNS["cfg2"], prompt_len=333, k=k, w=w, k_ctx_max=k, q_min=1, q_max=3, n_gen=30)
     w_, prompt, model, ctx = _setup(desc, run)
