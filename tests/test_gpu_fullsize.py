@@ -137,3 +137,35 @@ def test_committed_cache_equals_fresh_prefill_and_plain_greedy_agrees(full):
             ctx2.commit()
     finally:
         ctx2.close()
+
+
+def test_zero_output_projections_accept_the_whole_chain_at_full_size(full):
+    """W_o = W_down = 0 on all 32 layers (done last: it changes the shared weights): the logits reduce to
+    U.RMSNorm(E[x]), so greedy decoding follows the bigram's top-1 chain, which the oracle computes at the full
+    vocabulary.  Every verify call must then accept the whole first bigram row and commit w + 1 tokens, and the
+    committed tokens must be that chain (up to a near-tie of the bigram scores, where the comparison stops)."""
+    run, tol = full.run, TOL["bf16"]
+    for lw in full.dev_w["layers"]:
+        lw["wo"].zero_()
+        lw["w_down"].zero_()
+    ctx = ngg.Context(full.m, full.dev_w, max_seq=len(full.prompt) + 256, max_k=run["k"], max_w=run["w"])
+    try:
+        ctx.prefill(full.prompt)
+        n_calls, per_call = 8, run["w"] + 1
+        out, st = ctx.decode_more((n_calls + 1) * per_call, n_calls, run)
+        assert st["calls"] == n_calls
+        toks = [int(t) for t in ctx.get_tokens()]
+        prev, exact = int(full.prompt[-1]), True
+        for i, t in enumerate(toks[len(full.prompt):]):
+            want = full.bigram.next1(prev)
+            if t != want:
+                z = full.bigram.scores(prev)
+                assert abs(z[t] - z[want]) < tol * np.max(np.abs(z)), f"generated token {i}: {t} vs chain {want}"
+                exact = False
+                break
+            prev = t
+        if exact:                                           # no near-tie met: every call took the whole chain row
+            assert st["new_hist"][per_call] == n_calls and len(out) == n_calls * per_call
+            assert st["winner_src"][0] + st["winner_src"][1] == n_calls
+    finally:
+        ctx.close()
