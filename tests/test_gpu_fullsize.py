@@ -151,6 +151,17 @@ def test_zero_output_projections_accept_the_whole_chain_at_full_size(full):
     ctx = ngg.Context(full.m, full.dev_w, max_seq=len(full.prompt) + 256, max_k=run["k"], max_w=run["w"])
     try:
         ctx.prefill(full.prompt)
+        # the logits of a whole block against the closed form, position by position: U.(E[x] / rms(E[x]))
+        # whatever came before x (the attention output is multiplied by zero)
+        drafts, _, _ = ctx.build_drafts(run)
+        res = ctx.verify_step(None, run["k"], run["w"], want_logits=True)
+        last = int(ctx.get_tokens()[-1])
+        for r, j in [(0, 0), (0, 1), (3, 2), (run["k"] - 1, run["w"]), (5, 0), (7, 4)]:
+            x = last if j == 0 else int(drafts[r, j - 1])
+            e = full.bigram.tok_emb[x]
+            want = full.bigram.scores(x) / np.sqrt(np.mean(e * e) + full.m["rms_eps"])
+            got = res["logits"][r, j]
+            assert np.max(np.abs(got - want)) <= 1e-3 * np.max(np.abs(want)), (r, j)
         n_calls, per_call = 8, run["w"] + 1
         out, st = ctx.decode_more((n_calls + 1) * per_call, n_calls, run)
         assert st["calls"] == n_calls
