@@ -83,6 +83,10 @@ def test_calls_on_a_null_context_fail_cleanly(lib):
     assert lib.ngg_profile_bracket_overhead(None, None) == ngg.NGG_EINVAL
     assert lib.ngg_destroy(None) == ngg.NGG_EINVAL
     assert lib.ngg_verify_step(None, None, 1, 0, None) == ngg.NGG_EINVAL
+    assert lib.ngg_decode_more(None, 4, 2, None, None, None, None) == ngg.NGG_EINVAL
+    assert lib.ngg_greedy_decode(None, None, 1, 1, None, None, None) == ngg.NGG_EINVAL
+    assert lib.ngg_unigram_build(None, 8) == ngg.NGG_EINVAL
+    assert lib.ngg_profile_sample(None, 1) == ngg.NGG_EINVAL
     assert isinstance(lib.ngg_last_error(None), bytes)
 
 

@@ -307,6 +307,9 @@ def test_state_and_capacity_errors(tiny):
     with pytest.raises(ngg.NggError) as e:
         ctx.commit()
     assert e.value.status == ngg.NGG_ESTATE
+    with pytest.raises(ngg.NggError) as e:
+        ctx.decode_more(4, 2, run)                        # nothing to continue from
+    assert e.value.status == ngg.NGG_ESTATE
     ctx.prefill(prompt)                                   # n = 129
     with pytest.raises(ngg.NggError) as e:
         ctx.verify_step(np.zeros((5, 2), dtype=np.int32))
