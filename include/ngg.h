@@ -40,7 +40,8 @@ typedef enum { NGG_F32 = 0, NGG_BF16 = 1 } ngg_dtype;
  * with i + head_dim/2), SwiGLU feed-forward, no biases, a final RMSNorm and an
  * untied output embedding.  Constraints checked by ngg_create: head_dim in
  * {32, 64, 128}; d_model, d_ffn, n_heads*head_dim and vocab multiples of 32;
- * n_heads a multiple of n_kv_heads. */
+ * d_model <= 16384 and d_ffn <= 65536 (what the norm and sweep kernels hold
+ * per workgroup); n_heads a multiple of n_kv_heads. */
 typedef struct {
   int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
   int32_t dtype;      /* ngg_dtype of weights, KV cache and GEMM inputs; accumulation is always fp32 */
@@ -144,7 +145,10 @@ ngg_status ngg_verify_step(ngg_ctx *ctx, const int32_t *drafts, int32_t k, int32
 /* Commits the last verify call (Appendix D: the cache becomes that of the
  * longest accepted speculation): appends min(n_new, max_new) tokens and the
  * winner row's keys/values for the block columns they came from.  max_new <= 0
- * is NGG_EINVAL; NGG_ESTATE without a preceding verify.  n_committed may be NULL. */
+ * is NGG_EINVAL; NGG_ESTATE without a preceding verify.  The count is also cut
+ * to the room left in the context (a fully accepted block at n + w == max_seq
+ * appends w tokens, not w + 1); NGG_ECAPACITY only when n == max_seq already.
+ * n_committed may be NULL. */
 ngg_status ngg_commit(ngg_ctx *ctx, int32_t max_new, int32_t *n_committed);
 
 /* Prefill + repeated (build_drafts, verify_step, commit) until n_gen tokens
@@ -169,8 +173,8 @@ ngg_status ngg_decode_more(ngg_ctx *ctx, int32_t n_gen, int32_t max_calls, const
  * vocabulary entry x the library runs the decoder on [x] (Mcap contexts per
  * pass, each attending to itself only, position 0) and keeps the top_k token
  * ids by (logit desc, id asc) in a device table [vocab][top_k]; column 0 is
- * the chained extension's lookup ("Extensions to (k, w) ... can also be stored
- * as a O(1) lookup table").  Costs vocab / Mcap model calls, once.  Requires
+ * the lookup the chained extension to w > 1 tokens uses (Section 4.1,
+ * "Extensions").  Costs vocab / Mcap model calls, once.  Requires
  * max_k <= top_k <= min(64, vocab).  Leaves the committed state as it was; a
  * pending verify call can no longer be committed (NGG_ESTATE from ngg_commit). */
 ngg_status ngg_bigram_table_build(ngg_ctx *ctx, int32_t top_k);
@@ -224,9 +228,14 @@ ngg_status ngg_profile_bracket_overhead(ngg_ctx *ctx, double *us);
  * and reports its full size in *bytes.  Names: "h" (residual stream, fp32 [M][d_model]), "z"
  * (bigram scores of the last ngg_build_drafts, fp32 [vocab]), "next1" (int32 [vocab]), "hist"
  * (int32 token history), "block_tok" (int32 block tokens of the last forward), "kcache" /
- * "vcache" (whole caches: keys [layer][kv head][position][head_dim], values transposed
- * [layer][kv head][head_dim][position], positions padded to *stride), "attn" (attention output of
- * the last layer, model dtype [M][n_heads*head_dim]).  Synchronises the stream. */
+ * "vcache" (whole caches, [layer][kv head][*stride / 32 tiles]: a tile holds 32 positions x head_dim
+ * elements in MFMA operand order, i.e. blocks of 16 rows x 32 contraction elements of 512 elements
+ * each; a key tile is the [32 positions][head_dim] matrix with position 8a + 4f + b stored as row
+ * 16f + 4a + b, a value tile the transposed [head_dim][32 positions] matrix; element (row n, column
+ * k) of a tile matrix with K columns sits at ((n/16)*(K/32) + k/32)*512 + (((k%32)/8)*16 + n%16)*8
+ * + k%8 for 2-byte elements), "attn" (attention output of the last layer, model dtype, in
+ * chunks of 256 (bf16) or 128 (fp32) features: [feature chunk][Mcap rows][chunk]).
+ * Synchronises the stream. */
 ngg_status ngg_debug_peek(ngg_ctx *ctx, const char *name, void *dst, int64_t cap, int64_t *bytes, int32_t *stride);
 
 #ifdef __cplusplus

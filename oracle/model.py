@@ -8,7 +8,11 @@ RMSNorm and an untied output embedding.  A model call on an input block of
 shape (k, w+1) whose context is KV-cached (Section 3) is `forward_block`.
 
 Weights are read as stored (fp32 values, bf16-representable for bf16 models)
-and widened to fp64; no activation is rounded to a lower precision.
+and widened to fp64; no activation is rounded to a lower precision.  The
+widening is exact, so when it happens changes no result: by default every
+matrix is widened once in the constructor; `widen_at_use=True` keeps the layer
+matrices as stored and widens one layer at a time inside the forward pass,
+which bounds memory for deep, wide models.
 """
 from __future__ import annotations
 
@@ -39,13 +43,17 @@ class KVCache:
 
 
 class Model:
-    def __init__(self, desc: dict, weights: dict):
+    def __init__(self, desc: dict, weights: dict, widen_at_use: bool = False):
         self.desc = dict(desc)
         f64 = lambda a: np.asarray(a, dtype=np.float64)
         self.tok_emb = f64(weights["tok_emb"])        # V  (input embedding), [vocab][d]
         self.unemb = f64(weights["unemb"])            # U^T (output embedding), [vocab][d]
         self.final_norm = f64(weights["final_norm"])
-        self.layers = [{k: f64(v) for k, v in lw.items()} for lw in weights["layers"]]
+        self.widen_at_use = bool(widen_at_use)
+        if self.widen_at_use:
+            self.layers = [dict(lw) for lw in weights["layers"]]          # as stored; widened per layer in the forward pass
+        else:
+            self.layers = [{k: f64(v) for k, v in lw.items()} for lw in weights["layers"]]
         self.L = desc["n_layers"]
         self.H = desc["n_heads"]
         self.Hkv = desc["n_kv_heads"]
@@ -100,6 +108,8 @@ class Model:
         causal = np.tril(np.ones((c, c), dtype=bool))             # [query j, key s]: s <= j
         block_kv = []
         for li, lw in enumerate(self.layers):
+            if self.widen_at_use:
+                lw = {name: np.asarray(a, dtype=np.float64) for name, a in lw.items()}
             x = self.rmsnorm(h, lw["attn_norm"])
             q = (x @ lw["wq"].T).reshape(k, c, self.H, self.hd)
             kk = (x @ lw["wk"].T).reshape(k, c, self.Hkv, self.hd)

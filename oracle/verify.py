@@ -48,13 +48,20 @@ class State:
         self.cache = cache
 
 
-def prefill(model: Model, prompt) -> State:
-    """Run the prompt, cache all of it, append the first greedy token."""
+def prefill(model: Model, prompt, chunk: int | None = None) -> State:
+    """Run the prompt, cache all of it, append the first greedy token.  With
+    `chunk`, the prompt goes through the model in pieces of that many tokens, each
+    a (1, chunk) block on the cache of the pieces before it: the same causal
+    forward pass (Section 3's block call with k = 1), with bounded memory."""
     prompt = [int(t) for t in prompt]
-    logits, kv = model.forward_block(np.asarray(prompt)[None, :], None)
     cache = KVCache(model.L, model.Hkv, model.hd)
-    for li, (kk, vv) in enumerate(kv):
-        cache.append(li, kk[0], vv[0])
+    step = len(prompt) if not chunk else int(chunk)
+    for p0 in range(0, len(prompt), step):
+        piece = np.asarray(prompt[p0:p0 + step])[None, :]
+        last = p0 + step >= len(prompt)
+        logits, kv = model.forward_block(piece, cache if p0 else None, want_logits=last)
+        for li, (kk, vv) in enumerate(kv):
+            cache.append(li, kk[0], vv[0])
     first = int(greedy_argmax(logits[0, -1]))
     st = State(prompt + [first], cache)
     st.first_logits = logits[0, -1]              # logits that chose the first generated token

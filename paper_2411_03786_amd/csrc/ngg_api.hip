@@ -32,7 +32,8 @@ struct ngg_ctx {
   int Spad = 0, Mcap = 0, max_splits = 0, unembed_tiles = 0;
   // device buffers
   int32_t *hist = nullptr, *drafts = nullptr, *block_tok = nullptr, *res = nullptr, *next1 = nullptr;
-  int32_t *mlist = nullptr, *reps = nullptr, *ctx_rows = nullptr, *n_ctx = nullptr;
+  int32_t *mlist = nullptr, *reps = nullptr, *gtab = nullptr, *ctx_rows = nullptr, *n_ctx = nullptr;
+  int gtab_slots = 0;              // slots of the matcher's grouping table: a power of two >= 2 * Spad
   int32_t *bg_table = nullptr, *bg_tok = nullptr;   // full-model bigram table [vocab][bg_K]; token ids of one build pass
   int bg_K = 0;
   bool bg_use = false;             // bigram rows from the table instead of the U.E[x] sweep
@@ -280,7 +281,7 @@ const char *ngg_last_error(const ngg_ctx *ctx) { return ctx ? ctx->err.c_str() :
 ngg_status ngg_destroy(ngg_ctx *c) {
   if (!c) return NGG_EINVAL;
   (void)hipStreamSynchronize(c->stream);
-  void *bufs[] = {c->hist, c->drafts, c->block_tok, c->res, c->next1, c->mlist, c->reps, c->ctx_rows, c->n_ctx,
+  void *bufs[] = {c->hist, c->drafts, c->block_tok, c->res, c->next1, c->mlist, c->reps, c->gtab, c->ctx_rows, c->n_ctx,
                   c->row_src, c->hpart, c->wtiled, c->cand_val, c->cand_idx, c->kcache, c->vcache, c->kscr, c->vscr, c->h, c->part_o, c->part_ml, c->pmax_val, c->z,
                   c->logits, c->rope_cos, c->rope_sin, c->pmax_idx, c->xn, c->q, c->attn, c->act, c->bg_table, c->bg_tok, c->uni_top, c->row_ss};
   for (void *b : bufs)
@@ -303,6 +304,8 @@ ngg_status ngg_create(const ngg_model_desc *desc, const ngg_weights *weights, vo
     return fail(nullptr, NGG_EINVAL, "ngg_create: head_dim %d not in {32, 64, 128}", d.head_dim);
   if (d.d_model % 32 || d.d_ffn % 32 || (d.n_heads * d.head_dim) % 32)
     return fail(nullptr, NGG_EINVAL, "ngg_create: d_model, d_ffn and n_heads*head_dim must be multiples of 32");
+  if (d.d_model > 16384 || d.d_ffn > 65536)
+    return fail(nullptr, NGG_EINVAL, "ngg_create: d_model %d / d_ffn %d beyond the supported 16384 / 65536", d.d_model, d.d_ffn);
   if (d.vocab % 32) return fail(nullptr, NGG_EINVAL, "ngg_create: vocab must be a multiple of 32");
   if (d.n_heads % d.n_kv_heads) return fail(nullptr, NGG_EINVAL, "ngg_create: n_heads must be a multiple of n_kv_heads");
   if (d.max_k < 1 || d.max_k > 32 || d.max_w < 0 || d.max_w > 32)
@@ -343,6 +346,9 @@ ngg_status ngg_create(const ngg_model_desc *desc, const ngg_weights *weights, vo
   TRY(dev_alloc(c, &c->next1, (size_t)d.vocab * 4, true));
   TRY(dev_alloc(c, &c->mlist, (size_t)c->Spad * 4, true));
   TRY(dev_alloc(c, &c->reps, (size_t)c->Spad * 8, true));
+  c->gtab_slots = 128;
+  while (c->gtab_slots < 2 * c->Spad) c->gtab_slots <<= 1;
+  TRY(dev_alloc(c, &c->gtab, (size_t)3 * c->gtab_slots * 4, true));
   TRY(dev_alloc(c, &c->ctx_rows, (size_t)d.max_k * std::max(1, d.max_w) * 4, true));
   TRY(dev_alloc(c, &c->n_ctx, 16, true));
   TRY(dev_alloc(c, &c->row_src, (size_t)d.max_k, true));
@@ -447,7 +453,7 @@ ngg_status ngg_build_drafts(ngg_ctx *c, const ngg_draft_cfg *cfg, int32_t *draft
     ProfScope ps(c, NGG_PROF_DRAFTS);
     DraftArgs a{};
     a.hist = c->hist; a.n = c->n; a.k = cfg->k; a.w = cfg->w; a.k_ctx_max = cfg->k_ctx_max; a.q_min = cfg->q_min; a.q_max = cfg->q_max;
-    a.mlist = c->mlist; a.reps = c->reps; a.ctx_rows = c->ctx_rows; a.n_ctx = c->n_ctx;
+    a.mlist = c->mlist; a.reps = c->reps; a.gtab = c->gtab; a.gtab_slots = c->gtab_slots; a.ctx_rows = c->ctx_rows; a.n_ctx = c->n_ctx;
     a.tok_emb = c->w.tok_emb; a.unemb_t = c->unemb_t; a.d = c->d.d_model; a.vocab = c->d.vocab; a.z = c->z; a.cand_val = c->cand_val; a.cand_idx = c->cand_idx; a.next1 = c->next1;
     a.drafts = c->drafts; a.row_src = c->row_src;
     if (c->bg_use) { a.bg_table = c->bg_table; a.bg_K = c->bg_K; }
@@ -517,8 +523,9 @@ ngg_status ngg_commit(ngg_ctx *c, int32_t max_new, int32_t *n_committed) {
   if (max_new <= 0) return fail(c, NGG_EINVAL, "ngg_commit: max_new must be positive");
   if (!c->have_verify) return fail(c, NGG_ESTATE, "ngg_commit: no verify call to commit");
   const ngg_model_desc &d = c->d;
+  if (c->n >= d.max_seq) return fail(c, NGG_ECAPACITY, "ngg_commit: the context is full (n = max_seq = %d)", d.max_seq);
+  max_new = std::min(max_new, d.max_seq - c->n);       // a fully accepted block at n + w == max_seq loses its last token
   const int n_new = std::min(c->res_host[RES_NNEW], max_new);
-  if (c->n + n_new > d.max_seq) return fail(c, NGG_ECAPACITY, "ngg_commit: n=%d + %d exceeds max_seq=%d", c->n, n_new, d.max_seq);
   {
     ProfScope ps(c, NGG_PROF_ACCEPT_COMMIT);
     launch_commit(d.dtype, c->kcache, c->vcache, c->kscr, c->vscr, d.n_layers, d.n_kv_heads, d.head_dim, c->Spad, c->Mcap,

@@ -268,6 +268,8 @@ struct DraftArgs {
   int k, w, k_ctx_max, q_min, q_max;
   int32_t *mlist;         // [max_seq] scratch: matching window starts
   int32_t *reps;          // [2*max_seq] scratch: (count, last_start) of each distinct continuation
+  int32_t *gtab;          // [3][gtab_slots] scratch: grouping table (representative start | count | last start)
+  int gtab_slots;         // a power of two >= 2 * max_seq
   int32_t *ctx_rows;      // [max_k][max_w]
   int32_t *n_ctx;         // [1]
   const void *tok_emb;    // row-major [vocab][d]
@@ -284,6 +286,8 @@ struct DraftArgs {
   int8_t *row_src;        // [k]
 };
 void launch_build_drafts(int dtype, const DraftArgs &a, hipStream_t s);
+// the context matcher alone: reads hist, n, k, w, k_ctx_max, q_min, q_max and the three scratch arrays, writes ctx_rows, n_ctx
+void launch_ctx_match(const DraftArgs &a, hipStream_t s);
 // out[m][0..K) = ids of the K largest logits of row m by (value desc, id asc); logits [M][V] fp32
 void launch_row_topk(const float *logits, int M, int V, int K, int32_t *out, hipStream_t s);
 void launch_iota(int32_t *dst, int first, int n, hipStream_t s);

@@ -214,17 +214,52 @@ void launch_neg_row_sumsq(const float *rows, int M, int V, float *out, hipStream
 // by (count desc, last start desc); append continuations not taken yet until k_ctx_max rows.
 // Counts and last starts do not depend on the order in which matches were collected, so the
 // result is deterministic although the lists are filled with atomics.
+//
+// Grouping and ranking take one of two routes that give the same groups:
+//  * up to kSmallMatches matches: every match is compared with every other one, every group with
+//    every other group (a few hundred compares, no atomics on memory);
+//  * more (a frequent last token on a long context; a periodic context makes every window a
+//    match): the continuations go into an open-addressing hash table in the scratch memory, keyed
+//    by a hash of the w tokens and resolved by comparing the tokens themselves, each slot holding
+//    (a representative start, count, last start); the ranked prefix is then pulled out by
+//    repeated selection, every wave over its share of the groups and wave 0 over the waves'
+//    picks.  Linear in the number of matches.
 // ---------------------------------------------------------------------------------------------
+constexpr int kSmallMatches = 64;
+
 __device__ __forceinline__ bool same_cont(const int32_t *x, int a, int b, int w) {
   for (int t = 0; t < w; ++t)
     if (x[a + t] != x[b + t]) return false;
   return true;
 }
 
+__device__ __forceinline__ unsigned cont_hash(const int32_t *x, int a, int w) {
+  unsigned h = 0x811c9dc5u;
+  for (int t = 0; t < w; ++t) h = (h ^ (unsigned)x[a + t]) * 0x01000193u;
+  h ^= h >> 15;
+  h *= 0x2c1b3c6du;
+  h ^= h >> 12;
+  return h;
+}
+
+// rank key of a group: count in the high word, last start in the low word (distinct groups have
+// distinct last starts, so keys are unique); 0 = none
+__device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const unsigned lo = __shfl_xor((unsigned)v, off), hi = __shfl_xor((unsigned)(v >> 32), off);
+    const unsigned long long o = ((unsigned long long)hi << 32) | lo;
+    v = o > v ? o : v;
+  }
+  return v;
+}
+
 __global__ __launch_bounds__(1024) void ctx_match_kernel(const DraftArgs a) {
+  constexpr int NWAVE = 16, WANT_MAX = 64;
   __shared__ int n_match, n_rep, n_taken;
-  __shared__ int cand[64];          // start of the continuation ranked r among this q's groups
-  const int tid = threadIdx.x;
+  __shared__ int cand[WANT_MAX];                 // start of the continuation ranked r among this q's groups
+  __shared__ unsigned long long wkey[NWAVE * WANT_MAX];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int32_t *x = a.hist;
   const int n = a.n, w = a.w;
   const int kmax = min(a.k_ctx_max, a.k);
@@ -234,7 +269,7 @@ __global__ __launch_bounds__(1024) void ctx_match_kernel(const DraftArgs a) {
     for (int q = a.q_max; q >= a.q_min; --q) {
       if (q < 1 || n < q + w) continue;                     // uniform
       if (tid == 0) { n_match = 0; n_rep = 0; }
-      if (tid < 64) cand[tid] = -1;
+      if (tid < WANT_MAX) cand[tid] = -1;
       __syncthreads();
       if (n_taken >= kmax) break;                           // uniform: read after the barrier
       const int last_start = n - q - w;
@@ -245,30 +280,97 @@ __global__ __launch_bounds__(1024) void ctx_match_kernel(const DraftArgs a) {
       }
       __syncthreads();
       const int nm = n_match;
-      for (int t = tid; t < nm; t += 1024) {
-        const int i = a.mlist[t];
-        int cnt = 0, last = i;
-        for (int u = 0; u < nm; ++u) {
-          const int j = a.mlist[u];
-          if (same_cont(x, i + q, j + q, w)) { ++cnt; last = max(last, j); }
+      const int want = min(2 * kmax, WANT_MAX);
+      if (nm <= kSmallMatches) {
+        for (int t = tid; t < nm; t += 1024) {
+          const int i = a.mlist[t];
+          int cnt = 0, last = i;
+          for (int u = 0; u < nm; ++u) {
+            const int j = a.mlist[u];
+            if (same_cont(x, i + q, j + q, w)) { ++cnt; last = max(last, j); }
+          }
+          if (last == i) {                                  // one representative per continuation
+            const int slot = atomicAdd(&n_rep, 1);
+            a.reps[2 * slot] = cnt;
+            a.reps[2 * slot + 1] = i;
+          }
         }
-        if (last == i) {                                    // one representative per continuation
-          const int slot = atomicAdd(&n_rep, 1);
-          a.reps[2 * slot] = cnt;
-          a.reps[2 * slot + 1] = i;
+        __syncthreads();
+        const int nr = n_rep;
+        for (int t = tid; t < nr; t += 1024) {
+          const int cnt = a.reps[2 * t], i = a.reps[2 * t + 1];
+          int rank = 0;
+          for (int u = 0; u < nr; ++u) {
+            const int c2 = a.reps[2 * u], i2 = a.reps[2 * u + 1];
+            rank += (c2 > cnt || (c2 == cnt && i2 > i)) ? 1 : 0;
+          }
+          if (rank < want) cand[rank] = i + q;
         }
-      }
-      __syncthreads();
-      const int nr = n_rep;
-      const int want = min(2 * kmax, 64);
-      for (int t = tid; t < nr; t += 1024) {
-        const int cnt = a.reps[2 * t], i = a.reps[2 * t + 1];
-        int rank = 0;
-        for (int u = 0; u < nr; ++u) {
-          const int c2 = a.reps[2 * u], i2 = a.reps[2 * u + 1];
-          rank += (c2 > cnt || (c2 == cnt && i2 > i)) ? 1 : 0;
+      } else {
+        // ---- hash grouping: T >= 2 nm slots of (representative start, count, last start) ----------
+        int T = 128;
+        while (T < 2 * nm) T <<= 1;                           // T <= a.gtab_slots: the launcher sized it for 2 n matches
+        int *g_rep = a.gtab, *g_cnt = a.gtab + a.gtab_slots, *g_last = a.gtab + 2 * a.gtab_slots;
+        for (int sl = tid; sl < T; sl += 1024) { g_rep[sl] = -1; g_cnt[sl] = 0; g_last[sl] = -1; }
+        __syncthreads();
+        for (int t = tid; t < nm; t += 1024) {
+          const int i = a.mlist[t];
+          unsigned sl = cont_hash(x, i + q, w) & (unsigned)(T - 1);
+          for (int probe = 0; probe < T; ++probe) {         // the table is at most half full: an empty slot turns up
+            const int r = atomicCAS(&g_rep[sl], -1, i);
+            if (r == -1 || same_cont(x, r + q, i + q, w)) {
+              atomicAdd(&g_cnt[sl], 1);
+              atomicMax(&g_last[sl], i);
+              break;
+            }
+            sl = (sl + 1) & (unsigned)(T - 1);
+          }
         }
-        if (rank < want) cand[rank] = i + q;
+        __syncthreads();
+        // groups -> reps[] as (count, last start); the table was written by atomics, which act on the L2:
+        // read it there too (a plain load could hit a line the previous q left in this CU's L1)
+        for (int sl = tid; sl < T; sl += 1024) {
+          const int r = __hip_atomic_load(&g_rep[sl], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          if (r != -1) {
+            const int slot = atomicAdd(&n_rep, 1);
+            a.reps[2 * slot] = __hip_atomic_load(&g_cnt[sl], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            a.reps[2 * slot + 1] = __hip_atomic_load(&g_last[sl], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          }
+        }
+        __syncthreads();
+        const int nr = n_rep;
+        // ---- the `want` best groups in order: round r takes the largest key below the previous pick ----
+        unsigned long long prev = ~0ull;
+        for (int r = 0; r < want; ++r) {
+          unsigned long long best = 0;
+          for (int e = tid; e < nr; e += 1024) {
+            const unsigned long long key = ((unsigned long long)(unsigned)a.reps[2 * e] << 32) | (unsigned)a.reps[2 * e + 1];
+            if (key < prev && key > best) best = key;
+          }
+          best = wave_max_u64(best);
+          if (lane == 0) wkey[wave * WANT_MAX + r] = best;
+          prev = best;
+          if (best == 0) {                                  // this wave's share ran out: the later rounds are empty too
+            if (lane == 0)
+              for (int r2 = r + 1; r2 < want; ++r2) wkey[wave * WANT_MAX + r2] = 0;
+            break;
+          }
+        }
+        __syncthreads();
+        if (wave == 0) {
+          unsigned long long prev0 = ~0ull;
+          for (int r = 0; r < want; ++r) {
+            unsigned long long best = 0;
+            for (int e = lane; e < NWAVE * WANT_MAX; e += 64) {
+              const unsigned long long key = (e % WANT_MAX) < want ? wkey[e] : 0;
+              if (key < prev0 && key > best) best = key;
+            }
+            best = wave_max_u64(best);
+            if (best == 0) break;
+            if (lane == 0) cand[r] = (int)(unsigned)best + q;
+            prev0 = best;
+          }
+        }
       }
       __syncthreads();
       if (tid == 0) {
@@ -548,6 +650,8 @@ __global__ __launch_bounds__(64) void table_assemble_kernel(const DraftArgs a) {
     a.row_src[r] = 1;
   }
 }
+
+void launch_ctx_match(const DraftArgs &a, hipStream_t s) { hipLaunchKernelGGL(ctx_match_kernel, dim3(1), dim3(1024), 0, s, a); }
 
 void launch_build_drafts(int dtype, const DraftArgs &a, hipStream_t s) {
   if (a.bg_table || a.uni_top) {

@@ -181,3 +181,108 @@ def test_attention_cost_model_counts():
         pairs = sum(1 for r in range(k) for j in range(w + 1) for s in range((l - 1) + j + 1))
         assert pairs == k * ((w + 1) * (l - 1) + (w + 1) * (w + 2) // 2)
         assert pairs <= k * (w + 1) * (l + w)
+
+
+# ---------------------------------------------------------------------------
+# the greedy tie rule, the per-strategy bookkeeping, and the memory-bounded forms
+# ---------------------------------------------------------------------------
+
+def test_greedy_argmax_takes_the_lowest_id_among_equal_logits():
+    """Exact ties, hand-made: the FIRST maximum wins, in every position of a batch (a "last maximum" or a
+    "strictly greater from the right" scan fails each of these)."""
+    from oracle.model import greedy_argmax
+    assert int(greedy_argmax(np.array([1.0, 3.0, 3.0, 2.0]))) == 1
+    assert int(greedy_argmax(np.array([0.0, 5.0, 5.0]))) == 1            # the tie reaches the last entry
+    assert int(greedy_argmax(np.array([7.0, 7.0, 7.0, 7.0]))) == 0          # all equal
+    assert int(greedy_argmax(np.array([-2.0, -1.0, -3.0, -1.0]))) == 1      # negative logits
+    assert int(greedy_argmax(np.array([0.0, -0.0, 0.0]))) == 0              # +0 and -0 compare equal
+    grid = np.array([[[1.0, 1.0, 0.0], [0.0, 2.0, 2.0]], [[3.0, 0.0, 3.0], [0.0, 0.0, 0.0]]])
+    out = greedy_argmax(grid)
+    assert out.dtype == np.int32 and out.tolist() == [[0, 1], [0, 0]]
+
+
+class _ScriptedModel:
+    """A 'model' whose greedy prediction after token t is S[t], whatever came before: one-hot logits,
+    one layer of empty keys/values.  Offers what prefill / verify_step / commit use."""
+    L, Hkv, hd = 1, 1, 1
+
+    def __init__(self, succ):
+        self.succ = np.asarray(succ)
+
+    def forward_block(self, tokens, cache=None, want_logits=True):
+        tokens = np.asarray(tokens)
+        k, c = tokens.shape
+        logits = np.zeros((k, c, len(self.succ)))
+        for r in range(k):
+            for j in range(c):
+                logits[r, j, self.succ[tokens[r, j]]] = 1.0
+        kv = [(np.zeros((k, c, 1, 1)), np.zeros((k, c, 1, 1)))]
+        return logits, kv
+
+
+class _ScriptedBigram:
+    """Ranked first tokens from a table, chain through `nxt`."""
+
+    def __init__(self, top, nxt):
+        self.top, self.nxt = top, nxt
+
+    def rows(self, x, k_big, w):
+        out = []
+        for t in self.top[x][:k_big]:
+            row = [t]
+            while len(row) < w:
+                row.append(self.nxt[row[-1]])
+            out.append(tuple(row[:w]))
+        return out
+
+
+def test_strategy_bookkeeping_on_a_hand_worked_four_call_run():
+    """accept_hist / rank_hist / alloc_hist / new_hist / winner_src / ctx_rows of greedy_speculative, worked by
+    hand (Section 5.2's ablation quantities).  Model: next token S[t], S = two 4-cycles.  k=3, w=2, at most 2
+    context rows, q=2, 8 tokens.  Prompt 0 1 7 7 0 1 7 7 0 1; the prefill appends S[1] = 2.
+      call 1: query (1,2) never occurred: 0 context rows; bigram rows (4,5) (3,5) (5,6); the model says 3 then 0:
+              row 1 keeps 1 token -> bigram win, rank 1, 1 accepted, appends 3 0.
+      call 2: query (3,0) never occurred; bigram rows (2,3) (3,5) (4,5), the model says 1: nothing accepted, row 0
+              (a bigram row) 'wins' with 0 accepted -> no rank entry, appends 1.
+      call 3: query (0,1) occurred at 0, 4 (then 7 7) and 8 (then 2 3): context rows (7,7) [count 2], (2,3); one bigram
+              row (3,5); the model says 2 then 3: row 1 keeps 2 -> context win, rank 1, appends 2 3 0.
+      call 4: query (3,0) occurred at 11 (then 1 2): context row (1,2), bigram rows (2,3) (3,5); row 0 keeps 2 ->
+              context win, rank 0, 2 accepted, but only 1 token of budget is left: appends 1."""
+    S = [1, 2, 3, 0, 5, 6, 7, 4]
+    nxt = list(S)
+    nxt[3] = 5                                           # the chain is wrong after token 3
+    top = {2: [4, 3, 5], 0: [2, 3, 4], 1: [3, 2, 6]}
+    prompt = [0, 1, 7, 7, 0, 1, 7, 7, 0, 1]
+    gen, st = greedy_speculative(_ScriptedModel(S), prompt, 8, 3, 2, 2, 2, 2, bigram=_ScriptedBigram(top, nxt))
+    assert gen == [2, 3, 0, 1, 2, 3, 0, 1]
+    assert st["calls"] == 4
+    assert st["new_hist"] == [0, 2, 1, 1]
+    assert st["winner_src"] == [2, 2]
+    assert st["ctx_rows"] == [0, 0, 2, 1]
+    assert st["accept_hist"] == [[0, 0, 2], [1, 1, 0]]
+    assert st["rank_hist"] == [[1, 1, 0], [0, 1, 0]]
+    assert st["alloc_hist"] == [2, 1, 1, 0]
+    assert st["tokens_per_call"] == 7 / 4
+
+
+def test_chunked_prefill_and_widening_at_use_change_nothing(tiny):
+    """The memory-bounded forms used for long contexts and deep models: a prompt fed in pieces through the
+    cached block call gives the cache and first token of the one-piece prefill (up to fp64 summation order),
+    and widening the layer matrices at use instead of up front gives bit-identical logits."""
+    desc, w, run, prompt, m, plain = tiny
+    whole = prefill(m, prompt)
+    for chunk in (1, 7, 50, 127, 128, 500):
+        st = prefill(m, prompt, chunk=chunk)
+        assert st.tokens == whole.tokens and len(st.cache) == len(prompt)
+        for li in range(m.L):
+            assert np.allclose(st.cache.k[li], whole.cache.k[li], rtol=0, atol=1e-12)
+            assert np.allclose(st.cache.v[li], whole.cache.v[li], rtol=0, atol=1e-12)
+        assert np.allclose(st.first_logits, whole.first_logits, rtol=0, atol=1e-12)
+    lazy = Model(desc, w, widen_at_use=True)
+    assert lazy.layers[0]["wq"].dtype == np.float32                     # kept as stored
+    assert np.array_equal(lazy.forward_full(prompt[:40]), m.forward_full(prompt[:40]))
+    bdesc = si.reduced_layers(si.MODELS["small"], 1)
+    bdesc = dict(bdesc, vocab=256, d_model=64, n_heads=2, n_kv_heads=2, head_dim=32, d_ffn=128)
+    bw = si.make_weights(bdesc, seed=3)
+    assert np.array_equal(Model(bdesc, bw, widen_at_use=True).forward_full([1, 2, 3, 4, 5]),
+                          Model(bdesc, bw).forward_full([1, 2, 3, 4, 5]))
