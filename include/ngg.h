@@ -235,7 +235,8 @@ ngg_status ngg_profile_bracket_overhead(ngg_ctx *ctx, double *us);
  * k) of a tile matrix with K columns sits at ((n/16)*(K/32) + k/32)*512 + (((k%32)/8)*16 + n%16)*8
  * + k%8 for 2-byte elements), "attn" (attention output of the last layer, model dtype, in
  * chunks of 256 (bf16) or 128 (fp32) features: [feature chunk][Mcap rows][chunk]).
- * Synchronises the stream. */
+ * "attn_layout" (int32[4], host-side record of the last model call: slices of the key list per head,
+ * workgroups of the attention kernel, block rows, cached positions).  Synchronises the stream. */
 ngg_status ngg_debug_peek(ngg_ctx *ctx, const char *name, void *dst, int64_t cap, int64_t *bytes, int32_t *stride);
 
 #ifdef __cplusplus

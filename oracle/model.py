@@ -118,20 +118,26 @@ class Model:
             kk = self.rope(kk, pos)
             block_kv.append((kk, vv))
             kb, vb = self._expand_kv(kk), self._expand_kv(vv)
-            s_blk = np.einsum("rjhd,rshd->rhjs", q, kb) * scale    # [k, H, c, c]
+            # scores and weighted sums as stacked matrix products, heads moved in front of the token axis:
+            # q_h [k, H, c, hd]; keys and values of the block [k, H, c, hd], of the cached context [H, P, hd]
+            q_h = q.transpose(0, 2, 1, 3)
+            kb_h, vb_h = kb.transpose(0, 2, 1, 3), vb.transpose(0, 2, 1, 3)
+            s_blk = (q_h @ kb_h.transpose(0, 1, 3, 2)) * scale      # [k, H, c (query j), c (key s)]
             s_blk = np.where(causal[None, None], s_blk, -np.inf)
             if P > 0:
-                kp, vp = self._expand_kv(cache.k[li]), self._expand_kv(cache.v[li])
-                s_pre = np.einsum("rjhd,phd->rhjp", q, kp) * scale  # [k, H, c, P]
+                kp_h = self._expand_kv(cache.k[li]).transpose(1, 0, 2)       # [H, P, hd]
+                vp_h = self._expand_kv(cache.v[li]).transpose(1, 0, 2)
+                s_pre = (q_h @ kp_h.transpose(0, 2, 1)[None]) * scale       # [k, H, c, P]
                 s = np.concatenate([s_pre, s_blk], axis=-1)
             else:
                 s = s_blk
             s = s - s.max(axis=-1, keepdims=True)
             p = np.exp(s)
             p = p / p.sum(axis=-1, keepdims=True)
-            a = np.einsum("rhjs,rshd->rjhd", p[..., P:], vb)
+            a = p[..., P:] @ vb_h                                    # [k, H, c, hd]
             if P > 0:
-                a = a + np.einsum("rhjp,phd->rjhd", p[..., :P], vp)
+                a = a + p[..., :P] @ vp_h[None]
+            a = a.transpose(0, 2, 1, 3)                              # [k, c, H, hd]
             h = h + a.reshape(k, c, self.H * self.hd) @ lw["wo"].T
             x = self.rmsnorm(h, lw["mlp_norm"])
             h = h + (self.silu(x @ lw["w_gate"].T) * (x @ lw["w_up"].T)) @ lw["w_down"].T

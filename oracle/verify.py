@@ -48,11 +48,12 @@ class State:
         self.cache = cache
 
 
-def prefill(model: Model, prompt, chunk: int | None = None) -> State:
+def prefill(model: Model, prompt, chunk: int | None = None, progress=None) -> State:
     """Run the prompt, cache all of it, append the first greedy token.  With
     `chunk`, the prompt goes through the model in pieces of that many tokens, each
     a (1, chunk) block on the cache of the pieces before it: the same causal
-    forward pass (Section 3's block call with k = 1), with bounded memory."""
+    forward pass (Section 3's block call with k = 1), with bounded memory.
+    `progress(tokens_done)` is called after every piece."""
     prompt = [int(t) for t in prompt]
     cache = KVCache(model.L, model.Hkv, model.hd)
     step = len(prompt) if not chunk else int(chunk)
@@ -62,6 +63,8 @@ def prefill(model: Model, prompt, chunk: int | None = None) -> State:
         logits, kv = model.forward_block(piece, cache if p0 else None, want_logits=last)
         for li, (kk, vv) in enumerate(kv):
             cache.append(li, kk[0], vv[0])
+        if progress:
+            progress(min(p0 + step, len(prompt)))
     first = int(greedy_argmax(logits[0, -1]))
     st = State(prompt + [first], cache)
     st.first_logits = logits[0, -1]              # logits that chose the first generated token

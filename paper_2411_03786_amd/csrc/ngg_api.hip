@@ -59,6 +59,7 @@ struct ngg_ctx {
   int n = 0;                       // context length (0 = no prefill yet)
   bool have_verify = false;
   int last_k = 0, last_w = 0;
+  int32_t attn_layout[4] = {0, 0, 0, 0};   // last forward: key-list slices per head, attention workgroups, block rows, cached positions
   bool drafts_on_device = false;
   int drafts_k = 0, drafts_w = 0;
   std::string err;
@@ -138,6 +139,8 @@ ngg_status forward(ngg_ctx *c, int R, int C, int P, bool from_hist, int w, bool 
                  tok_src ? 0 : P, from_hist ? 1 : 0, s);
   }
   const int n_splits = attention_splits(dt, d.head_dim, d.n_heads, M, P, c->max_splits);
+  c->attn_layout[0] = n_splits; c->attn_layout[1] = attention_workgroups(dt, d.head_dim, d.n_heads, M, n_splits);
+  c->attn_layout[2] = M; c->attn_layout[3] = P;
   const size_t part_stride = (size_t)c->Mcap * d.d_model;
   const int ks_o = gemm_residual_splits(dt, M, d.d_model, dq), ks_down = gemm_residual_splits(dt, M, d.d_model, d.d_ffn);
   const int ss_segs = rmsnorm_segments(d.d_model);
@@ -788,6 +791,11 @@ ngg_status ngg_debug_peek(ngg_ctx *c, const char *name, void *dst, int64_t cap, 
   else if (nm == "kcache") { src = c->kcache; sz = kv; }
   else if (nm == "vcache") { src = c->vcache; sz = kv; }
   else if (nm == "attn") { src = c->attn; sz = act_elems(d.dtype, c->Mcap, d.n_heads * d.head_dim) * c->esize; }
+  else if (nm == "attn_layout") {                       // host-side record, no device copy
+    *bytes = (int64_t)sizeof c->attn_layout;
+    if (dst && cap > 0) memcpy(dst, c->attn_layout, std::min((size_t)cap, sizeof c->attn_layout));
+    return NGG_OK;
+  }
   else return fail(c, NGG_EINVAL, "ngg_debug_peek: unknown buffer '%s'", name);
   *bytes = (int64_t)sz;
   if (stride) *stride = c->Spad;

@@ -501,6 +501,12 @@ int attention_splits(int dtype, int hd, int H, int M, int P, int max_splits) {
   return s < 1 ? 1 : s;
 }
 
+int attention_workgroups(int dtype, int hd, int H, int M, int n_splits) {
+  const int qmax = dtype == 1 || hd <= 64 ? 2 : 1;
+  const int per_wg = M <= 16 ? 16 : (M <= 64 ? 64 : 64 * qmax);
+  return n_splits * H * ((M + per_wg - 1) / per_wg);
+}
+
 template <typename T>
 static void launch_t(int hd, const AttnArgs &a, hipStream_t s) {
   if (hd == 32) launch_hd<T, 32>(a, s);

@@ -251,6 +251,7 @@ void launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t s);
 int gemm_residual_splits(int dtype, int M, int N, int K);
 void launch_attention(int dtype, int hd, const AttnArgs &a, hipStream_t s);
 int attention_splits(int dtype, int hd, int H, int M, int P, int max_splits);
+int attention_workgroups(int dtype, int hd, int H, int M, int n_splits);   // workgroups the main attention kernel is launched with
 
 void launch_embed(int dtype, const void *tok_emb, const int32_t *hist, const int32_t *drafts, int32_t *block_tok,
                   float *h, int d, int M, int C, int w, int hist_base, int from_hist, hipStream_t s);

@@ -237,6 +237,34 @@ def test_degenerate_contexts_for_the_matcher():
         ctx.close()
 
 
+def test_matcher_on_long_contexts_with_thousands_of_matches():
+    """Contexts of several thousand tokens whose last token is frequent: hundreds to thousands of matching
+    windows, grouped through the hash table and ranked by repeated selection; exact against the oracle.
+    The model predicts succ(x) = x + 1, and every cut ends on a token whose successor is frequent in the
+    stream, so the generated last token has many earlier occurrences."""
+    desc, w, succ = _successor_model()
+    ctx = ngg.Context(desc, w, max_seq=5200, max_k=32, max_w=8)
+    rng = np.random.default_rng(21)
+    streams = ((si.prompt_spans(desc["vocab"], 5000, copied=0.5, seed=6), 0), (rng.integers(0, 4, 2500).astype(np.int32), 1),
+               (np.tile(np.array([3, 1, 4, 1, 5], dtype=np.int32), 600), 3), (np.zeros(3000, dtype=np.int32) + 2, 1))
+    rows_found = 0
+    for x, last in streams:
+        for cut in (len(x), len(x) - 1, len(x) // 2 + 3):
+            piece = x[:cut].copy()
+            piece[-1] = last
+            ctx.prefill(piece)
+            toks = [int(t) for t in ctx.get_tokens()]
+            assert toks[-1] == last + 1
+            for cfg in (dict(k=16, w=6, k_ctx_max=16, q_min=1, q_max=3), dict(k=32, w=2, k_ctx_max=32, q_min=1, q_max=1),
+                        dict(k=5, w=8, k_ctx_max=3, q_min=2, q_max=2)):
+                g_d, g_src, g_n = ctx.build_drafts(cfg)
+                want = oracle.context_rows(toks, cfg["w"], cfg["k_ctx_max"], cfg["q_min"], cfg["q_max"])
+                assert g_n == len(want) and [tuple(int(t) for t in r) for r in g_d[:g_n]] == [tuple(r) for r in want], (len(x), cut, cfg)
+                rows_found += g_n
+    ctx.close()
+    assert rows_found > 100
+
+
 def test_row_permutation_and_duplicate_rows(tiny):
     """Rows are independent given the shared prefix: a duplicate row gets the same logits as its original,
     permuting the rows permutes the results, and the committed tokens do not change (the winner is the
@@ -537,6 +565,54 @@ def test_7b_width_one_layer_twin_long_context_shape():
     ctx.close()
     print("7b one-layer twin, k=16 w=6:", rep)
     assert rep.max_rel_logit_err <= 2e-2
+
+
+def test_7b_width_one_layer_twin_at_the_long_context_configurations_own_length():
+    """Config 4 at its own context: prompt 16384 (50 % copied spans), k=16, w=6 (112 block rows), query
+    back-off q = 3..1, 7B widths, one layer.  The oracle takes the prompt in 512-token pieces through its
+    cached block call.  Covers what the shorter twins do not reach: rotary angles, cache tiles and the key
+    list at positions up to 16.4K, and the attention launch this shape takes (its slice count and workgroup
+    count are asserted, so a change of the layout shows up here)."""
+    desc = si.reduced_layers(si.MODELS["7b"], 1)
+    run = dict(si.RUNS["cfg4"], n_gen=16)
+    assert run["prompt_len"] == 16384 and (run["k"], run["w"]) == (16, 6)
+    w = si.make_weights(desc, seed=0)
+    prompt = si.make_prompt(run, desc["vocab"], seed=1)
+    model = oracle.Model(desc, w, widen_at_use=True)
+    ctx = ngg.Context(desc, w, max_seq=run["prompt_len"] + 64, max_k=run["k"], max_w=run["w"])
+    layouts = []
+    rep = lockstep_run(ctx, model, prompt, 16, run, TOL["bf16"], max_steps=2, oracle_chunk=512,
+                       on_step=lambda step: layouts.append(ctx.debug_peek("attn_layout", np.int32)[0].tolist()))
+    ctx.close()
+    print("7b one-layer twin at 16384 tokens, k=16 w=6:", rep, layouts)
+    assert rep.steps == 2 and rep.max_rel_logit_err <= 2e-2
+    for n_splits, wgs, M, P in layouts:
+        assert M == 112 and P >= 16384
+        assert n_splits >= 8 and wgs >= 256               # the key list of every head is cut into slices that fill the chip
+    assert layouts[0][:2] == list(EXPECTED_LONG_CONTEXT_LAYOUT), layouts[0]
+
+
+EXPECTED_LONG_CONTEXT_LAYOUT = (16, 512)      # slices per head, workgroups (two per CU) at M = 112, P = 16384, 32 heads
+
+
+@pytest.mark.parametrize("k,w", [(10, 5), (32, 8)])
+def test_3b_width_one_layer_twin_at_the_large_vocabulary_configurations_own_length(k, w):
+    """Config 5 at its own context: prompt 4096, 3B widths (24 heads of 128, vocabulary 128256), one layer;
+    k=10, w=5 and the largest block of its grid, k=32, w=8 (288 rows)."""
+    desc = si.reduced_layers(si.MODELS["3b"], 1)
+    run = dict(si.RUNS["cfg5"], k=k, w=w, k_ctx_max=k, n_gen=20)
+    assert run["prompt_len"] == 4096
+    w_ = si.make_weights(desc, seed=0)
+    prompt = si.make_prompt(run, desc["vocab"], seed=1)
+    model = oracle.Model(desc, w_, widen_at_use=True)
+    ctx = ngg.Context(desc, w_, max_seq=run["prompt_len"] + 64, max_k=k, max_w=w)
+    layouts = []
+    rep = lockstep_run(ctx, model, prompt, 20, run, TOL["bf16"], max_steps=2, oracle_chunk=1024,
+                       on_step=lambda step: layouts.append(ctx.debug_peek("attn_layout", np.int32)[0].tolist()))
+    ctx.close()
+    print("3b one-layer twin at 4096 tokens:", k, w, rep, layouts)
+    assert rep.steps == 2 and rep.max_rel_logit_err <= 2e-2
+    assert layouts[0][2] == k * (w + 1) and layouts[0][3] >= 4096 and layouts[0][1] >= 240
 
 
 @pytest.mark.parametrize("k,w", [(10, 5), (32, 8)])
