@@ -224,6 +224,22 @@ ngg_status ngg_profile_read(ngg_ctx *ctx, double *ms /*[NGG_PROF_COUNT]*/, int64
  * that is the dispatch of the launch and the events themselves, not the kernel. */
 ngg_status ngg_profile_bracket_overhead(ngg_ctx *ctx, double *us);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): the context N-gram rows of ngg_build_drafts without a context
+ * object and without any allocation.  tokens: DEVICE [n], the whole context, its last q tokens being
+ * the query; rows: DEVICE [k_ctx_max][w], the continuations found, in rank order (count descending,
+ * ties to the later match; query lengths q_max down to q_min, a continuation already taken is skipped);
+ * *n_rows: DEVICE, how many rows were found (rows beyond it are left untouched).  The matcher's working
+ * memory (match list, group table: 1.125 MiB) is a static device array inside the library, so
+ * n <= NGG_STATIC_MAX_TOKENS (NGG_ECAPACITY beyond); 1 <= w, k_ctx_max <= 32; 1 <= q_min <= q_max <= 64.
+ * The launch is queued on hip_stream (a hipStream_t, NULL = the default stream) and the call returns
+ * without synchronising; it calls no hipMalloc / hipFree / memset.  All calls on one GPU share the
+ * one array: calls that overlap in time on a GPU (different streams or threads) race; calls queued
+ * on one stream do not.  Errors are reported through ngg_last_error(NULL). */
+#define NGG_STATIC_MAX_TOKENS 32768
+ngg_status ngg_context_drafts_static(const int32_t *tokens, int32_t n, int32_t w, int32_t k_ctx_max, int32_t q_min,
+                                     int32_t q_max, int32_t *rows, int32_t *n_rows, void *hip_stream);
+
 /* Debug aid for parity tests: copies an internal device buffer to dst (HOST), at most cap bytes,
  * and reports its full size in *bytes.  Names: "h" (residual stream, fp32 [M][d_model]), "z"
  * (bigram scores of the last ngg_build_drafts, fp32 [vocab]), "next1" (int32 [vocab]), "hist"

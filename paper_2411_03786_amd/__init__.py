@@ -22,7 +22,9 @@ PROF_CLASSES = ("gemm_qkv", "gemm_o", "gemm_gateup", "gemm_down", "gemm_unembed"
 
 EXPORTS = ("ngg_create", "ngg_destroy", "ngg_prefill", "ngg_build_drafts", "ngg_verify_step", "ngg_commit",
            "ngg_greedy_decode", "ngg_get_tokens", "ngg_last_error", "ngg_profile_enable", "ngg_profile_reset",
-           "ngg_profile_read", "ngg_debug_peek", "ngg_bigram_table_build", "ngg_bigram_source", "ngg_profile_bracket_overhead", "ngg_unigram_build", "ngg_decode_more", "ngg_profile_sample")
+           "ngg_profile_read", "ngg_debug_peek", "ngg_bigram_table_build", "ngg_bigram_source", "ngg_profile_bracket_overhead", "ngg_unigram_build", "ngg_decode_more", "ngg_profile_sample",
+           "ngg_context_drafts_static")
+NGG_STATIC_MAX_TOKENS = 32768
 
 
 class ngg_model_desc(C.Structure):
@@ -93,6 +95,7 @@ def load_library():
     lib.ngg_unigram_build.argtypes = [vp, C.c_int32]
     lib.ngg_profile_bracket_overhead.argtypes = [vp, C.POINTER(C.c_double)]
     lib.ngg_bigram_source.argtypes = [vp, C.c_int32]
+    lib.ngg_context_drafts_static.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp, vp, vp]
     for name in EXPORTS:
         if name != "ngg_last_error":
             getattr(lib, name).restype = C.c_int32
@@ -289,3 +292,22 @@ class Context:
         cnt = (C.c_int64 * n)()
         self._check(self.lib.ngg_profile_read(self.h, ms, cnt))
         return {name: (ms[i], cnt[i]) for i, name in enumerate(PROF_CLASSES)}
+
+
+def context_drafts_static(tokens, w, k_ctx_max, q_min, q_max, rows, n_rows, stream=None, n=None):
+    """ngg_context_drafts_static: the context N-gram rows for `tokens` (int32 DEVICE tensor, the whole
+    context) into `rows` (int32 DEVICE tensor [k_ctx_max][w]) and `n_rows` (int32 DEVICE tensor [1]),
+    queued on `stream` (a torch stream, default: the current one) without synchronising.  Allocates
+    nothing.  `n` overrides the token count (for testing the argument checks)."""
+    import torch
+    lib = load_library()
+    for t in (tokens, rows, n_rows):
+        if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.int32 and t.is_contiguous()):
+            raise TypeError("context_drafts_static takes contiguous int32 device tensors")
+    if rows.numel() < k_ctx_max * w or n_rows.numel() < 1:
+        raise ValueError("rows must hold k_ctx_max * w entries and n_rows one")
+    s = stream if stream is not None else torch.cuda.current_stream()
+    st = lib.ngg_context_drafts_static(tokens.data_ptr(), int(tokens.numel() if n is None else n), int(w), int(k_ctx_max),
+                                       int(q_min), int(q_max), rows.data_ptr(), n_rows.data_ptr(), s.cuda_stream)
+    if st != NGG_OK:
+        raise NggError(st, lib.ngg_last_error(None).decode())

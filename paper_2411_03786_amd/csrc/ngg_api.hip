@@ -8,11 +8,19 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
 
 using namespace ngg;
+
+// Scratch memory of ngg_context_drafts_static: match list, (count, last start) pairs and the grouping
+// table of the context matcher for up to NGG_STATIC_MAX_TOKENS tokens.  Every GPU the library runs on
+// holds its own copy until the process ends.
+constexpr int kStaticSlots = 2 * NGG_STATIC_MAX_TOKENS;                       // a power of two
+constexpr size_t kStaticInts = (size_t)NGG_STATIC_MAX_TOKENS * 3 + (size_t)3 * kStaticSlots;
+static __device__ __align__(256) int32_t scratch[kStaticInts];
 
 namespace {
 
@@ -771,6 +779,46 @@ ngg_status ngg_bigram_source(ngg_ctx *c, int32_t source) {
   c->bg_use = source == NGG_BIGRAM_TABLE;
   c->uni_use = source == NGG_UNIGRAM;
   c->drafts_on_device = false;
+  return NGG_OK;
+}
+
+ngg_status ngg_context_drafts_static(const int32_t *tokens, int32_t n, int32_t w, int32_t k_ctx_max, int32_t q_min,
+                                     int32_t q_max, int32_t *rows, int32_t *n_rows, void *hip_stream) {
+  static_assert((kStaticSlots & (kStaticSlots - 1)) == 0, "the grouping table needs a power-of-two slot count");
+  if (!tokens || !rows || !n_rows) return fail(nullptr, NGG_EINVAL, "ngg_context_drafts_static: null pointer");
+  if (n < 1 || n > NGG_STATIC_MAX_TOKENS)
+    return fail(nullptr, NGG_ECAPACITY, "ngg_context_drafts_static: n=%d outside 1 .. %d (the static scratch holds no more)", n,
+                NGG_STATIC_MAX_TOKENS);
+  if (w < 1 || w > 32 || k_ctx_max < 1 || k_ctx_max > 32)
+    return fail(nullptr, NGG_EINVAL, "ngg_context_drafts_static: need 1 <= w <= 32 and 1 <= k_ctx_max <= 32");
+  if (q_min < 1 || q_max < q_min || q_max > 64)
+    return fail(nullptr, NGG_EINVAL, "ngg_context_drafts_static: need 1 <= q_min <= q_max <= 64");
+  // the array's device address, looked up once per device (each GPU has its own copy at its own address)
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static int32_t *base[kMaxDevices] = {};
+  int dev = -1;
+  NGG_HIP(nullptr, hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(nullptr, NGG_EINVAL, "ngg_context_drafts_static: device %d not supported", dev);
+  int32_t *ptr = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(mu);
+    if (!base[dev]) {
+      void *p = nullptr;
+      NGG_HIP(nullptr, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+      base[dev] = (int32_t *)p;
+    }
+    ptr = base[dev];
+  }
+  DraftArgs a{};
+  a.hist = tokens; a.n = n; a.k = k_ctx_max; a.w = w; a.k_ctx_max = k_ctx_max; a.q_min = q_min; a.q_max = q_max;
+  a.mlist = ptr;
+  a.reps = ptr + NGG_STATIC_MAX_TOKENS;
+  a.gtab = ptr + (size_t)3 * NGG_STATIC_MAX_TOKENS;
+  a.gtab_slots = kStaticSlots;
+  a.ctx_rows = rows; a.n_ctx = n_rows;
+  launch_ctx_match(a, (hipStream_t)hip_stream);      // clears the part of the table it uses itself: nothing to reset here
+  NGG_HIP(nullptr, hipGetLastError());
   return NGG_OK;
 }
 
