@@ -58,9 +58,11 @@ struct ngg_ctx {
   void *xn = nullptr, *q = nullptr, *attn = nullptr, *act = nullptr;
   // the library's own operand-order copies of every matrix it multiplies with
   void *wtiled = nullptr;          // one allocation
-  struct LayerT { const void *wqkv, *wo, *wgu, *wdown; };
+  struct LayerT { const void *wqkv, *wo, *wgu, *wdown; float s_qkv, s_o, s_gu, s_down; };   // s_*: power-of-two scale of the stored copy
   std::vector<LayerT> lt;
   const void *unemb_t = nullptr;
+  float unemb_scale = 1.0f;        // the operand-order copy of the output embedding holds the stored values times this
+  float emb_scale = 1.0f;          // rows of the input embedding are multiplied by this when they become a 16-bit operand
   int32_t *res_host = nullptr;     // pinned
   // host state
   std::vector<int32_t> tokens;     // committed history mirror
@@ -168,6 +170,7 @@ ngg_status forward(ngg_ctx *c, int R, int C, int P, bool from_hist, int w, bool 
       g.H = d.n_heads; g.Hkv = d.n_kv_heads; g.hd = d.head_dim; g.Mcap = c->Mcap; g.C = C; g.P = P;
       g.rope_cos = c->rope_cos; g.rope_sin = c->rope_sin;
       g.row_ss = c->row_ss; g.ss_segs = ss_segs; g.ss_eps = d.rms_eps;
+      g.out_scale = 1.0f / c->lt[l].s_qkv;
       launch_gemm(dt, EPI_QKV, g, s);
     }
     {
@@ -188,6 +191,7 @@ ngg_status forward(ngg_ctx *c, int R, int C, int P, bool from_hist, int w, bool 
       GemmArgs g{};
       g.X = c->attn; g.W0 = c->lt[l].wo; g.M = M; g.N = d.d_model; g.K = dq;
       g.hpart = c->hpart; g.KS = ks_o; g.Mcap = c->Mcap;
+      g.out_scale = 1.0f / c->lt[l].s_o;
       launch_gemm(dt, EPI_RESIDUAL, g, s);
     }
     { ProfScope ps(c, NGG_PROF_NORM); launch_rmsnorm(dt, c->h, c->hpart, ks_o, part_stride, lw.mlp_norm, c->xn, d.d_model, M, c->Mcap, c->row_ss, s); }
@@ -197,6 +201,7 @@ ngg_status forward(ngg_ctx *c, int R, int C, int P, bool from_hist, int w, bool 
       g.X = c->xn; g.W0 = c->lt[l].wgu; g.M = M; g.N = d.d_ffn; g.K = d.d_model;
       g.act = c->act; g.Mcap = c->Mcap;
       g.row_ss = c->row_ss; g.ss_segs = ss_segs; g.ss_eps = d.rms_eps;
+      g.out_scale = 1.0f / c->lt[l].s_gu;
       launch_gemm(dt, EPI_GATEUP, g, s);
     }
     {
@@ -204,6 +209,7 @@ ngg_status forward(ngg_ctx *c, int R, int C, int P, bool from_hist, int w, bool 
       GemmArgs g{};
       g.X = c->act; g.W0 = c->lt[l].wdown; g.M = M; g.N = d.d_model; g.K = d.d_ffn;
       g.hpart = c->hpart; g.KS = ks_down; g.Mcap = c->Mcap;
+      g.out_scale = 1.0f / c->lt[l].s_down;
       launch_gemm(dt, EPI_RESIDUAL, g, s);
     }
     pending = ks_down;
@@ -216,6 +222,7 @@ ngg_status forward(ngg_ctx *c, int R, int C, int P, bool from_hist, int w, bool 
     g.logits = want_logits ? c->logits : nullptr;
     g.pmax_val = c->pmax_val; g.pmax_idx = c->pmax_idx; g.Mcap = c->Mcap;
     g.row_ss = c->row_ss; g.ss_segs = ss_segs; g.ss_eps = d.rms_eps;
+    g.out_scale = 1.0f / c->unemb_scale;
     launch_gemm(dt, EPI_UNEMBED, g, s);
   }
   NGG_HIP(c, hipGetLastError());
@@ -234,11 +241,12 @@ ngg_status build_next1(ngg_ctx *c) {
   for (int x0 = 0; x0 < d.vocab; x0 += 64) {
     const int M = std::min(64, d.vocab - x0);
     launch_pack_rows(d.dtype, (const char *)c->w.tok_emb + (size_t)x0 * d.d_model * c->esize, c->xn, d.d_model, M, c->Mcap,
-                     c->stream);
+                     c->stream, c->emb_scale);
     GemmArgs g{};
     g.X = c->xn;
     g.W0 = c->unemb_t; g.M = M; g.N = d.vocab; g.K = d.d_model;
     g.pmax_val = c->pmax_val; g.pmax_idx = c->pmax_idx; g.Mcap = c->Mcap;
+    g.out_scale = 1.0f / (c->unemb_scale * c->emb_scale);
     launch_gemm(d.dtype, EPI_UNEMBED, g, c->stream);
     launch_next1_finish(c->pmax_val, c->pmax_idx, c->unembed_tiles, c->Mcap, M, c->next1 + x0, c->stream);
   }
@@ -247,7 +255,17 @@ ngg_status build_next1(ngg_ctx *c) {
   return NGG_OK;
 }
 
-// Copies every matrix the step multiplies with into operand order (one-off, at create).
+// Power of two that brings a matrix whose largest magnitude is `amax` to [2^13, 2^14) (fp16 holds up to
+// 65504): the 16-bit copy then keeps every bit of a bf16 value down to 2^-31 of the maximum.
+float operand_scale(int dtype, float amax) {
+  if (dtype != NGG_BF16 || !(amax > 0.0f) || !std::isfinite(amax)) return 1.0f;
+  int e = 0;
+  (void)std::frexp(amax, &e);                              // amax = m * 2^e, 0.5 <= m < 1
+  return std::ldexp(1.0f, 14 - e);
+}
+
+// Copies every matrix the step multiplies with into operand order (one-off, at create); 16-bit models:
+// scaled by a power of two per matrix (q, k, v share one, gate and up share one) and rounded to fp16.
 ngg_status tile_all_weights(ngg_ctx *c) {
   const ngg_model_desc &d = c->d;
   const size_t dq = (size_t)d.n_heads * d.head_dim, dkv = (size_t)d.n_kv_heads * d.head_dim;
@@ -256,24 +274,58 @@ ngg_status tile_all_weights(ngg_ctx *c) {
   const size_t total = e_layer * d.n_layers + (size_t)d.vocab * d.d_model;
   ngg_status st = dev_alloc(c, &c->wtiled, total * c->esize, false);
   if (st != NGG_OK) return st;
+  // largest magnitude per stored copy: 4 per layer, then the output and the input embedding
+  const int n_max = 4 * d.n_layers + 2;
+  unsigned *amax_dev = nullptr;
+  st = dev_alloc(c, &amax_dev, (size_t)n_max * sizeof(unsigned), true);
+  if (st != NGG_OK) return st;
+  std::vector<unsigned> amax_bits((size_t)n_max, 0u);
+  if (d.dtype == NGG_BF16) {
+    for (int l = 0; l < d.n_layers; ++l) {
+      const ngg_layer_weights &lw = c->layers[l];
+      unsigned *a = amax_dev + 4 * l;
+      launch_absmax(d.dtype, lw.wq, dq * d.d_model, a + 0, c->stream);
+      launch_absmax(d.dtype, lw.wk, dkv * d.d_model, a + 0, c->stream);
+      launch_absmax(d.dtype, lw.wv, dkv * d.d_model, a + 0, c->stream);
+      launch_absmax(d.dtype, lw.wo, e_o, a + 1, c->stream);
+      launch_absmax(d.dtype, lw.w_gate, e_gu / 2, a + 2, c->stream);
+      launch_absmax(d.dtype, lw.w_up, e_gu / 2, a + 2, c->stream);
+      launch_absmax(d.dtype, lw.w_down, e_down, a + 3, c->stream);
+    }
+    launch_absmax(d.dtype, c->w.unemb, (size_t)d.vocab * d.d_model, amax_dev + 4 * d.n_layers, c->stream);
+    launch_absmax(d.dtype, c->w.tok_emb, (size_t)d.vocab * d.d_model, amax_dev + 4 * d.n_layers + 1, c->stream);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipMemcpyAsync(amax_bits.data(), amax_dev, (size_t)n_max * sizeof(unsigned), hipMemcpyDeviceToHost, c->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) { (void)hipFree(amax_dev); return fail(c, NGG_EHIP, "ngg_create: weight range scan failed: %s", hipGetErrorString(e)); }
+  }
+  (void)hipFree(amax_dev);
+  auto scale_of = [&](int i) {
+    float amax;
+    memcpy(&amax, &amax_bits[(size_t)i], sizeof amax);
+    return operand_scale(d.dtype, amax);
+  };
   char *base = (char *)c->wtiled;
   c->lt.resize(d.n_layers);
   for (int l = 0; l < d.n_layers; ++l) {
     const ngg_layer_weights &lw = c->layers[l];
     char *p = base + (size_t)l * e_layer * c->esize;
     char *qkv = p, *o = qkv + e_qkv * c->esize, *gu = o + e_o * c->esize, *down = gu + e_gu * c->esize;
+    const float s_qkv = scale_of(4 * l), s_o = scale_of(4 * l + 1), s_gu = scale_of(4 * l + 2), s_down = scale_of(4 * l + 3);
     // q, k, v: every 16-row fragment holds 8 pairs (i, i + hd/2) of one head; gate/up: gate and up of 8 features
-    launch_tile_weights(d.dtype, lw.wq, qkv, (int)dq, d.d_model, 0, c->stream, 1, d.head_dim / 2);
-    launch_tile_weights(d.dtype, lw.wk, qkv, (int)dkv, d.d_model, (int)dq, c->stream, 1, d.head_dim / 2);
-    launch_tile_weights(d.dtype, lw.wv, qkv, (int)dkv, d.d_model, (int)(dq + dkv), c->stream, 1, d.head_dim / 2);
-    launch_tile_weights(d.dtype, lw.wo, o, d.d_model, (int)dq, 0, c->stream);
-    launch_tile_weights(d.dtype, lw.w_gate, gu, d.d_ffn, d.d_model, 0, c->stream, 2);
-    launch_tile_weights(d.dtype, lw.w_up, gu, d.d_ffn, d.d_model, 0, c->stream, 3);
-    launch_tile_weights(d.dtype, lw.w_down, down, d.d_model, d.d_ffn, 0, c->stream);
-    c->lt[l] = {qkv, o, gu, down};
+    launch_tile_weights(d.dtype, lw.wq, qkv, (int)dq, d.d_model, 0, c->stream, s_qkv, 1, d.head_dim / 2);
+    launch_tile_weights(d.dtype, lw.wk, qkv, (int)dkv, d.d_model, (int)dq, c->stream, s_qkv, 1, d.head_dim / 2);
+    launch_tile_weights(d.dtype, lw.wv, qkv, (int)dkv, d.d_model, (int)(dq + dkv), c->stream, s_qkv, 1, d.head_dim / 2);
+    launch_tile_weights(d.dtype, lw.wo, o, d.d_model, (int)dq, 0, c->stream, s_o);
+    launch_tile_weights(d.dtype, lw.w_gate, gu, d.d_ffn, d.d_model, 0, c->stream, s_gu, 2);
+    launch_tile_weights(d.dtype, lw.w_up, gu, d.d_ffn, d.d_model, 0, c->stream, s_gu, 3);
+    launch_tile_weights(d.dtype, lw.w_down, down, d.d_model, d.d_ffn, 0, c->stream, s_down);
+    c->lt[l] = {qkv, o, gu, down, s_qkv, s_o, s_gu, s_down};
   }
   char *ue = base + e_layer * d.n_layers * c->esize;
-  launch_tile_weights(d.dtype, c->w.unemb, ue, d.vocab, d.d_model, 0, c->stream);
+  c->unemb_scale = scale_of(4 * d.n_layers);
+  c->emb_scale = scale_of(4 * d.n_layers + 1);
+  launch_tile_weights(d.dtype, c->w.unemb, ue, d.vocab, d.d_model, 0, c->stream, c->unemb_scale);
   c->unemb_t = ue;
   NGG_HIP(c, hipGetLastError());
   return NGG_OK;
@@ -465,7 +517,7 @@ ngg_status ngg_build_drafts(ngg_ctx *c, const ngg_draft_cfg *cfg, int32_t *draft
     DraftArgs a{};
     a.hist = c->hist; a.n = c->n; a.k = cfg->k; a.w = cfg->w; a.k_ctx_max = cfg->k_ctx_max; a.q_min = cfg->q_min; a.q_max = cfg->q_max;
     a.mlist = c->mlist; a.reps = c->reps; a.gtab = c->gtab; a.gtab_slots = c->gtab_slots; a.ctx_rows = c->ctx_rows; a.n_ctx = c->n_ctx;
-    a.tok_emb = c->w.tok_emb; a.unemb_t = c->unemb_t; a.d = c->d.d_model; a.vocab = c->d.vocab; a.z = c->z; a.cand_val = c->cand_val; a.cand_idx = c->cand_idx; a.next1 = c->next1;
+    a.tok_emb = c->w.tok_emb; a.emb_scale = c->emb_scale; a.unemb_t = c->unemb_t; a.unemb_scale = c->unemb_scale; a.d = c->d.d_model; a.vocab = c->d.vocab; a.z = c->z; a.cand_val = c->cand_val; a.cand_idx = c->cand_idx; a.next1 = c->next1;
     a.drafts = c->drafts; a.row_src = c->row_src;
     if (c->bg_use) { a.bg_table = c->bg_table; a.bg_K = c->bg_K; }
     if (c->uni_use) a.uni_top = c->uni_top;
@@ -741,7 +793,8 @@ ngg_status ngg_unigram_build(ngg_ctx *c, int32_t top_k) {
   if (st == NGG_OK) st = dev_alloc(c, &mean, (size_t)d.d_model * 4, false);
   if (st == NGG_OK) st = dev_alloc(c, &negd2, (size_t)d.vocab * 4, false);
   if (st == NGG_OK) {
-    launch_tile_weights(d.dtype, c->w.tok_emb, emb_t, d.vocab, d.d_model, 0, c->stream);
+    launch_tile_weights(d.dtype, c->w.tok_emb, emb_t, d.vocab, d.d_model, 0, c->stream, c->emb_scale);
+    const float row_scale = d.dtype == NGG_BF16 ? 0.5f * c->unemb_scale : 1.0f;   // a centred row is at most twice the largest entry
     launch_column_mean(d.dtype, c->w.unemb, d.vocab, d.d_model, mean, c->stream);
     c->have_verify = false;                            // the activation buffers are reused
     // d(x)^2 = sum_y ((u_x - u_mean) . v_y)^2: rows u_x - u_mean through the GEMM against the input
@@ -749,11 +802,12 @@ ngg_status ngg_unigram_build(ngg_ctx *c, int32_t top_k) {
     for (int x0 = 0; x0 < d.vocab; x0 += c->Mcap) {
       const int M = std::min(c->Mcap, d.vocab - x0);
       launch_pack_rows(d.dtype, (const char *)c->w.unemb + (size_t)x0 * d.d_model * c->esize, c->xn, d.d_model, M, c->Mcap,
-                       c->stream, mean);
+                       c->stream, row_scale, mean);
       GemmArgs g{};
       g.X = c->xn;
       g.W0 = emb_t; g.M = M; g.N = d.vocab; g.K = d.d_model;
       g.logits = c->logits; g.pmax_val = c->pmax_val; g.pmax_idx = c->pmax_idx; g.Mcap = c->Mcap;
+      g.out_scale = 1.0f / (c->emb_scale * row_scale);
       launch_gemm(d.dtype, EPI_UNEMBED, g, c->stream);
       launch_neg_row_sumsq(c->logits, M, d.vocab, negd2 + x0, c->stream);
     }

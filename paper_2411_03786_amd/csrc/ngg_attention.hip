@@ -20,17 +20,23 @@
 
 namespace ngg {
 
-// Softmax arithmetic: the fp32 configuration uses expf on scores scaled by 1/sqrt(hd); the bf16
+// Softmax arithmetic: the fp32 configuration uses expf on scores scaled by 1/sqrt(hd); the 16-bit
 // configuration keeps scores, running maxima and the stored partial maxima in the base-2 domain
 // (scores times log2(e)/sqrt(hd)) so that each probability is one subtraction and one v_exp_f32.
+// There the probabilities are computed as 2^(s - max + 10): the factor 2^10 is carried by the running
+// sums and by the output alike and cancels in their quotient; it keeps probabilities down to 2^-24 of
+// the row maximum in fp16's normal range (an fp16 matrix operand below 2^-14 may be flushed to zero,
+// and thousands of such keys can add up to a visible share of a long context's softmax).
 template <typename T> struct Softmax;
 template <> struct Softmax<float> {
   static __device__ __forceinline__ float factor(float scale) { return scale; }
   static __device__ __forceinline__ float ex(float x) { return expf(x); }
+  static __device__ __forceinline__ float prob(float x) { return expf(x); }
 };
-template <> struct Softmax<bf16_t> {
+template <> struct Softmax<half_t> {
   static __device__ __forceinline__ float factor(float scale) { return scale * 1.44269504088896f; }
   static __device__ __forceinline__ float ex(float x) { return __builtin_amdgcn_exp2f(x); }
+  static __device__ __forceinline__ float prob(float x) { return __builtin_amdgcn_exp2f(x + 10.0f); }
 };
 
 // One 16-query fragment against one 32-key tile, after the scores: online softmax and P.V.
@@ -61,13 +67,13 @@ __device__ __forceinline__ void softmax_pv(const f32x4 (&Sc)[2], float sfac, boo
   if (full) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      p[e] = Softmax<T>::ex(sv[e] - mnew);
+      p[e] = Softmax<T>::prob(sv[e] - mnew);
       ps += p[e];
     }
   } else {
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      p[e] = sv[e] > 0.5f * kNegBig ? Softmax<T>::ex(sv[e] - mnew) : 0.0f;
+      p[e] = sv[e] > 0.5f * kNegBig ? Softmax<T>::prob(sv[e] - mnew) : 0.0f;
       ps += p[e];
     }
   }
@@ -515,7 +521,7 @@ static void launch_t(int hd, const AttnArgs &a, hipStream_t s) {
 }
 
 void launch_attention(int dtype, int hd, const AttnArgs &a, hipStream_t s) {
-  if (dtype == 1) launch_t<bf16_t>(hd, a, s);
+  if (dtype == 1) launch_t<half_t>(hd, a, s);
   else launch_t<float>(hd, a, s);
 }
 

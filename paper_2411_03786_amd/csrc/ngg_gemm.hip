@@ -54,8 +54,9 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
     if (!a.row_ss) return f32x4{0.f, 0.f, 0.f, 0.f};
     return *reinterpret_cast<const f32x4 *>(a.row_ss + (size_t)(m < a.Mcap ? m : a.Mcap - 1) * kNormSegs);
   };
+  // ... times the factor that undoes the power-of-two scales of the stored operands (1 for fp32 models)
   auto row_scale = [&](const f32x4 &ss) {
-    return a.row_ss ? 1.0f / sqrtf((((ss[0] + ss[1]) + ss[2]) + ss[3]) / (float)K + a.ss_eps) : 1.0f;
+    return (a.row_ss ? 1.0f / sqrtf((((ss[0] + ss[1]) + ss[2]) + ss[3]) / (float)K + a.ss_eps) : 1.0f) * a.out_scale;
   };
   const int n_groups = a.n_groups;
   int group = blockIdx.x * WN + wn;
@@ -303,7 +304,8 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
 #pragma unroll
             for (int f = 0; f < FN; ++f)
               *reinterpret_cast<float4 *>(dst + nbase[f] + 4 * g) =
-                  float4{acc[f][fm][0], acc[f][fm][1], acc[f][fm][2], acc[f][fm][3]};
+                  float4{acc[f][fm][0] * a.out_scale, acc[f][fm][1] * a.out_scale, acc[f][fm][2] * a.out_scale,
+                         acc[f][fm][3] * a.out_scale};
           }
         } else {   // EPI_UNEMBED: optional logits, and this wave's best (value, id) per column
           float bv = kNegBig;
@@ -442,7 +444,7 @@ static bool residual_narrow(int M, int N, int K) { return M <= 16 || K <= N; }
 // Split of the contraction across workgroups for the residual GEMMs: about one workgroup per CU, as
 // long as each split keeps at least 2 chunks.
 int gemm_residual_splits(int dtype, int M, int N, int K) {
-  const int kc = dtype == 1 ? KChunk<bf16_t>::value : KChunk<float>::value;
+  const int kc = dtype == 1 ? KChunk<half_t>::value : KChunk<float>::value;
   const int n_chunks = (K + kc - 1) / kc;
   const int blocks = residual_narrow(M, N, K) ? N / 32 : (N / 32 + 1) / 2;
   int ks = (256 + blocks - 1) / blocks;
@@ -474,7 +476,7 @@ static void launch_t(int epi, const GemmArgs &a_in, hipStream_t s) {
 }
 
 void launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t s) {
-  if (dtype == 1) launch_t<bf16_t>(epi, a, s);
+  if (dtype == 1) launch_t<half_t>(epi, a, s);
   else launch_t<float>(epi, a, s);
 }
 

@@ -7,8 +7,22 @@
 
 namespace ngg {
 
+// Element types.  A model stored in bf16 (ngg_dtype NGG_BF16) is computed with fp16 matrix operands: the
+// library's operand-order copies of the weights are the stored bf16 values times a power of two chosen
+// per matrix so that they are exact in fp16 (8 mantissa bits fit in 11; the scale brings the largest
+// magnitude to [2^13, 2^14), so everything down to 2^-31 of it keeps all its bits), and activations,
+// keys, values and probabilities are rounded to fp16 (11 mantissa bits) instead of bf16 (8).  The MFMA
+// rate is the same, HBM bytes are the same, and the rounding noise per operand is 8 times smaller:
+// with bf16 operands the logits of the 7B-width model drift past the 2e-2 logit tolerance between 8 and
+// 16 layers.  bf16_t below is only the type user weights are READ in; half_t is the internal type.
 typedef __bf16 bf16_t;
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half_t;
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+template <typename U> struct Internal;                       // storage type of the user's weights -> internal element type
+template <> struct Internal<float> { typedef float type; };
+template <> struct Internal<bf16_t> { typedef half_t type; };
+constexpr float kHalfMax = 65504.0f;
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
@@ -17,18 +31,18 @@ constexpr float kNegBig = -1.0e30f;   // "minus infinity" that stays finite unde
 // ---------------------------------------------------------------------------------------------
 // MFMA operand fragments.  A fragment is the 8 consecutive contraction-index elements one lane
 // feeds into a 16x16 matrix op: lane l supplies row/column (l % 16) and elements 8*(l/16) .. +8 of
-// a 32-element slice of the contraction index.  bf16 uses one v_mfma_f32_16x16x32_bf16; fp32
+// a 32-element slice of the contraction index.  fp16 uses one v_mfma_f32_16x16x32_f16; fp32
 // issues eight v_mfma_f32_16x16x4_f32 (element e of every lane goes into the e-th op, so both
 // operands see the same permutation of the 32-element slice).  The 16x16 fp32 result holds, in
 // lane l, column (l % 16) and rows 4*(l/16) .. +4.
 // ---------------------------------------------------------------------------------------------
 template <typename T> struct Frag;
-template <> struct Frag<bf16_t> { bf16x8 v; };
+template <> struct Frag<half_t> { half8 v; };
 template <> struct Frag<float> { float v[8]; };
 
-__device__ __forceinline__ Frag<bf16_t> load_frag(const bf16_t *p) {
-  Frag<bf16_t> f;
-  f.v = *reinterpret_cast<const bf16x8 *>(p);
+__device__ __forceinline__ Frag<half_t> load_frag(const half_t *p) {
+  Frag<half_t> f;
+  f.v = *reinterpret_cast<const half8 *>(p);
   return f;
 }
 __device__ __forceinline__ Frag<float> load_frag(const float *p) {
@@ -42,7 +56,7 @@ __device__ __forceinline__ Frag<float> load_frag(const float *p) {
 // Operand-order ("tiled") weight storage.  A matrix [N][K] is cut into blocks of 16 rows x 32
 // contraction elements, stored group-major: block (n/16, k/32) starts at element
 // ((n/16) * (K/32) + k/32) * 512.  Inside a bf16 block lane l = ((k%32)/8)*16 + n%16 owns elements
-// l*8 .. l*8+8 (its fragment); an fp32 block is two 1 KB halves, half h holding elements 4h .. 4h+4
+// l*8 .. l*8+8 (its fragment; "bf16" = 2-byte elements, fp16 inside the library); an fp32 block is two 1 KB halves, half h holding elements 4h .. 4h+4
 // of every lane's fragment at l*4.  A wave's load instruction therefore reads 1 KB contiguously.
 __host__ __device__ __forceinline__ size_t tiled_offset(int n, int k, int K, int elem_size) {
   const size_t block = ((size_t)(n / 16) * (K / 32) + k / 32) * 512;
@@ -53,7 +67,7 @@ template <typename T>
 __device__ __forceinline__ const T *tiled_block(const T *w, int group16, int n_steps, int lane) {
   return w + (size_t)group16 * n_steps * 512 + lane * (sizeof(T) == 2 ? 8 : 4);
 }
-__device__ __forceinline__ Frag<bf16_t> load_frag_tiled(const bf16_t *p) { return load_frag(p); }
+__device__ __forceinline__ Frag<half_t> load_frag_tiled(const half_t *p) { return load_frag(p); }
 __device__ __forceinline__ Frag<float> load_frag_tiled(const float *p) {
   Frag<float> f;
   const float4 a = *reinterpret_cast<const float4 *>(p);
@@ -66,9 +80,9 @@ __device__ __forceinline__ Frag<float> load_frag_tiled(const float *p) {
 // a non-temporal load, so the stream does not push the activations, which every workgroup re-reads,
 // out of the L2 (measured on MI355X at the 7B shapes: gate/up 45.0 -> 42.2 us, q/k/v 24.2 -> 22.8,
 // down 25.3 -> 23.4, unembedding 53 -> 49 at 60 block rows, and the same 2-3 us with one row).
-__device__ __forceinline__ Frag<bf16_t> load_frag_stream(const bf16_t *p) {
-  Frag<bf16_t> f;
-  f.v = __builtin_nontemporal_load(reinterpret_cast<const bf16x8 *>(p));
+__device__ __forceinline__ Frag<half_t> load_frag_stream(const half_t *p) {
+  Frag<half_t> f;
+  f.v = __builtin_nontemporal_load(reinterpret_cast<const half8 *>(p));
   return f;
 }
 __device__ __forceinline__ Frag<float> load_frag_stream(const float *p) {
@@ -99,7 +113,7 @@ __host__ __device__ __forceinline__ size_t v_offset(int pos, int dim, int hd, in
 // contiguous region spread over every L2 channel (row-major rows lie a multiple of the channel
 // interleave apart, which made all workgroups of a die hit the same few channels at once).
 template <typename T> struct KChunk;
-template <> struct KChunk<bf16_t> { static constexpr int value = 256; };
+template <> struct KChunk<half_t> { static constexpr int value = 256; };
 template <> struct KChunk<float> { static constexpr int value = 128; };
 template <typename T>
 __host__ __device__ __forceinline__ size_t act_offset(int m, int k, int Mcap) {
@@ -107,15 +121,15 @@ __host__ __device__ __forceinline__ size_t act_offset(int m, int k, int Mcap) {
   return ((size_t)(k / KC) * Mcap + m) * KC + k % KC;
 }
 inline size_t act_elems(int dtype, int Mcap, int K) {
-  const int kc = dtype == 1 ? KChunk<bf16_t>::value : KChunk<float>::value;
+  const int kc = dtype == 1 ? KChunk<half_t>::value : KChunk<float>::value;
   return (size_t)((K + kc - 1) / kc) * Mcap * kc;
 }
 
 template <typename T> __device__ __forceinline__ Frag<T> zero_frag();
-template <> __device__ __forceinline__ Frag<bf16_t> zero_frag<bf16_t>() {
-  Frag<bf16_t> f;
+template <> __device__ __forceinline__ Frag<half_t> zero_frag<half_t>() {
+  Frag<half_t> f;
 #pragma unroll
-  for (int e = 0; e < 8; ++e) f.v[e] = (bf16_t)0.0f;
+  for (int e = 0; e < 8; ++e) f.v[e] = (half_t)0.0f;
   return f;
 }
 template <> __device__ __forceinline__ Frag<float> zero_frag<float>() {
@@ -124,9 +138,11 @@ template <> __device__ __forceinline__ Frag<float> zero_frag<float>() {
   for (int e = 0; e < 8; ++e) f.v[e] = 0.0f;
   return f;
 }
-__device__ __forceinline__ void pack_frag(Frag<bf16_t> &f, const float *p) {
+// fp32 -> fp16, round to nearest even; magnitudes beyond the fp16 range saturate instead of becoming infinite
+__device__ __forceinline__ half_t to_half(float x) { return (half_t)fminf(fmaxf(x, -kHalfMax), kHalfMax); }
+__device__ __forceinline__ void pack_frag(Frag<half_t> &f, const float *p) {
 #pragma unroll
-  for (int e = 0; e < 8; ++e) f.v[e] = (bf16_t)p[e];     // round to nearest even
+  for (int e = 0; e < 8; ++e) f.v[e] = to_half(p[e]);
 }
 __device__ __forceinline__ void pack_frag(Frag<float> &f, const float *p) {
 #pragma unroll
@@ -134,8 +150,8 @@ __device__ __forceinline__ void pack_frag(Frag<float> &f, const float *p) {
 }
 
 // acc[i][j] += sum_k a[i][k] * b[k][j]: a's lane index is the result row, b's the result column.
-__device__ __forceinline__ void mma(f32x4 &acc, const Frag<bf16_t> &a, const Frag<bf16_t> &b) {
-  acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, acc, 0, 0, 0);
+__device__ __forceinline__ void mma(f32x4 &acc, const Frag<half_t> &a, const Frag<half_t> &b) {
+  acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a.v, b.v, acc, 0, 0, 0);
 }
 __device__ __forceinline__ void mma(f32x4 &acc, const Frag<float> &a, const Frag<float> &b) {
 #pragma unroll
@@ -144,16 +160,17 @@ __device__ __forceinline__ void mma(f32x4 &acc, const Frag<float> &a, const Frag
 
 __device__ __forceinline__ float to_f32(float x) { return x; }
 __device__ __forceinline__ float to_f32(bf16_t x) { return (float)x; }
+__device__ __forceinline__ float to_f32(half_t x) { return (float)x; }
 template <typename T> __device__ __forceinline__ T from_f32(float x);
 template <> __device__ __forceinline__ float from_f32<float>(float x) { return x; }
-template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float x) { return (bf16_t)x; }
+template <> __device__ __forceinline__ half_t from_f32<half_t>(float x) { return to_half(x); }
 
-// four consecutive elements in one store (8 bytes of bf16 or 16 bytes of fp32); dst is so aligned
+// four consecutive elements in one store (8 bytes of fp16 or 16 bytes of fp32); dst is so aligned
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ void store4(bf16_t *dst, float a, float b, float c, float d) {
-  bf16x4 v;
-  v[0] = (bf16_t)a; v[1] = (bf16_t)b; v[2] = (bf16_t)c; v[3] = (bf16_t)d;
-  *reinterpret_cast<bf16x4 *>(dst) = v;
+__device__ __forceinline__ void store4(half_t *dst, float a, float b, float c, float d) {
+  half4 v;
+  v[0] = to_half(a); v[1] = to_half(b); v[2] = to_half(c); v[3] = to_half(d);
+  *reinterpret_cast<half4 *>(dst) = v;
 }
 __device__ __forceinline__ void store4(float *dst, float a, float b, float c, float d) {
   *reinterpret_cast<float4 *>(dst) = float4{a, b, c, d};
@@ -188,12 +205,12 @@ __device__ __forceinline__ float other_half(float x) {
   return __uint_as_float((threadIdx.x & 32) ? b[0] : b[1]);
 }
 
-// x * sigmoid(x).  The bf16 configuration rounds the product to 8 mantissa bits anyway, so it takes
+// x * sigmoid(x).  The 16-bit configuration rounds the product to 11 mantissa bits anyway, so it takes
 // the hardware's base-2 exponential and reciprocal (about 1 ulp of fp32 each) in place of expf and
 // an IEEE division, which cost ten times the instructions; overflow of the exponential gives x * 0.
 template <typename T> __device__ __forceinline__ float silu(float x);
 template <> __device__ __forceinline__ float silu<float>(float x) { return x / (1.0f + expf(-x)); }
-template <> __device__ __forceinline__ float silu<bf16_t>(float x) {
+template <> __device__ __forceinline__ float silu<half_t>(float x) {
   return x * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * x));
 }
 
@@ -211,6 +228,7 @@ struct GemmArgs {
   const float *row_ss;
   int ss_segs;
   float ss_eps;
+  float out_scale;        // every result is multiplied by this: 1 / (scale of the stored weights * scale of X); 1 for fp32 models
   int n_groups;           // residual, unembedding: pairs of 16-row fragments; q/k/v, gate/up: fragments (filled by the launcher)
   // EPI_RESIDUAL: split ks of KS stores its fp32 partial at hpart[ks][m][n]; the next RMSNorm adds them
   float *hpart;           // [KS][Mcap][N]
@@ -257,7 +275,11 @@ void launch_embed(int dtype, const void *tok_emb, const int32_t *hist, const int
                   float *h, int d, int M, int C, int w, int hist_base, int from_hist, hipStream_t s);
 // h[m] += sum of n_part partials (hpart[s][m], stride part_stride floats between splits), then
 // xn[m] = rmsnorm(h[m]) * gain, written chunk-major
-void launch_pack_rows(int dtype, const void *src, void *dst, int d, int M, int Mcap, hipStream_t s, const float *centre = nullptr);
+// dst = (src - centre) * scale in the internal element type (src: the user's storage type)
+void launch_pack_rows(int dtype, const void *src, void *dst, int d, int M, int Mcap, hipStream_t s, float scale,
+                      const float *centre = nullptr);
+// *out_bits = max(*out_bits, bit pattern of max |src[i]|) (fp32 bits; non-negative floats order like unsigned integers)
+void launch_absmax(int dtype, const void *src, size_t n, unsigned *out_bits, hipStream_t s);
 void launch_column_mean(int dtype, const void *src, int N, int d, float *mean, hipStream_t s);
 void launch_neg_row_sumsq(const float *rows, int M, int V, float *out, hipStream_t s);
 void launch_rmsnorm(int dtype, float *h, const float *hpart, int n_part, size_t part_stride, const void *gain, void *xn,
@@ -273,8 +295,10 @@ struct DraftArgs {
   int gtab_slots;         // a power of two >= 2 * max_seq
   int32_t *ctx_rows;      // [max_k][max_w]
   int32_t *n_ctx;         // [1]
-  const void *tok_emb;    // row-major [vocab][d]
-  const void *unemb_t;    // operand order
+  const void *tok_emb;    // row-major [vocab][d], the user's storage type
+  float emb_scale;        // the embedding row is multiplied by this before it is rounded to the internal type
+  const void *unemb_t;    // operand order, internal type, stored values times unemb_scale
+  float unemb_scale;
   int d, vocab;
   float *z;               // [vocab]
   float *cand_val;        // [256][32] per-workgroup top-k candidates of the bigram sweep
@@ -297,8 +321,9 @@ void launch_noop(hipStream_t s);
 // row_map: 0 = row n goes to row0 + n; 1 = rotary pairing inside blocks of 2*half rows (row i < half of a block goes
 // to 16*(i/8) + i%8, row half + i to 16*(i/8) + 8 + i%8); 2 / 3 = first / second member of interleaved 8-row halves
 // (row n goes to 16*(n/8) + n%8, plus 8 for the second member)
-void launch_tile_weights(int dtype, const void *src, void *dst, int N, int K, int row0, hipStream_t s, int row_map = 0,
-                         int half = 0);
+// values are multiplied by `scale` (a power of two) on the way
+void launch_tile_weights(int dtype, const void *src, void *dst, int N, int K, int row0, hipStream_t s, float scale,
+                         int row_map = 0, int half = 0);
 
 // result block layout (int32 words)
 enum { RES_WINNER = 0, RES_NACCEPT = 1, RES_NNEW = 2, RES_NCTX = 3, RES_WINSRC = 4, RES_NEWTOK = 8, RES_ACCEPT = 48 };

@@ -3,6 +3,8 @@
 // model would have predicted it) and the KV commit (Appendix D).  All integer work is exact.
 #include "ngg_internal.h"
 
+#include <algorithm>
+
 namespace ngg {
 
 // ---------------------------------------------------------------------------------------------
@@ -66,9 +68,10 @@ __device__ __forceinline__ float block_sum_256(float v, float *sh) {
 // Every thread owns J groups of 4 consecutive features of segment blockIdx.y (group index
 // tid + 256*j): all loads of the row and of its residual partials are issued before anything is
 // used, so the kernel costs one memory round trip instead of one per feature.
-template <typename T, int J>
+// U: storage type of the gain (the user's weights); T: internal element type of xn.
+template <typename U, typename T, int J>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(float *__restrict__ h, const float *__restrict__ hpart, int n_part,
-                                                      size_t part_stride, const T *__restrict__ gain, T *__restrict__ xn,
+                                                      size_t part_stride, const U *__restrict__ gain, T *__restrict__ xn,
                                                       int d, int Mcap, float *__restrict__ row_ss) {
   __shared__ float sh[4];
   const int m = blockIdx.x, segs = gridDim.y;
@@ -82,7 +85,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float *__restrict__ h, con
     gn[j] = float4{0.f, 0.f, 0.f, 0.f};
     if (i4 < d4) {
       v[j] = *reinterpret_cast<const float4 *>(h + (size_t)m * d + 4 * (c4 + i4));
-      const T *gp = gain + 4 * (c4 + i4);
+      const U *gp = gain + 4 * (c4 + i4);
       gn[j] = float4{to_f32(gp[0]), to_f32(gp[1]), to_f32(gp[2]), to_f32(gp[3])};
     }
   }
@@ -140,13 +143,14 @@ int rmsnorm_segments(int d) {
   return segs;
 }
 
-template <typename T>
+template <typename U>
 static void launch_rmsnorm_t(float *h, const float *hpart, int n_part, size_t part_stride, const void *gain, void *xn, int d,
                              int M, int Mcap, float *row_ss, hipStream_t s) {
+  typedef typename Internal<U>::type T;
   const int segs = rmsnorm_segments(d);
   const int j = (d / segs / 4 + 255) / 256;
 #define NGG_NORM(J)                                                                                                        \
-  hipLaunchKernelGGL((rmsnorm_kernel<T, J>), dim3(M, segs), dim3(256), 0, s, h, hpart, n_part, part_stride, (const T *)gain, \
+  hipLaunchKernelGGL((rmsnorm_kernel<U, T, J>), dim3(M, segs), dim3(256), 0, s, h, hpart, n_part, part_stride, (const U *)gain, \
                      (T *)xn, d, Mcap, row_ss)
   if (j <= 1) NGG_NORM(1);
   else if (j <= 2) NGG_NORM(2);
@@ -162,19 +166,42 @@ void launch_rmsnorm(int dtype, float *h, const float *hpart, int n_part, size_t 
   else launch_rmsnorm_t<float>(h, hpart, n_part, part_stride, gain, xn, d, M, Mcap, row_ss, s);
 }
 
-// rows of a row-major matrix -> chunk-major activation layout (used to feed embedding rows to the GEMM);
-// `centre` (fp32 [d], may be null) is subtracted first
-template <typename T>
-__global__ __launch_bounds__(256) void pack_rows_kernel(const T *src, T *dst, int d, int Mcap, const float *centre) {
+// rows of a row-major matrix of the user's weights -> chunk-major activation layout in the internal type
+// (used to feed embedding rows to the GEMM); `centre` (fp32 [d], may be null) is subtracted first, then the
+// value is multiplied by `scale` (a power of two that the GEMM's out_scale undoes)
+template <typename U, typename T>
+__global__ __launch_bounds__(256) void pack_rows_kernel(const U *src, T *dst, int d, int Mcap, const float *centre, float scale) {
   for (int i = threadIdx.x; i < d; i += 256) {
-    const T v = src[(size_t)blockIdx.x * d + i];
-    dst[act_offset<T>(blockIdx.x, i, Mcap)] = centre ? from_f32<T>(to_f32(v) - centre[i]) : v;
+    const float v = to_f32(src[(size_t)blockIdx.x * d + i]);
+    dst[act_offset<T>(blockIdx.x, i, Mcap)] = from_f32<T>((centre ? v - centre[i] : v) * scale);
   }
 }
 
-void launch_pack_rows(int dtype, const void *src, void *dst, int d, int M, int Mcap, hipStream_t s, const float *centre) {
-  if (dtype == 1) hipLaunchKernelGGL(pack_rows_kernel<bf16_t>, dim3(M), dim3(256), 0, s, (const bf16_t *)src, (bf16_t *)dst, d, Mcap, centre);
-  else hipLaunchKernelGGL(pack_rows_kernel<float>, dim3(M), dim3(256), 0, s, (const float *)src, (float *)dst, d, Mcap, centre);
+void launch_pack_rows(int dtype, const void *src, void *dst, int d, int M, int Mcap, hipStream_t s, float scale,
+                      const float *centre) {
+  if (dtype == 1)
+    hipLaunchKernelGGL((pack_rows_kernel<bf16_t, half_t>), dim3(M), dim3(256), 0, s, (const bf16_t *)src, (half_t *)dst, d, Mcap, centre, scale);
+  else
+    hipLaunchKernelGGL((pack_rows_kernel<float, float>), dim3(M), dim3(256), 0, s, (const float *)src, (float *)dst, d, Mcap, centre, scale);
+}
+
+// largest magnitude of a matrix, left as an fp32 bit pattern (magnitudes order like unsigned integers)
+template <typename U>
+__global__ __launch_bounds__(256) void absmax_kernel(const U *src, size_t n, unsigned *out_bits) {
+  __shared__ float sh[4];
+  float m = 0.0f;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) m = fmaxf(m, fabsf(to_f32(src[i])));
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) atomicMax(out_bits, __float_as_uint(fmaxf(fmaxf(sh[0], sh[1]), fmaxf(sh[2], sh[3]))));
+}
+
+void launch_absmax(int dtype, const void *src, size_t n, unsigned *out_bits, hipStream_t s) {
+  const unsigned blocks = (unsigned)std::min<size_t>(2048, (n + 255) / 256);
+  if (dtype == 1) hipLaunchKernelGGL(absmax_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, (const bf16_t *)src, n, out_bits);
+  else hipLaunchKernelGGL(absmax_kernel<float>, dim3(blocks), dim3(256), 0, s, (const float *)src, n, out_bits);
 }
 
 // mean[i] = (1/N) sum over rows of src[n][i]: one workgroup per 256 columns, rows summed in index
@@ -412,15 +439,15 @@ __device__ __forceinline__ bool ranks_before(float v, int i, float ov, int oi) {
   return v > ov || (v == ov && i < oi);
 }
 
-template <typename T>
-__global__ __launch_bounds__(256) void bigram_gemv_kernel(const T *tok_emb, const T *unemb_t, const int32_t *hist, int n,
+template <typename U, typename T>
+__global__ __launch_bounds__(256) void bigram_gemv_kernel(const U *tok_emb, const T *unemb_t, const int32_t *hist, int n,
                                                           int d, int vocab, int ksel, float *z, float *cand_val,
-                                                          int *cand_idx) {
+                                                          int *cand_idx, float emb_scale, float out_scale) {
   extern __shared__ __attribute__((aligned(16))) unsigned char gemv_smem[];
-  T *es = reinterpret_cast<T *>(gemv_smem);                  // [d] embedding of x_last
+  T *es = reinterpret_cast<T *>(gemv_smem);                  // [d] embedding of x_last (times emb_scale, internal type)
   float *zs = reinterpret_cast<float *>(gemv_smem + (size_t)d * sizeof(T));   // this block's scores
   const int x = hist[n - 1];
-  for (int i = threadIdx.x; i < d; i += 256) es[i] = tok_emb[(size_t)x * d + i];
+  for (int i = threadIdx.x; i < d; i += 256) es[i] = from_f32<T>(to_f32(tok_emb[(size_t)x * d + i]) * emb_scale);
   __syncthreads();
   const int lane = threadIdx.x & 63, li = lane & 15, g = lane >> 4;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -451,8 +478,8 @@ __global__ __launch_bounds__(256) void bigram_gemv_kernel(const T *tok_emb, cons
           if (li == 0) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-              z[grp * 16 + 4 * g + r] = acc[r];
-              zs[(grp - g0) * 16 + 4 * g + r] = acc[r];
+              z[grp * 16 + 4 * g + r] = acc[r] * out_scale;
+              zs[(grp - g0) * 16 + 4 * g + r] = acc[r] * out_scale;
             }
           }
           acc = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -510,29 +537,39 @@ __host__ __device__ inline int tile_dest_row(int n, int row_map, int half) {
   return n;
 }
 
-template <typename T>
-__global__ __launch_bounds__(256) void tile_weights_kernel(const T *src, T *dst, int N, int K, int row0, int row_map, int half) {
+template <typename U, typename T>
+__global__ __launch_bounds__(256) void tile_weights_kernel(const U *src, T *dst, int N, int K, int row0, int row_map, int half,
+                                                           float scale) {
   const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
   const int pieces = K / 8;
   if (idx >= (size_t)N * pieces) return;
   const int n = (int)(idx / pieces), k = (int)(idx % pieces) * 8;
-  const T *p = src + (size_t)n * K + k;
+  const U *p = src + (size_t)n * K + k;
   T *q = dst + tiled_offset(row0 + tile_dest_row(n, row_map, half), k, K, (int)sizeof(T));
   if constexpr (sizeof(T) == 2) {
-    *reinterpret_cast<u32x4 *>(q) = *reinterpret_cast<const u32x4 *>(p);
+    // stored bf16 value times a power of two, rounded to fp16: exact unless it falls more than 2^31 below the matrix maximum
+    const u32x4 raw = *reinterpret_cast<const u32x4 *>(p);
+    const bf16_t *e = reinterpret_cast<const bf16_t *>(&raw);
+    half8 o;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] = to_half(to_f32(e[i]) * scale);
+    *reinterpret_cast<half8 *>(q) = o;
   } else {
     *reinterpret_cast<u32x4 *>(q) = *reinterpret_cast<const u32x4 *>(p);
     *reinterpret_cast<u32x4 *>(q + 256) = *reinterpret_cast<const u32x4 *>(p + 4);
   }
 }
 
-void launch_tile_weights(int dtype, const void *src, void *dst, int N, int K, int row0, hipStream_t s, int row_map, int half) {
+void launch_tile_weights(int dtype, const void *src, void *dst, int N, int K, int row0, hipStream_t s, float scale, int row_map,
+                         int half) {
   const size_t total = (size_t)N * (K / 8);
   const unsigned blocks = (unsigned)((total + 255) / 256);
   if (dtype == 1)
-    hipLaunchKernelGGL(tile_weights_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, (const bf16_t *)src, (bf16_t *)dst, N, K, row0, row_map, half);
+    hipLaunchKernelGGL((tile_weights_kernel<bf16_t, half_t>), dim3(blocks), dim3(256), 0, s, (const bf16_t *)src, (half_t *)dst, N, K,
+                       row0, row_map, half, scale);
   else
-    hipLaunchKernelGGL(tile_weights_kernel<float>, dim3(blocks), dim3(256), 0, s, (const float *)src, (float *)dst, N, K, row0, row_map, half);
+    hipLaunchKernelGGL((tile_weights_kernel<float, float>), dim3(blocks), dim3(256), 0, s, (const float *)src, (float *)dst, N, K,
+                       row0, row_map, half, scale);
 }
 
 // Top-(k - n_ctx) of z by (score desc, id asc), chained extension through next1, and assembly of
@@ -664,12 +701,15 @@ void launch_build_drafts(int dtype, const DraftArgs &a, hipStream_t s) {
   if (a.w >= 1) {
     const int n_groups = a.vocab / 16, gpb = (n_groups + kGemvBlocks - 1) / kGemvBlocks;
     const size_t lds = (size_t)a.d * (dtype == 1 ? 2 : 4) + (size_t)gpb * 16 * sizeof(float);
+    const float out_scale = 1.0f / (a.emb_scale * a.unemb_scale);       // powers of two: exact
     if (dtype == 1)
-      hipLaunchKernelGGL(bigram_gemv_kernel<bf16_t>, dim3(kGemvBlocks), dim3(256), lds, s, (const bf16_t *)a.tok_emb,
-                         (const bf16_t *)a.unemb_t, a.hist, a.n, a.d, a.vocab, a.k, a.z, a.cand_val, a.cand_idx);
+      hipLaunchKernelGGL((bigram_gemv_kernel<bf16_t, half_t>), dim3(kGemvBlocks), dim3(256), lds, s, (const bf16_t *)a.tok_emb,
+                         (const half_t *)a.unemb_t, a.hist, a.n, a.d, a.vocab, a.k, a.z, a.cand_val, a.cand_idx,
+                         a.emb_scale, out_scale);
     else
-      hipLaunchKernelGGL(bigram_gemv_kernel<float>, dim3(kGemvBlocks), dim3(256), lds, s, (const float *)a.tok_emb,
-                         (const float *)a.unemb_t, a.hist, a.n, a.d, a.vocab, a.k, a.z, a.cand_val, a.cand_idx);
+      hipLaunchKernelGGL((bigram_gemv_kernel<float, float>), dim3(kGemvBlocks), dim3(256), lds, s, (const float *)a.tok_emb,
+                         (const float *)a.unemb_t, a.hist, a.n, a.d, a.vocab, a.k, a.z, a.cand_val, a.cand_idx,
+                         a.emb_scale, out_scale);
   }
   hipLaunchKernelGGL(ctx_match_kernel, dim3(1), dim3(1024), 0, s, a);
   hipLaunchKernelGGL(topk_assemble_kernel, dim3(1), dim3(1024), 0, s, a);
@@ -850,8 +890,8 @@ void launch_commit(int dtype, void *kcache, void *vcache, const void *kscr, cons
                    int Spad, int Mcap, int C, int P, const int32_t *res, int fixed_row, int fixed_n, int max_new,
                    int32_t *hist, hipStream_t s) {
   if (dtype == 1)
-    hipLaunchKernelGGL(commit_kernel<bf16_t>, dim3(Hkv, L), dim3(256), 0, s, (bf16_t *)kcache, (bf16_t *)vcache,
-                       (const bf16_t *)kscr, (const bf16_t *)vscr, Hkv, hd, Spad, Mcap, C, P, res, fixed_row, fixed_n,
+    hipLaunchKernelGGL(commit_kernel<half_t>, dim3(Hkv, L), dim3(256), 0, s, (half_t *)kcache, (half_t *)vcache,
+                       (const half_t *)kscr, (const half_t *)vscr, Hkv, hd, Spad, Mcap, C, P, res, fixed_row, fixed_n,
                        max_new, hist);
   else
     hipLaunchKernelGGL(commit_kernel<float>, dim3(Hkv, L), dim3(256), 0, s, (float *)kcache, (float *)vcache,

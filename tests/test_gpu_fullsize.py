@@ -139,6 +139,26 @@ def test_committed_cache_equals_fresh_prefill_and_plain_greedy_agrees(full):
         ctx2.close()
 
 
+@pytest.mark.parametrize("depth", [4, 8, 16, 32])
+def test_logits_against_the_oracle_at_depth(full, depth):
+    """The first `depth` layers of the full-width model against the oracle, logits and all, on a short prompt
+    (k=10, w=5): the bf16 path's error must stay inside the 2e-2 bound as the layers stack up.  The oracle
+    keeps the matrices as stored and widens one layer at a time."""
+    run = dict(full.run, prompt_len=96, n_gen=12)
+    desc = si.reduced_layers(full.m, depth)
+    host = lambda t: t.float().cpu().numpy()
+    w = dict(tok_emb=full.bigram.tok_emb, unemb=full.bigram.unemb, final_norm=host(full.dev_w["final_norm"]),
+             layers=[{k: host(v) for k, v in lw.items()} for lw in full.dev_w["layers"][:depth]])
+    model = oracle.Model(desc, w, widen_at_use=True)
+    dev = dict(full.dev_w, layers=full.dev_w["layers"][:depth])
+    ctx = ngg.Context(desc, dev, max_seq=run["prompt_len"] + 64, max_k=run["k"], max_w=run["w"])
+    from lockstep import run as lockstep_run
+    rep = lockstep_run(ctx, model, full.prompt[:96], 12, run, TOL["bf16"], max_steps=2, bigram=full.bigram)
+    ctx.close()
+    print(f"depth {depth}: {rep}")
+    assert rep.steps == 2 and rep.max_rel_logit_err <= 2e-2
+
+
 def test_zero_output_projections_accept_the_whole_chain_at_full_size(full):
     """W_o = W_down = 0 on all 32 layers (done last: it changes the shared weights): the logits reduce to
     U.RMSNorm(E[x]), so greedy decoding follows the bigram's top-1 chain, which the oracle computes at the full
@@ -180,23 +200,3 @@ def test_zero_output_projections_accept_the_whole_chain_at_full_size(full):
             assert st["winner_src"][0] + st["winner_src"][1] == n_calls
     finally:
         ctx.close()
-
-
-@pytest.mark.parametrize("depth", [4, 8])
-def test_logits_against_the_oracle_at_depth(full, depth):
-    """The first `depth` layers of the full-width model against the oracle, logits and all, on a short prompt
-    (k=10, w=5): the bf16 path's error must stay inside the 2e-2 bound as the layers stack up.  The oracle
-    keeps the matrices as stored and widens one layer at a time."""
-    run = dict(full.run, prompt_len=96, n_gen=12)
-    desc = si.reduced_layers(full.m, depth)
-    host = lambda t: t.float().cpu().numpy()
-    w = dict(tok_emb=full.bigram.tok_emb, unemb=full.bigram.unemb, final_norm=host(full.dev_w["final_norm"]),
-             layers=[{k: host(v) for k, v in lw.items()} for lw in full.dev_w["layers"][:depth]])
-    model = oracle.Model(desc, w, widen_at_use=True)
-    dev = dict(full.dev_w, layers=full.dev_w["layers"][:depth])
-    ctx = ngg.Context(desc, dev, max_seq=run["prompt_len"] + 64, max_k=run["k"], max_w=run["w"])
-    from lockstep import run as lockstep_run
-    rep = lockstep_run(ctx, model, full.prompt[:96], 12, run, TOL["bf16"], max_steps=2, bigram=full.bigram)
-    ctx.close()
-    print(f"depth {depth}: {rep}")
-    assert rep.steps == 2 and rep.max_rel_logit_err <= 2e-2
