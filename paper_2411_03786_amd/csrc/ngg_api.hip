@@ -24,7 +24,7 @@ static __device__ __align__(256) int32_t scratch[kStaticInts];
 
 namespace {
 
-constexpr int kPrefillChunk = 128;   // prompt tokens per forward pass of ngg_prefill: the largest GEMM row tile
+constexpr int kPrefillChunk = 256;   // prompt tokens per forward pass of ngg_prefill: one pass of the wide GEMM kernel (fp32: two 128-row tiles)
 thread_local std::string g_create_error = "";
 
 struct ProfSpan { int cls; hipEvent_t e0, e1; };

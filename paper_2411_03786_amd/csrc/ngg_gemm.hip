@@ -20,6 +20,97 @@
 
 namespace ngg {
 
+// ---------------------------------------------------------------------------------------------
+// Epilogues, shared by the skinny and the wide kernel.  `sum` is one complete 16x16 accumulator
+// fragment: this lane holds column (block row) m and fragment rows 4g .. 4g+3.
+// ---------------------------------------------------------------------------------------------
+
+// q/k/v and gate/up: the fragment's rows 0..7 are the first members of 8 output pairs, rows 8..15 the
+// second members (rotary pairs (i, i + hd/2) of one head; gate and up of 8 FFN features).  rs: the row's
+// 1 / rms times the operand scales.  The caller has checked frag < n_groups; lanes g >= 2 only lend values.
+template <typename T, int EPI>
+__device__ __forceinline__ void epi_paired(const GemmArgs &a, int frag, int m, int M, int g, float rs, const f32x4 &sum) {
+  float v[4], x2[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) { v[r] = sum[r] * rs; x2[r] = other_half(v[r]); }
+  if (m < M && g < 2) {
+    if constexpr (EPI == EPI_GATEUP) {
+      float o[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) o[r] = silu<T>(v[r]) * x2[r];
+      store4((T *)a.act + act_offset<T>(m, frag * 8 + 4 * g, a.Mcap), o[0], o[1], o[2], o[3]);   // 4 features, one chunk
+    } else {
+      const int half = a.hd / 2, fph = a.hd / 16;    // fragments per head
+      const int hh = frag / fph, sub = frag - hh * fph;                 // head over [q heads | k heads | v heads]
+      const int kind = hh < a.H ? 0 : (hh < a.H + a.Hkv ? 1 : 2);
+      const int head = kind == 0 ? hh : (kind == 1 ? hh - a.H : hh - a.H - a.Hkv);
+      const int i0 = sub * 8 + 4 * g;                // dims i0 .. i0+3 and their partners i0 + half ..
+      if (kind < 2) {                                // rotary embedding on q and k
+        const int pos = a.P + (m % a.C);
+        const float *cs = a.rope_cos + (size_t)pos * half + i0;
+        const float *sn = a.rope_sin + (size_t)pos * half + i0;
+        float lo[4], hi[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          lo[r] = v[r] * cs[r] - x2[r] * sn[r];
+          hi[r] = x2[r] * cs[r] + v[r] * sn[r];
+        }
+        if (kind == 0) {
+          T *dst = (T *)a.q + ((size_t)head * a.Mcap + m) * a.hd + i0;
+          store4(dst, lo[0], lo[1], lo[2], lo[3]);
+          store4(dst + half, hi[0], hi[1], hi[2], hi[3]);
+        } else {                                     // keys: tiles of 32 block positions in operand order
+          T *kh = (T *)a.kscr + (size_t)head * a.Mcap * a.hd;
+          store4(kh + k_offset(m, i0, a.hd, (int)sizeof(T)), lo[0], lo[1], lo[2], lo[3]);
+          store4(kh + k_offset(m, i0 + half, a.hd, (int)sizeof(T)), hi[0], hi[1], hi[2], hi[3]);
+        }
+      } else {                                       // values: the transposed tiles
+        T *vh = (T *)a.vscr + (size_t)head * a.Mcap * a.hd;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          vh[v_offset(m, i0 + r, a.hd, (int)sizeof(T))] = from_f32<T>(v[r]);
+          vh[v_offset(m, i0 + half + r, a.hd, (int)sizeof(T))] = from_f32<T>(x2[r]);
+        }
+      }
+    }
+  }
+}
+
+// residual: split ks stores its fp32 partial of output features n0 + 4g .. +4 of block row m
+__device__ __forceinline__ void epi_residual(const GemmArgs &a, int ks, int m, int n0, int g, const f32x4 &sum) {
+  float *dst = a.hpart + ((size_t)ks * a.Mcap + m) * a.N;
+  *reinterpret_cast<float4 *>(dst + n0 + 4 * g) =
+      float4{sum[0] * a.out_scale, sum[1] * a.out_scale, sum[2] * a.out_scale, sum[3] * a.out_scale};
+}
+
+// unembedding: optional logits, and the best (value, id) of block row m over the FN fragments of `group`
+// (vocabulary rows nbase[f] ..): ascending ids, so the first maximum stays
+template <int FN>
+__device__ __forceinline__ void epi_unembed(const GemmArgs &a, int group, int m, bool live, int g, float rs,
+                                            const int (&nbase)[FN], const f32x4 (&sum)[FN]) {
+  float bv = kNegBig;
+  int bi = 0x7fffffff;
+#pragma unroll
+  for (int f = 0; f < FN; ++f)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const float v = sum[f][r] * rs;
+      const int n = nbase[f] + 4 * g + r;
+      if (a.logits && live) a.logits[(size_t)m * a.N + n] = v;
+      if (v > bv) { bv = v; bi = n; }
+    }
+#pragma unroll
+  for (int off = 16; off < 64; off <<= 1) {
+    const float ov = __shfl_xor(bv, off);
+    const int oi = __shfl_xor(bi, off);
+    if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+  }
+  if (live && g == 0) {
+    a.pmax_val[(size_t)group * a.Mcap + m] = bv;
+    a.pmax_idx[(size_t)group * a.Mcap + m] = bi;
+  }
+}
+
 template <typename T, int EPI, int FM, int WN, int WK, int RING, int FN>
 __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArgs a) {
   constexpr int XD = FM > 4 ? 1 : 2;         // X register stages (chunks fetched ahead); one when the tile is 128 rows
@@ -211,55 +302,7 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
         f32x4 sum = red[(size_t)idx * 64 + lane];
 #pragma unroll
         for (int o = 1; o < WK; ++o) sum += red[((size_t)o * items + idx) * 64 + lane];
-        float v[4];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) v[r] = sum[r];
-        // lanes g < 2 hold rows 4g + r of the fragment (first members of the pairs), lanes g + 2 the
-        // second members of the same pairs
-        float x2[4];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) { v[r] *= rs; x2[r] = other_half(v[r]); }
-        if (m < M && g < 2 && frag < n_groups) {
-          if constexpr (EPI == EPI_GATEUP) {
-            float o[4];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) o[r] = silu<T>(v[r]) * x2[r];
-            store4((T *)a.act + act_offset<T>(m, frag * 8 + 4 * g, a.Mcap), o[0], o[1], o[2], o[3]);   // 4 features, one chunk
-          } else {
-            const int half = a.hd / 2, fph = a.hd / 16;    // fragments per head
-            const int hh = frag / fph, sub = frag - hh * fph;                 // head over [q heads | k heads | v heads]
-            const int kind = hh < a.H ? 0 : (hh < a.H + a.Hkv ? 1 : 2);
-            const int head = kind == 0 ? hh : (kind == 1 ? hh - a.H : hh - a.H - a.Hkv);
-            const int i0 = sub * 8 + 4 * g;                // dims i0 .. i0+3 and their partners i0 + half ..
-            if (kind < 2) {                                // rotary embedding on q and k
-              const int pos = a.P + (m % a.C);
-              const float *cs = a.rope_cos + (size_t)pos * half + i0;
-              const float *sn = a.rope_sin + (size_t)pos * half + i0;
-              float lo[4], hi[4];
-#pragma unroll
-              for (int r = 0; r < 4; ++r) {
-                lo[r] = v[r] * cs[r] - x2[r] * sn[r];
-                hi[r] = x2[r] * cs[r] + v[r] * sn[r];
-              }
-              if (kind == 0) {
-                T *dst = (T *)a.q + ((size_t)head * a.Mcap + m) * a.hd + i0;
-                store4(dst, lo[0], lo[1], lo[2], lo[3]);
-                store4(dst + half, hi[0], hi[1], hi[2], hi[3]);
-              } else {                                     // keys: tiles of 32 block positions in operand order
-                T *kh = (T *)a.kscr + (size_t)head * a.Mcap * a.hd;
-                store4(kh + k_offset(m, i0, a.hd, (int)sizeof(T)), lo[0], lo[1], lo[2], lo[3]);
-                store4(kh + k_offset(m, i0 + half, a.hd, (int)sizeof(T)), hi[0], hi[1], hi[2], hi[3]);
-              }
-            } else {                                       // values: the transposed tiles
-              T *vh = (T *)a.vscr + (size_t)head * a.Mcap * a.hd;
-#pragma unroll
-              for (int r = 0; r < 4; ++r) {
-                vh[v_offset(m, i0 + r, a.hd, (int)sizeof(T))] = from_f32<T>(v[r]);
-                vh[v_offset(m, i0 + half + r, a.hd, (int)sizeof(T))] = from_f32<T>(x2[r]);
-              }
-            }
-          }
-        }
+        if (frag < n_groups) epi_paired<T, EPI>(a, frag, m, M, g, rs, sum);   // (uniform per wave)
       }
       }
     }
@@ -300,40 +343,212 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
         const bool live = m < M;
         if constexpr (EPI == EPI_RESIDUAL) {
           if (live) {
-            float *dst = a.hpart + ((size_t)ks * a.Mcap + m) * a.N;
 #pragma unroll
-            for (int f = 0; f < FN; ++f)
-              *reinterpret_cast<float4 *>(dst + nbase[f] + 4 * g) =
-                  float4{acc[f][fm][0] * a.out_scale, acc[f][fm][1] * a.out_scale, acc[f][fm][2] * a.out_scale,
-                         acc[f][fm][3] * a.out_scale};
+            for (int f = 0; f < FN; ++f) epi_residual(a, ks, m, nbase[f], g, acc[f][fm]);
           }
-        } else {   // EPI_UNEMBED: optional logits, and this wave's best (value, id) per column
-          float bv = kNegBig;
-          int bi = 0x7fffffff;
-          const float rs = rs_lds[fm * 16 + li];
+        } else {   // EPI_UNEMBED
+          f32x4 sums[FN];
 #pragma unroll
-          for (int f = 0; f < FN; ++f)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              const float v = acc[f][fm][r] * rs;
-              const int n = nbase[f] + 4 * g + r;
-              if (a.logits && live) a.logits[(size_t)m * a.N + n] = v;
-              if (v > bv) { bv = v; bi = n; }                 // ascending n: the first maximum stays
-            }
-#pragma unroll
-          for (int off = 16; off < 64; off <<= 1) {
-            const float ov = __shfl_xor(bv, off);
-            const int oi = __shfl_xor(bi, off);
-            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
-          }
-          if (live && g == 0) {
-            a.pmax_val[(size_t)group * a.Mcap + m] = bv;
-            a.pmax_idx[(size_t)group * a.Mcap + m] = bi;
-          }
+          for (int f = 0; f < FN; ++f) sums[f] = acc[f][fm];
+          epi_unembed<FN>(a, group, m, live, g, rs_lds[fm * 16 + li], nbase, sums);
         }
       }
     }
     __syncthreads();                                       // LDS is reused by the next column block
+  }
+}
+
+
+// ---------------------------------------------------------------------------------------------
+// Wide blocks (more than 128 rows; 16-bit types): one pass over W for up to 16*FM = 288 block rows.
+// Section 3's cost model has the call leave the memory-bound regime as k*(w+1) grows; with 128-row
+// tiles the skinny kernel re-streamed all of W for every further 128 rows, which put that transition
+// far below the chip's ops-to-bytes ratio.  Here a workgroup's four waves own FN different 16-row
+// fragments of W each (8 fragments = 128 rows of W per workgroup) and keep accumulators for ALL row
+// blocks of the tile (FN * FM fragments per wave), so a W fragment is loaded once from HBM and meets
+// every block row.  X is staged through LDS in slices of 64 contraction elements (two MFMA steps), double
+// buffered, and every wave reads all of it (LDS reads and MFMA issue are about balanced at FN = 2).
+// W goes from global memory straight into registers, 4 steps ahead, as in the skinny kernel.  No hand-over
+// between waves: each wave finishes its own fragments.  gridDim.y splits the contraction (residual only).
+// ---------------------------------------------------------------------------------------------
+template <typename T, int EPI, int FM, int FN>
+__global__ __launch_bounds__(256) void gemm_wide_kernel(const GemmArgs a) {
+  static_assert(sizeof(T) == 2, "16-bit operands only");
+  constexpr bool PAIRED = EPI == EPI_QKV || EPI == EPI_GATEUP;
+  static_assert(PAIRED || FN == 2, "unembedding partials are indexed by pairs of fragments");
+  constexpr int KC = KChunk<T>::value;       // chunk of the activation layout (256)
+  constexpr int KW = 64;                     // contraction elements staged per slice: two steps
+  constexpr int SPS = KW / 32;               // steps per slice
+  constexpr int LDX = KW + 8;                // LDS row stride in elements (16 bytes of padding)
+  constexpr int ROWS = 16 * FM;
+  constexpr int PPR = KW / 8;                // 16-byte pieces per row
+  constexpr int PIECES = (ROWS * PPR + 255) / 256;
+  constexpr int RING = 4;                    // W steps in flight per wave (two slices)
+
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  T *xs = reinterpret_cast<T *>(smem);       // [2][ROWS][LDX]
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int li = lane & 15, g = lane >> 4;
+  const int K = a.K, M = a.M;
+  const int n_frags = a.n_groups;            // 16-row fragments of W (the launcher fills it)
+  const int n_steps = K / 32;
+  const int n_slices = (n_steps + SPS - 1) / SPS;
+  const int KS = gridDim.y, ks = blockIdx.y;
+  const int c0 = (int)(((long)n_slices * ks) / KS), c1 = (int)(((long)n_slices * (ks + 1)) / KS);
+
+  const T *wblk[FN];
+  int fragi[FN];
+  bool frag_live[FN];
+#pragma unroll
+  for (int f = 0; f < FN; ++f) {
+    int frag = (blockIdx.x * 4 + wave) * FN + f;
+    frag_live[f] = frag < n_frags;
+    if (!frag_live[f]) frag = n_frags - 1;   // repeats a fragment it does not store
+    fragi[f] = frag;
+    wblk[f] = tiled_block((const T *)a.W0, frag, n_steps, lane);
+  }
+
+  static_assert(kNormSegs == 4, "one float4 per row");
+  auto row_scale = [&](int m) {
+    float r = 1.0f;
+    if (a.row_ss) {
+      const f32x4 ss = *reinterpret_cast<const f32x4 *>(a.row_ss + (size_t)(m < a.Mcap ? m : a.Mcap - 1) * kNormSegs);
+      r = 1.0f / sqrtf((((ss[0] + ss[1]) + ss[2]) + ss[3]) / (float)K + a.ss_eps);
+    }
+    return r * a.out_scale;
+  };
+
+  for (int m0 = 0; m0 < M; m0 += ROWS) {
+    // X staging: piece p = tid + 256 i is row p / PPR, 16 bytes at column piece p % PPR of the slice; pieces
+    // past the tile repeat its last row, rows past the buffers' Mcap rows read row Mcap - 1 (never stored)
+    const T *xsrc[PIECES];
+    int xdst[PIECES];
+#pragma unroll
+    for (int i = 0; i < PIECES; ++i) {
+      const int p = tid + 256 * i;
+      const int row = min(p / PPR, ROWS - 1), col = p % PPR;
+      xsrc[i] = (const T *)a.X + (size_t)min(m0 + row, a.Mcap - 1) * KC + col * 8;
+      xdst[i] = row * LDX + col * 8;
+    }
+    u32x4 stage[2][PIECES];
+    auto stage_load = [&](u32x4 (&st)[PIECES], int c) {     // slice c of the matrix (clamped into it)
+      const int cl = min(c, n_slices - 1);
+      const int k0 = cl * KW;
+      const size_t off = (size_t)(k0 / KC) * a.Mcap * KC + k0 % KC;
+#pragma unroll
+      for (int i = 0; i < PIECES; ++i) st[i] = *reinterpret_cast<const u32x4 *>(xsrc[i] + off);
+    };
+    auto stage_store = [&](const u32x4 (&st)[PIECES], int buf) {
+#pragma unroll
+      for (int i = 0; i < PIECES; ++i) *reinterpret_cast<u32x4 *>(xs + (size_t)buf * ROWS * LDX + xdst[i]) = st[i];
+    };
+
+    f32x4 acc[FN][FM];
+#pragma unroll
+    for (int f = 0; f < FN; ++f)
+#pragma unroll
+      for (int fm = 0; fm < FM; ++fm) acc[f][fm] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    Frag<T> ring[RING][FN];
+    auto load_w = [&](Frag<T> (&slot)[FN], int t) {         // wave-step t >= 0 is global step c0 * SPS + t (clamped)
+      const int st = min(c0 * SPS + t, n_steps - 1);
+#pragma unroll
+      for (int f = 0; f < FN; ++f) slot[f] = load_frag_stream(wblk[f] + (size_t)st * 512);
+    };
+
+    // As in the skinny kernel the loop starts one unrolled group (two slices) early with the multiplications
+    // off, so that every trip enters with the same loads outstanding in the same order.
+    const int n_iter = (c1 - c0 + 1) / 2 * 2;
+    for (int ci = -2; ci < n_iter; ci += 2) {
+      const bool warm = ci < 0;
+#pragma unroll
+      for (int cc = 0; cc < 2; ++cc) {
+        const int sl = c0 + ci + cc;                         // slice of this half trip
+        if (!warm) stage_store(stage[cc], cc);
+        __syncthreads();
+        stage_load(stage[cc], max(sl + 2, c0));
+        const T *xb = xs + (size_t)cc * ROWS * LDX + li * LDX + g * 8;
+#pragma unroll
+        for (int i = 0; i < SPS; ++i) {
+          const int slot = cc * SPS + i;
+          if (!warm && sl < c1 && sl * SPS + i < n_steps) {   // uniform per workgroup
+#pragma unroll
+            for (int fm = 0; fm < FM; ++fm) {
+              const Frag<T> xf = load_frag(xb + fm * 16 * LDX + i * 32);
+#pragma unroll
+              for (int f = 0; f < FN; ++f) mma(acc[f][fm], ring[slot][f], xf);
+            }
+          }
+          load_w(ring[slot], max((ci + cc) * SPS + i + RING, 0));
+        }
+      }
+    }
+    __syncthreads();                                         // everyone is done with xs
+    float *rs_lds = reinterpret_cast<float *>(smem);         // [ROWS] 1 / rms (times the operand scales) of the tile's rows
+    for (int r = tid; r < ROWS; r += 256) rs_lds[r] = row_scale(m0 + r);
+    __syncthreads();
+
+#pragma unroll
+    for (int fm = 0; fm < FM; ++fm) {
+      const int m = m0 + fm * 16 + li;
+      const bool live = m < M;
+      if constexpr (PAIRED) {
+        const float rs = rs_lds[fm * 16 + li];
+#pragma unroll
+        for (int f = 0; f < FN; ++f)
+          if (frag_live[f]) epi_paired<T, EPI>(a, fragi[f], m, M, g, rs, acc[f][fm]);     // uniform per wave
+      } else if constexpr (EPI == EPI_RESIDUAL) {
+#pragma unroll
+        for (int f = 0; f < FN; ++f)
+          if (live && frag_live[f]) epi_residual(a, ks, m, fragi[f] * 16, g, acc[f][fm]);
+      } else {
+        if (frag_live[0]) {                                  // a pair of fragments is live or not as a whole (N % 32 == 0)
+          int nbase[FN];
+          f32x4 sums[FN];
+#pragma unroll
+          for (int f = 0; f < FN; ++f) { nbase[f] = fragi[f] * 16; sums[f] = acc[f][fm]; }
+          epi_unembed<FN>(a, fragi[0] / FN, m, live, g, rs_lds[fm * 16 + li], nbase, sums);
+        }
+      }
+    }
+    __syncthreads();                                         // LDS is reused by the next tile
+  }
+}
+
+template <typename T, int EPI, int FM>
+static void launch_wide_fm(const GemmArgs &a_in, int KS, hipStream_t s) {
+  constexpr int FN = 2;
+  GemmArgs a = a_in;
+  a.n_groups = a.N / 16 * ((EPI == EPI_GATEUP) ? 2 : 1);     // fragments: gate/up interleaves 2 * d_ffn rows
+  if (EPI == EPI_QKV) a.n_groups = (a.H + 2 * a.Hkv) * (a.hd / 16);
+  const size_t lds = (size_t)2 * 16 * FM * (64 + 8) * sizeof(T);
+  const int blocks = (a.n_groups + 4 * FN - 1) / (4 * FN);
+  if (lds > 64 * 1024) {
+    static const hipError_t opted = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_wide_kernel<T, EPI, FM, FN>),
+                                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    (void)opted;
+  }
+  hipLaunchKernelGGL((gemm_wide_kernel<T, EPI, FM, FN>), dim3(blocks, KS), dim3(256), lds, s, a);
+}
+
+// Row tiles of the wide kernel: as few passes as possible (288 rows at most each), then the smallest even
+// number of 16-row blocks that holds a pass's share of the rows.
+int gemm_wide_row_blocks(int M) {
+  const int passes = (M + 287) / 288;
+  const int rows = (M + passes - 1) / passes;
+  const int fm = (rows + 15) / 16;
+  return (fm + 1) / 2 * 2 < 10 ? 10 : (fm + 1) / 2 * 2;
+}
+
+template <typename T, int EPI>
+static void launch_wide(const GemmArgs &a, int KS, hipStream_t s) {
+  switch (gemm_wide_row_blocks(a.M)) {
+    case 10: launch_wide_fm<T, EPI, 10>(a, KS, s); break;
+    case 12: launch_wide_fm<T, EPI, 12>(a, KS, s); break;
+    case 14: launch_wide_fm<T, EPI, 14>(a, KS, s); break;
+    case 16: launch_wide_fm<T, EPI, 16>(a, KS, s); break;
+    default: launch_wide_fm<T, EPI, 18>(a, KS, s);
   }
 }
 
@@ -444,6 +659,13 @@ static bool residual_narrow(int M, int N, int K) { return M <= 16 || K <= N; }
 // Split of the contraction across workgroups for the residual GEMMs: about one workgroup per CU, as
 // long as each split keeps at least 2 chunks.
 int gemm_residual_splits(int dtype, int M, int N, int K) {
+  if (dtype == 1 && M > 128) {              // wide kernel: 128 rows of W per workgroup, slices of 64; at least 8 slices per split
+    const int blocks = (N / 16 + 7) / 8, n_slices = (K + 63) / 64;
+    int ks = (256 + blocks - 1) / blocks;
+    ks = ks > kMaxResidualSplits ? kMaxResidualSplits : ks;
+    while (ks > 1 && n_slices / ks < 8) --ks;
+    return ks < 1 ? 1 : ks;
+  }
   const int kc = dtype == 1 ? KChunk<half_t>::value : KChunk<float>::value;
   const int n_chunks = (K + kc - 1) / kc;
   const int blocks = residual_narrow(M, N, K) ? N / 32 : (N / 32 + 1) / 2;
@@ -460,6 +682,17 @@ int gemm_residual_splits(int dtype, int M, int N, int K) {
 template <typename T>
 static void launch_t(int epi, const GemmArgs &a_in, hipStream_t s) {
   GemmArgs a = a_in;
+  if constexpr (sizeof(T) == 2) {
+    if (a.M > 128) {
+      switch (epi) {
+        case EPI_QKV: launch_wide<T, EPI_QKV>(a, 1, s); break;
+        case EPI_GATEUP: launch_wide<T, EPI_GATEUP>(a, 1, s); break;
+        case EPI_RESIDUAL: launch_wide<T, EPI_RESIDUAL>(a, a.KS, s); break;
+        default: launch_wide<T, EPI_UNEMBED>(a, 1, s);
+      }
+      return;
+    }
+  }
   a.n_groups = gemm_groups(epi, a);
   const bool wide = a.n_groups >= 4 * 200;
   switch (epi) {

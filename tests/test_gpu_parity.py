@@ -528,11 +528,12 @@ def test_cfg2_small_bf16_lockstep():
     assert rep.tolerated_argmax <= 0.1 * positions
 
 
-@pytest.mark.parametrize("k,w", [(16, 6), (32, 8), (13, 4), (12, 7)])
+@pytest.mark.parametrize("k,w", [(16, 6), (32, 8), (13, 4), (12, 7), (13, 9), (20, 7), (32, 7), (20, 14), (32, 32)])
 def test_bf16_blocks_of_more_than_64_rows(k, w):
-    """Blocks of 112, 288, 65 and 96 rows on the small bf16 widths (3 layers): GEMM row tiles of 7, 8, 5
-    and 6 column blocks, the attention workgroups with two query groups per wave and, at 288 rows,
-    several passes over the weights."""
+    """Blocks of 112, 288, 65 and 96 rows on the small 16-bit widths (3 layers): GEMM row tiles of 7, 8, 5
+    and 6 column blocks and the attention workgroups with two query groups per wave; then the wide GEMM
+    kernel (more than 128 rows in one pass over the weights): 130, 160, 256 and 288 rows (tiles of 10, 10, 16
+    and 18 row blocks), 300 rows (two passes of 160) and 1056 rows (four passes of 272)."""
     desc = si.reduced_layers(si.MODELS["small"], 3)
     run = dict(si.RUNS["cfg2"], prompt_len=333, k=k, w=w, k_ctx_max=k, q_min=1, q_max=3, n_gen=30)
     w_, prompt, model, ctx = _setup(desc, run)
@@ -540,6 +541,19 @@ def test_bf16_blocks_of_more_than_64_rows(k, w):
     ctx.close()
     print("wide block:", k, w, rep)
     assert rep.max_rel_logit_err <= 2e-2
+
+
+def test_prefill_piece_boundaries_16_bit():
+    """Prompts around the prefill's 256-token pieces on the small 16-bit widths (2 layers): the last piece has
+    1 .. 256 rows, so the first generated token comes through the skinny kernel (up to 128 rows) or the wide one."""
+    desc = si.reduced_layers(si.MODELS["small"], 2)
+    run = dict(si.RUNS["cfg2"], prompt_len=700, n_gen=8)
+    w_, _, model, ctx = _setup(desc, run)
+    for n_prompt in (129, 200, 255, 256, 257, 300, 384, 385, 512, 513, 640):
+        prompt = si.prompt_spans(desc["vocab"], n_prompt, 0.3, seed=7)
+        rep = lockstep_run(ctx, model, prompt, 4, run, TOL["bf16"], max_steps=1)
+        assert rep.max_rel_logit_err <= 2e-2, n_prompt
+    ctx.close()
 
 
 def test_7b_width_two_layer_twin_bf16_lockstep():
