@@ -516,12 +516,8 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(const GemmArgs a) {
   }
 }
 
-template <typename T, int EPI, int FM>
-static void launch_wide_fm(const GemmArgs &a_in, int KS, hipStream_t s) {
-  constexpr int FN = 2;
-  GemmArgs a = a_in;
-  a.n_groups = a.N / 16 * ((EPI == EPI_GATEUP) ? 2 : 1);     // fragments: gate/up interleaves 2 * d_ffn rows
-  if (EPI == EPI_QKV) a.n_groups = (a.H + 2 * a.Hkv) * (a.hd / 16);
+template <typename T, int EPI, int FM, int FN>
+static void launch_wide_cfg(const GemmArgs &a, int KS, hipStream_t s) {
   const size_t lds = (size_t)2 * 16 * FM * (64 + 8) * sizeof(T);
   const int blocks = (a.n_groups + 4 * FN - 1) / (4 * FN);
   if (lds > 64 * 1024) {
@@ -530,6 +526,26 @@ static void launch_wide_fm(const GemmArgs &a_in, int KS, hipStream_t s) {
     (void)opted;
   }
   hipLaunchKernelGGL((gemm_wide_kernel<T, EPI, FM, FN>), dim3(blocks, KS), dim3(256), lds, s, a);
+}
+
+template <typename T, int EPI, int FM>
+static void launch_wide_fm(const GemmArgs &a_in, int KS, hipStream_t s) {
+  GemmArgs a = a_in;
+  a.n_groups = a.N / 16 * ((EPI == EPI_GATEUP) ? 2 : 1);     // fragments: gate/up interleaves 2 * d_ffn rows
+  if (EPI == EPI_QKV) a.n_groups = (a.H + 2 * a.Hkv) * (a.hd / 16);
+  // Two fragments per wave (128 rows of W per workgroup) where that still gives most CUs a workgroup, one
+  // otherwise (q/k/v of a 4096-wide model has 768 fragments: 96 workgroups against 192): every workgroup reads
+  // all of X whatever it owns, so the W rows per workgroup only matter once the chip is full.
+  // (q/k/v tiles of 16 and 18 row blocks always take one: with two, the unrolled rotary epilogue over 36
+  // accumulator fragments no longer fits the registers)
+  if constexpr (EPI == EPI_QKV && FM >= 16) {
+    launch_wide_cfg<T, EPI, FM, 1>(a, KS, s);
+  } else {
+    if constexpr (EPI == EPI_QKV || EPI == EPI_GATEUP) {
+      if ((a.n_groups + 7) / 8 * KS < 160) { launch_wide_cfg<T, EPI, FM, 1>(a, KS, s); return; }
+    }
+    launch_wide_cfg<T, EPI, FM, 2>(a, KS, s);
+  }
 }
 
 // Row tiles of the wide kernel: as few passes as possible (288 rows at most each), then the smallest even
