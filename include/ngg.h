@@ -196,6 +196,17 @@ ngg_status ngg_unigram_build(ngg_ctx *ctx, int32_t top_k);
 enum { NGG_BIGRAM_DIRECT = 0, NGG_BIGRAM_TABLE = 1, NGG_UNIGRAM = 2 };
 ngg_status ngg_bigram_source(ngg_ctx *ctx, int32_t source);
 
+/* Row allocation between the two strategies inside ngg_greedy_decode / ngg_decode_more (Section 5.2 closes on
+ * the remark that the context strategy is often handed the whole batch although its wins come from its first
+ * rows, and that a better allocation could gain more).  NGG_ALLOC_FIXED (default): every call may take up to
+ * cfg.k_ctx_max context rows, the rule of Section 4.3.  NGG_ALLOC_ADAPTIVE: once warmup_wins calls since the
+ * last prefill were won by a context row with at least one accepted token, a call may take at most c context
+ * rows, c being the smallest count of leading context rows that held coverage_percent of those wins (never
+ * more than cfg.k_ctx_max, never fewer than 1); the bigram fills the rest.  The choice changes the drafts,
+ * never the committed tokens.  ngg_build_drafts called directly is not affected. */
+enum { NGG_ALLOC_FIXED = 0, NGG_ALLOC_ADAPTIVE = 1 };
+ngg_status ngg_allocation(ngg_ctx *ctx, int32_t mode, int32_t coverage_percent, int32_t warmup_wins);
+
 /* Committed token history: copies min(n, cap) tokens to dst (HOST), n to *n. */
 ngg_status ngg_get_tokens(const ngg_ctx *ctx, int32_t *dst, int32_t cap, int32_t *n);
 

@@ -13,4 +13,4 @@ from .model import Model, KVCache                                   # noqa: F401
 from .drafts import (context_ngram_groups, context_rows, bigram_scores, rank_ids,   # noqa: F401
                      Bigram, ModelBigram, unigram_distances, UnigramDrafts, build_drafts)
 from .verify import (accept_lengths, select_winner, State, prefill, verify_step,    # noqa: F401
-                     commit, greedy_plain, greedy_plain_cached, greedy_speculative)
+                     commit, greedy_plain, greedy_plain_cached, greedy_speculative, adaptive_context_cap)

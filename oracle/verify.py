@@ -125,11 +125,29 @@ def greedy_plain_cached(model: Model, prompt, n_gen: int):
     return out[:n_gen]
 
 
+def adaptive_context_cap(ctx_rank_wins, k_ctx_max: int, coverage_percent: int, warmup_wins: int) -> int:
+    """Context rows allowed in the next call under the adaptive allocation: the ablation of Section 5.2 finds
+    the context strategy's wins in its first few rows while it often fills the whole batch.  Once
+    `warmup_wins` calls were won by a context row (with an accepted token), allow the smallest number of
+    leading context rows that held `coverage_percent` of those wins; at least 1, at most k_ctx_max."""
+    total = sum(ctx_rank_wins)
+    if total < warmup_wins:
+        return k_ctx_max
+    seen = 0
+    for r, n in enumerate(ctx_rank_wins):
+        seen += n
+        if 100 * seen >= coverage_percent * total:
+            return min(k_ctx_max, max(1, r + 1))
+    return k_ctx_max
+
+
 def greedy_speculative(model: Model, prompt, n_gen: int, k: int, w: int, k_ctx_max: int,
-                       q_min: int, q_max: int, bigram: Bigram | None = None):
+                       q_min: int, q_max: int, bigram: Bigram | None = None, allocation: dict | None = None):
     """Greedy decoding with batched learning-free drafts.  Returns
     (generated tokens [n_gen], stats) with stats = calls, tokens per call,
-    histogram of new tokens per call, winner source counts, context rows found."""
+    histogram of new tokens per call, winner source counts, context rows found.
+    `allocation` = dict(coverage_percent, warmup_wins) switches the row allocation
+    from the fixed cap k_ctx_max (Section 4.3) to adaptive_context_cap."""
     bigram = bigram or Bigram(model.tok_emb, model.unemb)
     st = prefill(model, prompt)
     n0 = len(prompt)
@@ -137,7 +155,10 @@ def greedy_speculative(model: Model, prompt, n_gen: int, k: int, w: int, k_ctx_m
     stats = dict(calls=0, new_hist=[0] * (w + 2), winner_src=[0, 0], ctx_rows=[],
                  accept_hist=[[0] * (w + 1), [0] * (w + 1)], rank_hist=[[0] * k, [0] * k], alloc_hist=[0] * (k + 1))
     while len(st.tokens) - n0 < n_gen:
-        drafts, src, n_ctx = build_drafts(st.tokens, bigram, k, w, k_ctx_max, q_min, q_max)
+        cap = k_ctx_max
+        if allocation:
+            cap = adaptive_context_cap(stats["rank_hist"][0], k_ctx_max, allocation["coverage_percent"], allocation["warmup_wins"])
+        drafts, src, n_ctx = build_drafts(st.tokens, bigram, k, w, cap, q_min, q_max)
         res = verify_step(model, st, drafts)
         n_new = commit(st, res, max_new=n_gen - (len(st.tokens) - n0))
         stats["calls"] += 1

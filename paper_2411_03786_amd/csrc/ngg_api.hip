@@ -72,6 +72,9 @@ struct ngg_ctx {
   int32_t attn_layout[4] = {0, 0, 0, 0};   // last forward: key-list slices per head, attention workgroups, block rows, cached positions
   bool drafts_on_device = false;
   int drafts_k = 0, drafts_w = 0;
+  // row allocation between the strategies inside the library's decode loop (ngg_allocation)
+  int alloc_mode = NGG_ALLOC_FIXED, alloc_coverage = 90, alloc_warmup = 8;
+  int64_t ctx_rank_wins[32] = {};  // since the last prefill: calls won, with an accepted draft, by the r-th context row
   std::string err;
   // profiling
   int prof_mask = 0;               // bit i: record events around kernels of class i
@@ -474,6 +477,7 @@ ngg_status ngg_prefill(ngg_ctx *c, const int32_t *prompt, int32_t n_prompt) {
   c->n = 0;
   c->have_verify = false;
   c->drafts_on_device = false;
+  for (auto &r : c->ctx_rank_wins) r = 0;
   c->tokens.assign(prompt, prompt + n_prompt);
   NGG_HIP(c, hipMemcpyAsync(c->hist, prompt, (size_t)n_prompt * 4, hipMemcpyHostToDevice, c->stream));
   const ngg_model_desc &d = c->d;
@@ -603,6 +607,25 @@ ngg_status ngg_commit(ngg_ctx *c, int32_t max_new, int32_t *n_committed) {
   return NGG_OK;
 }
 
+// Rows the context strategy may take in the next call.  Fixed: the configured cap.  Adaptive (the ablation of
+// Section 5.2 finds the context strategy's wins concentrated in its first rows, with diminishing returns from
+// more, while it is often handed the whole batch): the smallest number of leading context rows that held
+// `coverage` percent of the context strategy's wins so far, once `warmup` such wins were seen; the rows
+// this frees go to the bigram.  Integer arithmetic only: the oracle takes the same decision.
+static int context_row_cap(const ngg_ctx *c, int configured) {
+  if (c->alloc_mode != NGG_ALLOC_ADAPTIVE) return configured;
+  int64_t total = 0;
+  for (int64_t r : c->ctx_rank_wins) total += r;
+  if (total < c->alloc_warmup) return configured;
+  int64_t seen = 0;
+  int cap = 32;
+  for (int r = 0; r < 32; ++r) {
+    seen += c->ctx_rank_wins[r];
+    if (100 * seen >= (int64_t)c->alloc_coverage * total) { cap = r + 1; break; }
+  }
+  return std::min(configured, std::max(1, cap));
+}
+
 // (build_drafts, verify_step, commit) until n_gen tokens were appended after position n0 or max_calls
 // verify calls were made
 static ngg_status decode_loop(ngg_ctx *c, int n0, int n_gen, int64_t max_calls, const ngg_draft_cfg *cfg, ngg_stats &st) {
@@ -612,6 +635,7 @@ static ngg_status decode_loop(ngg_ctx *c, int n0, int n_gen, int64_t max_calls, 
     ngg_draft_cfg step = *cfg;
     const int left = n_gen - (c->n - n0);
     step.w = std::min(step.w, std::max(0, std::min(left - 1, c->d.max_seq - c->n)));
+    step.k_ctx_max = context_row_cap(c, step.k_ctx_max);
     double t0 = now_ms();
     // nothing is fetched here, so the forward pass is queued while the drafts are still being built; the
     // accept kernel hands the builder's row bookkeeping back with the result
@@ -636,6 +660,7 @@ static ngg_status decode_loop(ngg_ctx *c, int n0, int n_gen, int64_t max_calls, 
     st.ctx_rows += n_ctx;
     st.accept_hist[ws][vo.n_accept] += 1;
     if (vo.n_accept > 0) st.rank_hist[ws][ws ? vo.winner - n_ctx : vo.winner] += 1;
+    if (vo.n_accept > 0 && ws == 0) c->ctx_rank_wins[vo.winner] += 1;
     st.alloc_hist[n_ctx] += 1;
     ++calls;
   }
@@ -821,6 +846,16 @@ ngg_status ngg_unigram_build(ngg_ctx *c, int32_t top_k) {
   if (negd2) (void)hipFree(negd2);
   if (st != NGG_OK) return st;
   c->uni_K = top_k;
+  return NGG_OK;
+}
+
+ngg_status ngg_allocation(ngg_ctx *c, int32_t mode, int32_t coverage_percent, int32_t warmup_wins) {
+  if (!c) return NGG_EINVAL;
+  if (mode != NGG_ALLOC_FIXED && mode != NGG_ALLOC_ADAPTIVE) return fail(c, NGG_EINVAL, "ngg_allocation: unknown mode %d", mode);
+  if (mode == NGG_ALLOC_ADAPTIVE && (coverage_percent < 1 || coverage_percent > 100 || warmup_wins < 1))
+    return fail(c, NGG_EINVAL, "ngg_allocation: need 1 <= coverage_percent <= 100 and warmup_wins >= 1");
+  c->alloc_mode = mode;
+  if (mode == NGG_ALLOC_ADAPTIVE) { c->alloc_coverage = coverage_percent; c->alloc_warmup = warmup_wins; }
   return NGG_OK;
 }
 

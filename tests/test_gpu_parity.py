@@ -265,6 +265,37 @@ def test_matcher_on_long_contexts_with_thousands_of_matches():
     assert rows_found > 100
 
 
+def test_adaptive_allocation_follows_the_oracle():
+    """The adaptive row allocation (fewer context rows once their wins are seen to sit in the first ranks)
+    inside the library's decode loop: same tokens, same per-call allocation and statistics as the oracle
+    under the same rule, and a different allocation than the fixed cap on a stream where the context wins."""
+    desc, w, succ = _successor_model(period=9)
+    model = oracle.Model(desc, w)
+    rng = np.random.default_rng(5)
+    x = [2]
+    for _ in range(150):
+        x.append(int(succ[x[-1]]) if rng.random() < 0.8 else int(rng.integers(0, 9)))
+    cfg = dict(k=8, w=3, k_ctx_max=8, q_min=1, q_max=2)
+    ctx = ngg.Context(desc, w, max_seq=400, max_k=8, max_w=4)
+    fixed_tok, fixed = ctx.greedy_decode(x, 60, cfg)
+    with pytest.raises(ngg.NggError) as e:
+        ctx.allocation(1, 0, 3)
+    assert e.value.status == ngg.NGG_EINVAL
+    ctx.allocation(1, 90, 3)
+    got, st = ctx.greedy_decode(x, 60, cfg)
+    ctx.allocation(0)
+    again, st_fixed = ctx.greedy_decode(x, 60, cfg)
+    ctx.close()
+    want, o_st = oracle.greedy_speculative(model, x, 60, cfg["k"], cfg["w"], cfg["k_ctx_max"], cfg["q_min"], cfg["q_max"],
+                                           allocation=dict(coverage_percent=90, warmup_wins=3))
+    assert list(got) == want == list(fixed_tok) == list(again)
+    assert st["calls"] == o_st["calls"] and st["alloc_hist"][:9] == o_st["alloc_hist"] and st["ctx_rows"] == sum(o_st["ctx_rows"])
+    assert st["winner_src"] == o_st["winner_src"] and st["rank_hist"][0][:8] == o_st["rank_hist"][0]
+    assert st_fixed["alloc_hist"] == fixed["alloc_hist"]                      # back to the fixed rule
+    assert st["alloc_hist"] != fixed["alloc_hist"] and st["ctx_rows"] < fixed["ctx_rows"]
+    print("adaptive allocation:", st["alloc_hist"][:9], "fixed:", fixed["alloc_hist"][:9])
+
+
 def test_row_permutation_and_duplicate_rows(tiny):
     """Rows are independent given the shared prefix: a duplicate row gets the same logits as its original,
     permuting the rows permutes the results, and the committed tokens do not change (the winner is the

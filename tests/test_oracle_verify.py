@@ -286,3 +286,20 @@ def test_chunked_prefill_and_widening_at_use_change_nothing(tiny):
     bw = si.make_weights(bdesc, seed=3)
     assert np.array_equal(Model(bdesc, bw, widen_at_use=True).forward_full([1, 2, 3, 4, 5]),
                           Model(bdesc, bw).forward_full([1, 2, 3, 4, 5]))
+
+
+def test_adaptive_context_cap_by_hand_and_the_invariant(tiny):
+    from oracle import adaptive_context_cap
+    wins = [5, 3, 1, 1, 0, 0]                                  # 10 context wins: 5 by the first row, 3 by the second, ...
+    assert adaptive_context_cap(wins, 6, 90, 8) == 3           # 5 + 3 + 1 = 9 of 10 reach 90 %
+    assert adaptive_context_cap(wins, 6, 80, 8) == 2           # 8 of 10
+    assert adaptive_context_cap(wins, 6, 81, 8) == 3
+    assert adaptive_context_cap(wins, 6, 100, 8) == 4          # every win
+    assert adaptive_context_cap(wins, 2, 100, 8) == 2          # never above the configured cap
+    assert adaptive_context_cap(wins, 6, 90, 11) == 6          # not warmed up: the configured cap
+    assert adaptive_context_cap([7, 0, 0], 3, 90, 1) == 1      # all wins in the first row
+    assert adaptive_context_cap([0, 0, 0], 3, 90, 1) == 3      # no wins yet
+    assert adaptive_context_cap([0, 0, 4], 3, 1, 1) == 3       # the first rows never won: the cap still reaches the row that did
+    desc, w, run, prompt, m, plain = tiny
+    gen, st = greedy_speculative(m, prompt, 24, 5, 4, 5, 1, 3, allocation=dict(coverage_percent=50, warmup_wins=1))
+    assert gen == plain                                        # whatever the allocation, the tokens are the greedy tokens
