@@ -182,11 +182,12 @@ def measure(ngg, si, torch, workload, steps, warmup, dev_w, args, full=True):
                 "traffic": measured_traffic(workload),
                 "bytes_per_launch": gb, "avg_launch_us": avg_us, "launches": dom_n,
                 "empty_kernel_bracket_us": bracket_us}
+    read_gbps = ctx.profile_read_bandwidth() if full else None
     ctx.close()
     gbps = lambda b, ms: b / (ms * 1e-3) / 1e9
     return dict(run=run, m=m, prompt_len=len(prompt), k=k, w=w, new_tokens=new_tokens, elapsed=elapsed, ms_per_step=ms_per_step,
                 decode_ms=decode_ms, tokens_per_call=new_tokens / steps, breakdown=breakdown, roof=roof,
-                prefill_s=prefill_s, table_build_s=table_build_s,
+                prefill_s=prefill_s, table_build_s=table_build_s, read_gbps=read_gbps,
                 step_hbm={"algorithmic_bytes": step_bytes, "GBps": gbps(step_bytes, ms_per_step),
                           "frac_of_peak": gbps(step_bytes, ms_per_step) / HBM_PEAK_GBPS},
                 decode_hbm={"algorithmic_bytes": dec_bytes, "GBps": gbps(dec_bytes, decode_ms),
@@ -271,6 +272,9 @@ def main():
         "decode_hbm": r["decode_hbm"],
         "target": {"step_frac_of_peak_min": 0.70, "verify_over_decode_max": 1.15,
                    "met": bool(r["step_hbm"]["frac_of_peak"] >= 0.70 and ms_per_step / decode_ms <= 1.15)},
+        # context: what a plain streaming read of the same weight buffer reaches on this machine (all CUs, 16-byte loads)
+        "plain_read_GBps": r["read_gbps"],
+        "step_frac_of_plain_read": (r["step_hbm"]["GBps"] / r["read_gbps"]) if r["read_gbps"] else None,
         "prefill": {"tokens": r["prompt_len"], "seconds": r["prefill_s"], "tokens_per_s": r["prompt_len"] / r["prefill_s"]},
         "kernel_breakdown": r["breakdown"],
         "variant": (f"damped residual (W_o, W_down x {args.damped_residual:g}): acceptance coverage, not the headline"

@@ -251,6 +251,11 @@ ngg_status ngg_profile_bracket_overhead(ngg_ctx *ctx, double *us);
 ngg_status ngg_context_drafts_static(const int32_t *tokens, int32_t n, int32_t w, int32_t k_ctx_max, int32_t q_min,
                                      int32_t q_max, int32_t *rows, int32_t *n_rows, void *hip_stream);
 
+/* What a plain streaming read reaches on this GPU, in GB/s: every CU reads its share of the library's copy of
+ * the weights once with 16-byte loads (2048 workgroups, best of 4 sweeps, timed with events on the context's
+ * stream).  Context for the roofline fractions, which are quoted against the published 8 TB/s. */
+ngg_status ngg_profile_read_bandwidth(ngg_ctx *ctx, double *gbps);
+
 /* Debug aid for parity tests: copies an internal device buffer to dst (HOST), at most cap bytes,
  * and reports its full size in *bytes.  Names: "h" (residual stream, fp32 [M][d_model]), "z"
  * (bigram scores of the last ngg_build_drafts, fp32 [vocab]), "next1" (int32 [vocab]), "hist"

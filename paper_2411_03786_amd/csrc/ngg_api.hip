@@ -773,6 +773,39 @@ ngg_status ngg_profile_bracket_overhead(ngg_ctx *c, double *us) {
   return NGG_OK;
 }
 
+ngg_status ngg_profile_read_bandwidth(ngg_ctx *c, double *gbps) {
+  if (!c || !gbps) return NGG_EINVAL;
+  // one sweep over the library's own operand-order copy of the weights (read-only here), timed with events on the
+  // context's stream: 4 repetitions after one warm-up, the best one reported
+  const ngg_model_desc &d = c->d;
+  const size_t dq = (size_t)d.n_heads * d.head_dim, dkv = (size_t)d.n_kv_heads * d.head_dim;
+  const size_t bytes = (((dq + 2 * dkv) * d.d_model + (size_t)d.d_model * dq + (size_t)3 * d.d_ffn * d.d_model) * d.n_layers +
+                        (size_t)d.vocab * d.d_model) * c->esize / 16 * 16;
+  constexpr int kBlocks = 2048, kReps = 4;
+  unsigned *sink = nullptr;
+  ngg_status st = dev_alloc(c, &sink, kBlocks * sizeof(unsigned), true);
+  if (st != NGG_OK) return st;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  hipError_t err = hipEventCreate(&e0);
+  if (err == hipSuccess) err = hipEventCreate(&e1);
+  double best_ms = 1e30;
+  for (int r = 0; r <= kReps && err == hipSuccess; ++r) {
+    err = hipEventRecord(e0, c->stream);
+    launch_read_probe(c->wtiled, bytes, sink, kBlocks, c->stream);
+    if (err == hipSuccess) err = hipEventRecord(e1, c->stream);
+    if (err == hipSuccess) err = hipEventSynchronize(e1);
+    float ms = 0.0f;
+    if (err == hipSuccess) err = hipEventElapsedTime(&ms, e0, e1);
+    if (r > 0 && ms < best_ms) best_ms = ms;
+  }
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  (void)hipFree(sink);
+  if (err != hipSuccess) return fail(c, NGG_EHIP, "ngg_profile_read_bandwidth: %s", hipGetErrorString(err));
+  *gbps = (double)bytes / (best_ms * 1e-3) / 1e9;
+  return NGG_OK;
+}
+
 ngg_status ngg_bigram_table_build(ngg_ctx *c, int32_t top_k) {
   if (!c) return NGG_EINVAL;
   const ngg_model_desc &d = c->d;

@@ -317,6 +317,7 @@ void launch_ctx_match(const DraftArgs &a, hipStream_t s);
 void launch_row_topk(const float *logits, int M, int V, int K, int32_t *out, hipStream_t s);
 void launch_iota(int32_t *dst, int first, int n, hipStream_t s);
 void launch_noop(hipStream_t s);
+void launch_read_probe(const void *src, size_t bytes, unsigned *sink, int blocks, hipStream_t s);   // sink: >= blocks words
 // copies src [N][K] (row-major) into rows row0 .. row0+N of the operand-order matrix dst
 // row_map: 0 = row n goes to row0 + n; 1 = rotary pairing inside blocks of 2*half rows (row i < half of a block goes
 // to 16*(i/8) + i%8, row half + i to 16*(i/8) + 8 + i%8); 2 / 3 = first / second member of interleaved 8-row halves
