@@ -142,13 +142,16 @@ ngg_status dev_alloc(ngg_ctx *c, P **p, size_t bytes, bool zero) {
 ngg_status forward(ngg_ctx *c, int R, int C, int P, bool from_hist, int w, bool unembed, bool want_logits,
                    const int32_t *tok_src = nullptr) {   // tok_src: from_hist reads its tokens here instead of the history
   const ngg_model_desc &d = c->d;
-  const int M = R * C;
+  // a verify block keeps one copy of the column every row shares (the uncached last context token): 1 + R*w tokens
+  const int shared0 = (!from_hist && C >= 2) ? 1 : 0;
+  const int M = block_tokens(R, C, shared0);
+  (void)w;
   const int dt = d.dtype;
   const int dq = d.n_heads * d.head_dim;
   hipStream_t s = c->stream;
   {
     ProfScope ps(c, NGG_PROF_OTHER);
-    launch_embed(dt, c->w.tok_emb, tok_src ? tok_src : c->hist, c->drafts, c->block_tok, c->h, d.d_model, M, C, w,
+    launch_embed(dt, c->w.tok_emb, tok_src ? tok_src : c->hist, c->drafts, c->block_tok, c->h, d.d_model, M,
                  tok_src ? 0 : P, from_hist ? 1 : 0, s);
   }
   const int n_splits = attention_splits(dt, d.head_dim, d.n_heads, M, P, c->max_splits);
@@ -170,7 +173,7 @@ ngg_status forward(ngg_ctx *c, int R, int C, int P, bool from_hist, int w, bool 
       g.X = c->xn; g.W0 = c->lt[l].wqkv;
       g.M = M; g.N = dq + 2 * d.n_kv_heads * d.head_dim; g.K = d.d_model;
       g.q = c->q; g.kscr = kscr_l; g.vscr = vscr_l;
-      g.H = d.n_heads; g.Hkv = d.n_kv_heads; g.hd = d.head_dim; g.Mcap = c->Mcap; g.C = C; g.P = P;
+      g.H = d.n_heads; g.Hkv = d.n_kv_heads; g.hd = d.head_dim; g.Mcap = c->Mcap; g.C = C; g.P = P; g.shared0 = shared0;
       g.rope_cos = c->rope_cos; g.rope_sin = c->rope_sin;
       g.row_ss = c->row_ss; g.ss_segs = ss_segs; g.ss_eps = d.rms_eps;
       g.out_scale = 1.0f / c->lt[l].s_qkv;
@@ -185,7 +188,7 @@ ngg_status forward(ngg_ctx *c, int R, int C, int P, bool from_hist, int w, bool 
       a.kscr = kscr_l; a.vscr = vscr_l;
       a.part_o = c->part_o; a.part_ml = c->part_ml; a.out = c->attn;
       a.H = d.n_heads; a.Hkv = d.n_kv_heads; a.Mcap = c->Mcap; a.Spad = c->Spad; a.M = M; a.C = C; a.P = P;
-      a.n_splits = n_splits;
+      a.n_splits = n_splits; a.shared0 = shared0;
       a.scale = 1.0f / std::sqrt((float)d.head_dim);
       launch_attention(dt, d.head_dim, a, s);
     }
@@ -488,10 +491,10 @@ ngg_status ngg_prefill(ngg_ctx *c, const int32_t *prompt, int32_t n_prompt) {
     if (st != NGG_OK) return st;
     ProfScope ps(c, NGG_PROF_ACCEPT_COMMIT);
     if (last)
-      launch_argmax_accept(c->pmax_val, c->pmax_idx, c->unembed_tiles, c->Mcap, C, 0, C, nullptr, nullptr, nullptr, c->res,
+      launch_argmax_accept(c->pmax_val, c->pmax_idx, c->unembed_tiles, c->Mcap, 1, 0, C, 0, nullptr, nullptr, nullptr, c->res,
                            res_greedy_off(d.max_k), c->stream);
     launch_commit(d.dtype, c->kcache, c->vcache, c->kscr, c->vscr, d.n_layers, d.n_kv_heads, d.head_dim, c->Spad,
-                  c->Mcap, C, p0, nullptr, 0, C, C, c->hist, c->stream);
+                  c->Mcap, C, 0, p0, nullptr, 0, C, C, c->hist, c->stream);
   }
   // first generated token = greedy prediction after the last prompt token
   const int last_c = (n_prompt - 1) % kPrefillChunk;
@@ -559,18 +562,29 @@ ngg_status ngg_verify_step(ngg_ctx *c, const int32_t *drafts, int32_t k, int32_t
     return fail(c, NGG_ESTATE, "ngg_verify_step: no device drafts of shape (%d, %d); call ngg_build_drafts or pass drafts", k, w);
   }
   if (out->logits) { ngg_status st = ensure_logits(c); if (st != NGG_OK) return st; }
-  const int C = w + 1, M = k * C;
+  const int C = w + 1, M = k * C;                       // M: entries of the (k, w+1) grid the caller sees
+  const int shared0 = C >= 2 ? 1 : 0;                  // the block itself holds 1 + k*w tokens (forward)
   ngg_status st = forward(c, k, C, c->n - 1, false, w, true, out->logits != nullptr);
   if (st != NGG_OK) return st;
   const int goff = res_greedy_off(d.max_k);
   {
     ProfScope ps(c, NGG_PROF_ACCEPT_COMMIT);
-    launch_argmax_accept(c->pmax_val, c->pmax_idx, c->unembed_tiles, c->Mcap, M, k, C, c->drafts, c->row_src, c->n_ctx, c->res, goff,
-                         c->stream);
+    launch_argmax_accept(c->pmax_val, c->pmax_idx, c->unembed_tiles, c->Mcap, k, k, C, shared0, c->drafts, c->row_src, c->n_ctx,
+                         c->res, goff, c->stream);
   }
   NGG_HIP(c, hipGetLastError());
   NGG_HIP(c, hipMemcpyAsync(c->res_host, c->res, (size_t)(goff + M) * 4, hipMemcpyDeviceToHost, c->stream));
-  if (out->logits) NGG_HIP(c, hipMemcpyAsync(out->logits, c->logits, (size_t)M * d.vocab * 4, hipMemcpyDeviceToHost, c->stream));
+  if (out->logits) {
+    // device logits are per block token; the caller's [k][w+1][vocab] grid repeats the shared column in every row
+    const size_t row = (size_t)d.vocab * 4;
+    for (int r = 0; r < k; ++r) {
+      char *dst = (char *)out->logits + (size_t)r * C * row;
+      NGG_HIP(c, hipMemcpyAsync(dst, c->logits + (size_t)block_index(r, 0, C, shared0) * d.vocab, row, hipMemcpyDeviceToHost, c->stream));
+      if (w > 0)
+        NGG_HIP(c, hipMemcpyAsync(dst + row, c->logits + (size_t)block_index(r, 1, C, shared0) * d.vocab, (size_t)w * row,
+                                  hipMemcpyDeviceToHost, c->stream));
+    }
+  }
   NGG_HIP(c, hipStreamSynchronize(c->stream));
   out->k = k; out->w = w;
   out->winner = c->res_host[RES_WINNER];
@@ -596,7 +610,7 @@ ngg_status ngg_commit(ngg_ctx *c, int32_t max_new, int32_t *n_committed) {
   {
     ProfScope ps(c, NGG_PROF_ACCEPT_COMMIT);
     launch_commit(d.dtype, c->kcache, c->vcache, c->kscr, c->vscr, d.n_layers, d.n_kv_heads, d.head_dim, c->Spad, c->Mcap,
-                  c->last_w + 1, c->n - 1, c->res, 0, 0, max_new, c->hist, c->stream);
+                  c->last_w + 1, c->last_w >= 1 ? 1 : 0, c->n - 1, c->res, 0, 0, max_new, c->hist, c->stream);
   }
   NGG_HIP(c, hipGetLastError());
   for (int i = 0; i < n_new; ++i) c->tokens.push_back(c->res_host[RES_NEWTOK + i]);

@@ -41,10 +41,10 @@ template <> struct Softmax<half_t> {
 
 // One 16-query fragment against one 32-key tile, after the scores: online softmax and P.V.
 // Sc: transposed scores (fragment f's row i is key 8*(i/4) + 4f + (i%4) of the tile, so this lane
-// holds the 8 consecutive keys k0 .. k0+7 of its query); keys outside [lo, hi] are masked unless the
-// whole tile is visible to every query (full).
+// holds the 8 consecutive keys k0 .. k0+7 of its query); keys outside [lo, hi] are masked (except key 0
+// when key0 is set: the block token every row shares) unless the whole tile is visible to every query (full).
 template <typename T, int DF, typename VFrag>
-__device__ __forceinline__ void softmax_pv(const f32x4 (&Sc)[2], float sfac, bool full, int k0, int lo, int hi,
+__device__ __forceinline__ void softmax_pv(const f32x4 (&Sc)[2], float sfac, bool full, int k0, int lo, int hi, bool key0,
                                            float &mrun, float &lrun, f32x4 (&O)[DF], VFrag vfrag) {
   float sv[8], p[8];
   float mx = kNegBig, ps = 0.0f;
@@ -57,7 +57,7 @@ __device__ __forceinline__ void softmax_pv(const f32x4 (&Sc)[2], float sfac, boo
   } else {
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      const bool vis = k0 + e >= lo && k0 + e <= hi;
+      const bool vis = (k0 + e >= lo && k0 + e <= hi) || (key0 && k0 + e == 0);
       sv[e] = vis ? Sc[e >> 2][e & 3] * sfac : kNegBig;
       mx = fmaxf(mx, sv[e]);
     }
@@ -127,8 +127,8 @@ __global__ __launch_bounds__(256) void attn_stream_kernel(const AttnArgs a, int 
   //      rows of this workgroup's queries; this workgroup takes list entries [t_begin, t_end) -----------
   const int q_lo = min(q0, M - 1), q_hi = min(M, q0 + GQ) - 1;
   const int NP = (P + 31) / 32;
-  const int sb = ((q_lo / C) * C) / 32;                     // first block tile
-  const int NS = (min(M, (q_hi / C + 1) * C) + 31) / 32 - sb;
+  const int sb = block_row_start(q_lo, C, a.shared0) / 32 * (a.shared0 ? 0 : 1);   // first block tile (tile 0 holds the shared token)
+  const int NS = q_hi / 32 + 1 - sb;                        // no query sees a block key beyond itself
   const int TL = NP + NS;
   const int t_begin = (int)((long)TL * split / S), t_end = (int)((long)TL * (split + 1) / S);
   const int n_tiles = active ? t_end - t_begin : 0;
@@ -142,7 +142,7 @@ __global__ __launch_bounds__(256) void attn_stream_kernel(const AttnArgs a, int 
 #pragma unroll
   for (int qf = 0; qf < QF; ++qf) {
     const int mq = min(q0 + qf * 16 + li, M - 1);
-    qlo[qf] = (mq / C) * C;
+    qlo[qf] = block_row_start(mq, C, a.shared0);
     qhi[qf] = mq;
     mrun[qf] = kNegBig;
     lrun[qf] = 0.0f;
@@ -197,8 +197,8 @@ __global__ __launch_bounds__(256) void attn_stream_kernel(const AttnArgs a, int 
 #pragma unroll
         for (int j = 0; j < QG; ++j) {
           const int qf = q2 + j;
-          softmax_pv<T, DF>(Sc[j], sfac, full, k0, own ? qlo[qf] : 0, own ? qhi[qf] : P - 1, mrun[qf], lrun[qf], O[qf],
-                            [&](int df) { return vr[df]; });
+          softmax_pv<T, DF>(Sc[j], sfac, full, k0, own ? qlo[qf] : 0, own ? qhi[qf] : P - 1, own && a.shared0, mrun[qf],
+                            lrun[qf], O[qf], [&](int df) { return vr[df]; });
         }
       }
     }
@@ -304,8 +304,8 @@ __global__ __launch_bounds__(256) void attn_shared_kernel(const AttnArgs a, int 
 
   const int q_hi = min(M, q0 + GQ) - 1;
   const int NP = (P + 31) / 32;
-  const int sb = ((q0 / C) * C) / 32;
-  const int NS = (min(M, (q_hi / C + 1) * C) + 31) / 32 - sb;
+  const int sb = block_row_start(q0, C, a.shared0) / 32 * (a.shared0 ? 0 : 1);     // first block tile (tile 0 holds the shared token)
+  const int NS = q_hi / 32 + 1 - sb;                        // no query sees a block key beyond itself
   const int TL = NP + NS;
   const int t_begin = (int)((long)TL * split / S), t_end = (int)((long)TL * (split + 1) / S);
   const int n_tiles = t_end - t_begin;
@@ -345,7 +345,7 @@ __global__ __launch_bounds__(256) void attn_shared_kernel(const AttnArgs a, int 
 #pragma unroll
   for (int qf = 0; qf < QF; ++qf) {
     const int mq = min(qw + qf * 16 + li, M - 1);
-    qlo[qf] = (mq / C) * C;
+    qlo[qf] = block_row_start(mq, C, a.shared0);
     qhi[qf] = mq;
     mrun[qf] = kNegBig;
     lrun[qf] = 0.0f;
@@ -380,8 +380,8 @@ __global__ __launch_bounds__(256) void attn_shared_kernel(const AttnArgs a, int 
         }
 #pragma unroll
       for (int qf = 0; qf < QF; ++qf)
-        softmax_pv<T, DF>(Sc[qf], sfac, full, k0, own ? qlo[qf] : 0, own ? qhi[qf] : P - 1, mrun[qf], lrun[qf], O[qf],
-                          [&](int df) { return load_frag_tiled(vt + df * 512); });
+        softmax_pv<T, DF>(Sc[qf], sfac, full, k0, own ? qlo[qf] : 0, own ? qhi[qf] : P - 1, own && a.shared0, mrun[qf],
+                          lrun[qf], O[qf], [&](int df) { return load_frag_tiled(vt + df * 512); });
     }
   };
 

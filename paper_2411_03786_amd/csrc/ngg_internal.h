@@ -215,6 +215,26 @@ template <> __device__ __forceinline__ float silu<half_t>(float x) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Block token index.  The model call of Section 3 takes a block of R rows x C columns.  Plain layout
+// (pieces of a prompt, table builds): m = r*C + j.  Shared-first-column layout (a verify block,
+// C = w + 1 >= 2): column 0 of every row is the same token (the uncached last context token) at the same
+// position and sees the same keys, so its activations, keys/values and logits are identical in every
+// row and are computed once: m = 0 for column 0 and m = r*(C-1) + j for columns j >= 1, 1 + R*w distinct
+// block tokens in all.  Token m sees the cached context, and of the block: itself, the earlier drafted
+// tokens of its own row (indices block_row_start(m) .. m) and, in the shared layout, token 0.
+// ---------------------------------------------------------------------------------------------
+__host__ __device__ __forceinline__ int block_index(int r, int j, int C, int shared0) {
+  return shared0 ? (j == 0 ? 0 : r * (C - 1) + j) : r * C + j;
+}
+__host__ __device__ __forceinline__ int block_col(int m, int C, int shared0) {
+  return shared0 ? (m == 0 ? 0 : (m - 1) % (C - 1) + 1) : m % C;
+}
+__host__ __device__ __forceinline__ int block_row_start(int m, int C, int shared0) {
+  return shared0 ? (m == 0 ? 0 : m - (m - 1) % (C - 1)) : m - m % C;
+}
+__host__ __device__ __forceinline__ int block_tokens(int R, int C, int shared0) { return shared0 ? 1 + R * (C - 1) : R * C; }
+
+// ---------------------------------------------------------------------------------------------
 // Launch descriptions (plain structs passed by value to the kernels).
 // ---------------------------------------------------------------------------------------------
 enum GemmEpilogue { EPI_QKV = 0, EPI_RESIDUAL = 1, EPI_GATEUP = 2, EPI_UNEMBED = 3 };
@@ -239,7 +259,8 @@ struct GemmArgs {
   void *q;                // [H][Mcap][hd] T
   void *kscr;             // this layer's block keys, [Hkv][Mcap/32] tiles (k_offset)
   void *vscr;             // this layer's block values, [Hkv][Mcap/32] tiles (v_offset)
-  int H, Hkv, hd, Mcap, C, P;   // m = row*C + col sits at position P + col
+  int H, Hkv, hd, Mcap, C, P;   // block token m sits at position P + block_col(m, C, shared0)
+  int shared0;
   const float *rope_cos, *rope_sin;   // [Spad][hd/2]
   // EPI_UNEMBED
   float *logits;          // [M][N] fp32 or null
@@ -260,6 +281,7 @@ struct AttnArgs {
   float *part_ml;         // [H][n_splits][Mcap][2]
   void *out;              // chunk-major [H*hd/KC][Mcap][KC] T
   int H, Hkv, Mcap, Spad, M, C, P, n_splits;   // n_splits: workgroups that share a head's list of key tiles
+  int shared0;            // block layout (block_index)
   float scale;
 };
 
@@ -271,8 +293,10 @@ void launch_attention(int dtype, int hd, const AttnArgs &a, hipStream_t s);
 int attention_splits(int dtype, int hd, int H, int M, int P, int max_splits);
 int attention_workgroups(int dtype, int hd, int H, int M, int n_splits);   // workgroups the main attention kernel is launched with
 
+// from_hist: block token m is history token hist_base + m; otherwise the verify block in the shared-first-column
+// layout: token 0 is hist[hist_base], token m >= 1 is drafts[m - 1]
 void launch_embed(int dtype, const void *tok_emb, const int32_t *hist, const int32_t *drafts, int32_t *block_tok,
-                  float *h, int d, int M, int C, int w, int hist_base, int from_hist, hipStream_t s);
+                  float *h, int d, int M, int hist_base, int from_hist, hipStream_t s);
 // h[m] += sum of n_part partials (hpart[s][m], stride part_stride floats between splits), then
 // xn[m] = rmsnorm(h[m]) * gain, written chunk-major
 // dst = (src - centre) * scale in the internal element type (src: the user's storage type)
@@ -330,11 +354,13 @@ void launch_tile_weights(int dtype, const void *src, void *dst, int N, int K, in
 enum { RES_WINNER = 0, RES_NACCEPT = 1, RES_NNEW = 2, RES_NCTX = 3, RES_WINSRC = 4, RES_NEWTOK = 8, RES_ACCEPT = 48 };
 inline int res_greedy_off(int max_k) { return RES_ACCEPT + ((max_k + 7) / 8) * 8; }
 
-void launch_argmax_accept(const float *pmax_val, const int *pmax_idx, int tiles, int Mcap, int M, int k, int C,
+// greedy grid [rows][C] from the per-token partial maxima (token block_index(r, j, C, shared0)); k > 0: then the
+// accepted lengths and the winner of the k x (C-1) drafts
+void launch_argmax_accept(const float *pmax_val, const int *pmax_idx, int tiles, int Mcap, int rows, int k, int C, int shared0,
                           const int32_t *drafts, const int8_t *row_src, const int32_t *n_ctx, int32_t *res, int greedy_off,
                           hipStream_t s);
 void launch_commit(int dtype, void *kcache, void *vcache, const void *kscr, const void *vscr, int L, int Hkv, int hd,
-                   int Spad, int Mcap, int C, int P, const int32_t *res, int fixed_row, int fixed_n, int max_new,
+                   int Spad, int Mcap, int C, int shared0, int P, const int32_t *res, int fixed_row, int fixed_n, int max_new,
                    int32_t *hist, hipStream_t s);
 void launch_next1_finish(const float *pmax_val, const int *pmax_idx, int tiles, int Mcap, int M, int32_t *next1_out,
                          hipStream_t s);

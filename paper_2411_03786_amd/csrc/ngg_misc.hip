@@ -8,21 +8,16 @@
 namespace ngg {
 
 // ---------------------------------------------------------------------------------------------
-// block tokens + embedding gather.  Block position m = r*C + j holds the uncached last context
-// token for j = 0 and row r's drafted token j-1 otherwise (Section 3: input block (k, w+1)); in
-// prefill mode it holds history token hist_base + m.
+// block tokens + embedding gather.  A verify block (Section 3: input block (k, w+1)) in the
+// shared-first-column layout: token 0 is the uncached last context token, token m >= 1 is drafted
+// token m - 1 of the k x w draft batch (row-major: the same order).  In prefill mode token m is
+// history token hist_base + m.
 // ---------------------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void embed_kernel(const T *tok_emb, const int32_t *hist, const int32_t *drafts,
-                                                    int32_t *block_tok, float *h, int d, int C, int w, int hist_base,
-                                                    int from_hist) {
+                                                    int32_t *block_tok, float *h, int d, int hist_base, int from_hist) {
   const int m = blockIdx.x;
-  int tok;
-  if (from_hist) tok = hist[hist_base + m];
-  else {
-    const int r = m / C, j = m - r * C;
-    tok = j == 0 ? hist[hist_base] : drafts[r * w + j - 1];
-  }
+  const int tok = from_hist ? hist[hist_base + m] : (m == 0 ? hist[hist_base] : drafts[m - 1]);
   if (threadIdx.x == 0) block_tok[m] = tok;
   const T *e = tok_emb + (size_t)tok * d;
   for (int i = 4 * threadIdx.x; i < d; i += 1024) {         // d is a multiple of 32: four elements per load
@@ -38,13 +33,13 @@ __global__ __launch_bounds__(256) void embed_kernel(const T *tok_emb, const int3
 }
 
 void launch_embed(int dtype, const void *tok_emb, const int32_t *hist, const int32_t *drafts, int32_t *block_tok,
-                  float *h, int d, int M, int C, int w, int hist_base, int from_hist, hipStream_t s) {
+                  float *h, int d, int M, int hist_base, int from_hist, hipStream_t s) {
   if (dtype == 1)
     hipLaunchKernelGGL(embed_kernel<bf16_t>, dim3(M), dim3(256), 0, s, (const bf16_t *)tok_emb, hist, drafts, block_tok,
-                       h, d, C, w, hist_base, from_hist);
+                       h, d, hist_base, from_hist);
   else
     hipLaunchKernelGGL(embed_kernel<float>, dim3(M), dim3(256), 0, s, (const float *)tok_emb, hist, drafts, block_tok, h,
-                       d, C, w, hist_base, from_hist);
+                       d, hist_base, from_hist);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -728,13 +723,15 @@ __device__ __forceinline__ void wave_argmax(float &bv, int &bi) {
   }
 }
 
-// greedy[m] = argmax over the vocabulary of position m, from the per-tile maxima; one workgroup per position
+// greedy[r*C + j] = argmax over the vocabulary after block token block_index(r, j), from the per-tile maxima; one
+// workgroup per entry of the grid (in the shared-first-column layout the k entries of column 0 read the same token)
 __global__ __launch_bounds__(256) void argmax_reduce_kernel(const float *__restrict__ pmax_val,
                                                             const int *__restrict__ pmax_idx, int tiles, int Mcap,
-                                                            int32_t *greedy) {
+                                                            int32_t *greedy, int C, int shared0) {
   __shared__ float wv[4];
   __shared__ int wi[4];
-  const int m = blockIdx.x, tid = threadIdx.x;
+  const int tid = threadIdx.x;
+  const int m = block_index(blockIdx.x / C, blockIdx.x % C, C, shared0);
   float bv = kNegBig;
   int bi = 0x7fffffff;
   for (int t0 = tid; t0 < tiles; t0 += 1024) {              // four independent loads in flight
@@ -756,7 +753,7 @@ __global__ __launch_bounds__(256) void argmax_reduce_kernel(const float *__restr
   if (tid == 0) {
     for (int t = 1; t < 4; ++t)
       if (wv[t] > bv || (wv[t] == bv && wi[t] < bi)) { bv = wv[t]; bi = wi[t]; }
-    greedy[m] = bi;
+    greedy[blockIdx.x] = bi;
   }
 }
 
@@ -786,16 +783,17 @@ __global__ __launch_bounds__(64) void accept_kernel(int k, int C, const int32_t 
   }
 }
 
-void launch_argmax_accept(const float *pmax_val, const int *pmax_idx, int tiles, int Mcap, int M, int k, int C,
+void launch_argmax_accept(const float *pmax_val, const int *pmax_idx, int tiles, int Mcap, int rows, int k, int C, int shared0,
                           const int32_t *drafts, const int8_t *row_src, const int32_t *n_ctx, int32_t *res, int greedy_off,
                           hipStream_t s) {
-  hipLaunchKernelGGL(argmax_reduce_kernel, dim3(M), dim3(256), 0, s, pmax_val, pmax_idx, tiles, Mcap, res + greedy_off);
+  hipLaunchKernelGGL(argmax_reduce_kernel, dim3(rows * C), dim3(256), 0, s, pmax_val, pmax_idx, tiles, Mcap, res + greedy_off, C,
+                     shared0);
   if (k > 0) hipLaunchKernelGGL(accept_kernel, dim3(1), dim3(64), 0, s, k, C, drafts, row_src, n_ctx, res, greedy_off);
 }
 
 void launch_next1_finish(const float *pmax_val, const int *pmax_idx, int tiles, int Mcap, int M, int32_t *next1_out,
                          hipStream_t s) {
-  hipLaunchKernelGGL(argmax_reduce_kernel, dim3(M), dim3(256), 0, s, pmax_val, pmax_idx, tiles, Mcap, next1_out);
+  hipLaunchKernelGGL(argmax_reduce_kernel, dim3(M), dim3(256), 0, s, pmax_val, pmax_idx, tiles, Mcap, next1_out, 1, 0);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -891,7 +889,7 @@ void launch_iota(int32_t *dst, int first, int n, hipStream_t s) {
 // ---------------------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void commit_kernel(T *kcache, T *vcache, const T *kscr, const T *vscr, int Hkv, int hd,
-                                                     int Spad, int Mcap, int C, int P, const int32_t *res, int fixed_row,
+                                                     int Spad, int Mcap, int C, int shared0, int P, const int32_t *res, int fixed_row,
                                                      int fixed_n, int max_new, int32_t *hist) {
   const int layer = blockIdx.y, hkv = blockIdx.x;
   int row = fixed_row, n_new = fixed_n;
@@ -903,7 +901,7 @@ __global__ __launch_bounds__(256) void commit_kernel(T *kcache, T *vcache, const
   T *vc = vcache + lh * hd * Spad;
   for (int i = threadIdx.x; i < n_new * hd; i += 256) {
     const int j = i / hd, dd = i - j * hd;
-    const int src = row * C + j, dst = P + j;            // both live in tiles of 32 positions, in operand order
+    const int src = block_index(row, j, C, shared0), dst = P + j;   // both live in tiles of 32 positions, in operand order
     kc[k_offset(dst, dd, hd, (int)sizeof(T))] = ks[k_offset(src, dd, hd, (int)sizeof(T))];
     vc[v_offset(dst, dd, hd, (int)sizeof(T))] = vs[v_offset(src, dd, hd, (int)sizeof(T))];
   }
@@ -912,15 +910,15 @@ __global__ __launch_bounds__(256) void commit_kernel(T *kcache, T *vcache, const
 }
 
 void launch_commit(int dtype, void *kcache, void *vcache, const void *kscr, const void *vscr, int L, int Hkv, int hd,
-                   int Spad, int Mcap, int C, int P, const int32_t *res, int fixed_row, int fixed_n, int max_new,
+                   int Spad, int Mcap, int C, int shared0, int P, const int32_t *res, int fixed_row, int fixed_n, int max_new,
                    int32_t *hist, hipStream_t s) {
   if (dtype == 1)
     hipLaunchKernelGGL(commit_kernel<half_t>, dim3(Hkv, L), dim3(256), 0, s, (half_t *)kcache, (half_t *)vcache,
-                       (const half_t *)kscr, (const half_t *)vscr, Hkv, hd, Spad, Mcap, C, P, res, fixed_row, fixed_n,
+                       (const half_t *)kscr, (const half_t *)vscr, Hkv, hd, Spad, Mcap, C, shared0, P, res, fixed_row, fixed_n,
                        max_new, hist);
   else
     hipLaunchKernelGGL(commit_kernel<float>, dim3(Hkv, L), dim3(256), 0, s, (float *)kcache, (float *)vcache,
-                       (const float *)kscr, (const float *)vscr, Hkv, hd, Spad, Mcap, C, P, res, fixed_row, fixed_n,
+                       (const float *)kscr, (const float *)vscr, Hkv, hd, Spad, Mcap, C, shared0, P, res, fixed_row, fixed_n,
                        max_new, hist);
 }
 
