@@ -179,11 +179,13 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
 
   for (int m0 = 0; m0 < M; m0 += ROWS) {
     // X staging: piece p = tid + NT*i covers row p / PPR (= tid / PPR + i * NT / PPR), 16 bytes at column
-    // piece p % PPR.  Rows past M are read as they are (the buffers hold Mcap rows, a multiple of 64,
-    // of finite stale values) and never stored.
+    // piece p % PPR.
     static_assert(NT % PPR == 0, "row stride of the staging pieces must be constant");
     constexpr int RPI = NT / PPR;                          // rows between a thread's consecutive pieces
-    const T *xsrc0 = (const T *)a.X + (size_t)(m0 + tid / PPR) * KC + (tid % PPR) * PAD;   // chunk c adds c * Mcap * KC
+    // (rows past the block's last one repeat it: the same cache lines as the threads that stage that row, so they
+    // cost no further traffic from L2; what lands in their LDS rows is never stored)
+    const T *xsrc0 = (const T *)a.X + (tid % PPR) * PAD;                 // chunk c adds c * Mcap * KC, piece i its row * KC
+    const int xrow0 = m0 + tid / PPR, xrow_last = M - 1;
     const int xdst0 = (tid / PPR) * LDX + (tid % PPR) * PAD;
     // X is fetched XD chunks ahead into register stages (an L2 hit takes longer than one chunk of
     // MFMA work), then written to the LDS buffer of its chunk's parity.
@@ -191,7 +193,8 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
     auto stage_load = [&](u32x4 (&st)[PIECES], int c) {
       const int cl = c < n_chunks ? c : n_chunks - 1;      // activation buffers are padded to whole chunks
 #pragma unroll
-      for (int i = 0; i < PIECES; ++i) st[i] = *reinterpret_cast<const u32x4 *>(xsrc0 + (size_t)cl * a.Mcap * KC + i * RPI * KC);
+      for (int i = 0; i < PIECES; ++i)
+        st[i] = *reinterpret_cast<const u32x4 *>(xsrc0 + ((size_t)cl * a.Mcap + min(xrow0 + i * RPI, xrow_last)) * KC);
     };
     auto stage_store = [&](const u32x4 (&st)[PIECES], int buf) {
 #pragma unroll
@@ -421,14 +424,15 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(const GemmArgs a) {
 
   for (int m0 = 0; m0 < M; m0 += ROWS) {
     // X staging: piece p = tid + 256 i is row p / PPR, 16 bytes at column piece p % PPR of the slice; pieces
-    // past the tile repeat its last row, rows past the buffers' Mcap rows read row Mcap - 1 (never stored)
+    // past the tile repeat its last row, rows past the block's last row repeat that row (the same cache lines
+    // as the threads that stage it: no further traffic from L2; never stored)
     const T *xsrc[PIECES];
     int xdst[PIECES];
 #pragma unroll
     for (int i = 0; i < PIECES; ++i) {
       const int p = tid + 256 * i;
       const int row = min(p / PPR, ROWS - 1), col = p % PPR;
-      xsrc[i] = (const T *)a.X + (size_t)min(m0 + row, a.Mcap - 1) * KC + col * 8;
+      xsrc[i] = (const T *)a.X + (size_t)min(m0 + row, M - 1) * KC + col * 8;
       xdst[i] = row * LDX + col * 8;
     }
     u32x4 stage[2][PIECES];
