@@ -408,6 +408,21 @@ def test_grouped_query_attention_and_random_gains():
     assert rep.tolerated_argmax == 0 and rep.max_rel_logit_err <= 1e-4
 
 
+@pytest.mark.parametrize("hd,heads,kv", [(64, 12, 4), (128, 8, 2), (32, 8, 1)])
+def test_grouped_query_attention_16_bit(hd, heads, kv):
+    """Grouped-query attention in the 16-bit configuration, every head_dim the library takes, random gains: 3, 4 and
+    8 query heads per key/value head; verify blocks (shared kernel), single-token steps (stream kernel), prefill."""
+    desc = dict(si.reduced_layers(si.MODELS["small"], 2), n_heads=heads, n_kv_heads=kv, head_dim=hd, d_model=heads * hd,
+                vocab=4096)
+    run = dict(si.RUNS["cfg2"], prompt_len=300, n_gen=12)
+    w, prompt, model, ctx = _setup(desc, run, seed=6, random_gains=True)
+    rep = lockstep_run(ctx, model, prompt, 12, run, TOL["bf16"], max_steps=3)
+    rep1 = lockstep_run(ctx, model, prompt[:77], 5, dict(k=1, w=0, k_ctx_max=0, q_min=1, q_max=1), TOL["bf16"])
+    ctx.close()
+    print("16-bit GQA:", hd, heads, kv, rep, rep1)
+    assert rep.max_rel_logit_err <= 2e-2 and rep1.max_rel_logit_err <= 2e-2
+
+
 def test_damped_residual_variant_accepts_bigram_rows():
     """W_o and W_down scaled by 1e-2: the embedding path dominates, so bigram rows
     are accepted (a labelled variant for coverage, not a headline configuration)."""
