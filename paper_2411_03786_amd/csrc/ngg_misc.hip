@@ -239,7 +239,7 @@ void launch_neg_row_sumsq(const float *rows, int M, int V, float *out, hipStream
 //
 // Grouping and ranking take one of two routes that give the same groups:
 //  * up to kSmallMatches matches: every match is compared with every other one, every group with
-//    every other group (a few hundred compares, no atomics on memory);
+//    every other group (a few hundred compares per thread, no atomics on memory);
 //  * more (a frequent last token on a long context; a periodic context makes every window a
 //    match): the continuations go into an open-addressing hash table in the scratch memory, keyed
 //    by a hash of the w tokens and resolved by comparing the tokens themselves, each slot holding
@@ -247,7 +247,7 @@ void launch_neg_row_sumsq(const float *rows, int M, int V, float *out, hipStream
 //    repeated selection, every wave over its share of the groups and wave 0 over the waves'
 //    picks.  Linear in the number of matches.
 // ---------------------------------------------------------------------------------------------
-constexpr int kSmallMatches = 64;
+constexpr int kSmallMatches = 256;
 
 __device__ __forceinline__ bool same_cont(const int32_t *x, int a, int b, int w) {
   for (int t = 0; t < w; ++t)

@@ -423,6 +423,29 @@ def test_grouped_query_attention_16_bit(hd, heads, kv):
     assert rep.max_rel_logit_err <= 2e-2 and rep1.max_rel_logit_err <= 2e-2
 
 
+def test_weight_rescaling_keeps_small_rows_exact_16_bit():
+    """The library multiplies bf16 weights as fp16 operands after an exact power-of-two rescale per matrix.  Output
+    embedding rows spread over 18 binary orders of magnitude (the smallest far below fp16's normal range before the
+    rescale) must all give bigram scores as accurate as fp32 accumulation allows, relative to each row's own size."""
+    desc = dict(si.reduced_layers(si.MODELS["small"], 1), vocab=2048)
+    run = dict(si.RUNS["cfg2"], prompt_len=64, n_gen=4)
+    w = si.make_weights(desc, seed=8)
+    exps = np.random.default_rng(8).integers(-12, 7, desc["vocab"])
+    w["unemb"] = (w["unemb"] * (2.0 ** exps)[:, None]).astype(np.float32)          # exact: powers of two on bf16 values
+    ctx = ngg.Context(desc, w, max_seq=128, max_k=8, max_w=4)
+    prompt = si.make_prompt(run, desc["vocab"], seed=1)
+    ctx.prefill(prompt)
+    x_last = int(ctx.get_tokens()[-1])
+    ctx.build_drafts(run)
+    z, _ = ctx.debug_peek("z", np.float32)
+    ctx.close()
+    zo = oracle.bigram_scores(w["tok_emb"], w["unemb"], x_last)
+    row_size = np.linalg.norm(w["unemb"].astype(np.float64), axis=1) * np.linalg.norm(w["tok_emb"][x_last].astype(np.float64))
+    rel = np.abs(z - zo) / row_size
+    print("rescaled rows: max error relative to |u_v||e| =", rel.max(), "at exponent", exps[int(np.argmax(rel))])
+    assert rel.max() <= 1e-5
+
+
 def test_damped_residual_variant_accepts_bigram_rows():
     """W_o and W_down scaled by 1e-2: the embedding path dominates, so bigram rows
     are accepted (a labelled variant for coverage, not a headline configuration)."""
