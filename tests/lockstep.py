@@ -9,24 +9,10 @@ one near-tie cannot desynchronise the rest of the run).
 """
 from __future__ import annotations
 
-import os
-import time
-
 import numpy as np
 
 import oracle
 
-
-def progress_note(text):
-    """Appends a line to gpurun_out/test_progress.log: long oracle passes keep a file growing, so a
-    run that is merely busy on the host is not taken to be hung."""
-    try:
-        root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-        os.makedirs(os.path.join(root, "gpurun_out"), exist_ok=True)
-        with open(os.path.join(root, "gpurun_out", "test_progress.log"), "a") as f:
-            f.write(f"{time.strftime('%H:%M:%S')} {text}\n")
-    except OSError:
-        pass
 
 TOL = {"f32": 1e-4, "bf16": 2e-2}     # max abs logit error relative to the position's logit scale
 
@@ -88,8 +74,7 @@ def run(ctx, model, prompt, n_gen, cfg, tol, check_logits=True, injected=None, m
     rep = Report()
     bigram = bigram or oracle.Bigram(model.tok_emb, model.unemb)
     ctx.prefill(prompt)
-    st = oracle.prefill(model, prompt, chunk=oracle_chunk,
-                        progress=(lambda done: progress_note(f"oracle prefill {done}/{len(prompt)}")) if oracle_chunk else None)
+    st = oracle.prefill(model, prompt, chunk=oracle_chunk)
     g_first = int(ctx.get_tokens()[-1])
     _check_argmax(g_first, st.first_logits, tol, rep, "first token")
     st.tokens[-1] = g_first
@@ -108,7 +93,6 @@ def run(ctx, model, prompt, n_gen, cfg, tol, check_logits=True, injected=None, m
             res_g = ctx.verify_step(drafts, want_logits=check_logits)
         if on_step:
             on_step(rep.steps)
-        progress_note(f"lock-step step {rep.steps}: GPU done, oracle verify next")
         res_o = oracle.verify_step(model, st, drafts)
         k, w = drafts.shape
         if check_logits:
