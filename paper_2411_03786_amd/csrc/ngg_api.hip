@@ -152,7 +152,7 @@ ngg_status forward(ngg_ctx *c, int R, int C, int P, bool from_hist, int w, bool 
   {
     ProfScope ps(c, NGG_PROF_OTHER);
     launch_embed(dt, c->w.tok_emb, tok_src ? tok_src : c->hist, c->drafts, c->block_tok, c->h, d.d_model, M,
-                 tok_src ? 0 : P, from_hist ? 1 : 0, s);
+                 tok_src ? 0 : P, from_hist ? 1 : (shared0 ? 0 : 2), s);
   }
   const int n_splits = attention_splits(dt, d.head_dim, d.n_heads, M, P, c->max_splits);
   c->attn_layout[0] = n_splits; c->attn_layout[1] = attention_workgroups(dt, d.head_dim, d.n_heads, M, n_splits);

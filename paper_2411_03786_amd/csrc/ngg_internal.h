@@ -293,10 +293,11 @@ void launch_attention(int dtype, int hd, const AttnArgs &a, hipStream_t s);
 int attention_splits(int dtype, int hd, int H, int M, int P, int max_splits);
 int attention_workgroups(int dtype, int hd, int H, int M, int n_splits);   // workgroups the main attention kernel is launched with
 
-// from_hist: block token m is history token hist_base + m; otherwise the verify block in the shared-first-column
-// layout: token 0 is hist[hist_base], token m >= 1 is drafts[m - 1]
+// mode 1: block token m is history token hist_base + m; mode 0: the verify block in the shared-first-column
+// layout (token 0 is hist[hist_base], token m >= 1 is drafts[m - 1]); mode 2: a block of single-column rows (w = 0),
+// every token hist[hist_base]
 void launch_embed(int dtype, const void *tok_emb, const int32_t *hist, const int32_t *drafts, int32_t *block_tok,
-                  float *h, int d, int M, int hist_base, int from_hist, hipStream_t s);
+                  float *h, int d, int M, int hist_base, int mode, hipStream_t s);
 // h[m] += sum of n_part partials (hpart[s][m], stride part_stride floats between splits), then
 // xn[m] = rmsnorm(h[m]) * gain, written chunk-major
 // dst = (src - centre) * scale in the internal element type (src: the user's storage type)

@@ -15,9 +15,11 @@ namespace ngg {
 // ---------------------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void embed_kernel(const T *tok_emb, const int32_t *hist, const int32_t *drafts,
-                                                    int32_t *block_tok, float *h, int d, int hist_base, int from_hist) {
+                                                    int32_t *block_tok, float *h, int d, int hist_base, int mode) {
   const int m = blockIdx.x;
-  const int tok = from_hist ? hist[hist_base + m] : (m == 0 ? hist[hist_base] : drafts[m - 1]);
+  // mode 0: a verify block whose rows share token 0 (the last context token), then the drafts row by row;
+  // mode 1: consecutive history tokens; mode 2: single-column rows, every one the last context token
+  const int tok = mode == 1 ? hist[hist_base + m] : (m == 0 || mode == 2 ? hist[hist_base] : drafts[m - 1]);
   if (threadIdx.x == 0) block_tok[m] = tok;
   const T *e = tok_emb + (size_t)tok * d;
   for (int i = 4 * threadIdx.x; i < d; i += 1024) {         // d is a multiple of 32: four elements per load
@@ -33,13 +35,13 @@ __global__ __launch_bounds__(256) void embed_kernel(const T *tok_emb, const int3
 }
 
 void launch_embed(int dtype, const void *tok_emb, const int32_t *hist, const int32_t *drafts, int32_t *block_tok,
-                  float *h, int d, int M, int hist_base, int from_hist, hipStream_t s) {
+                  float *h, int d, int M, int hist_base, int mode, hipStream_t s) {
   if (dtype == 1)
     hipLaunchKernelGGL(embed_kernel<bf16_t>, dim3(M), dim3(256), 0, s, (const bf16_t *)tok_emb, hist, drafts, block_tok,
-                       h, d, hist_base, from_hist);
+                       h, d, hist_base, mode);
   else
     hipLaunchKernelGGL(embed_kernel<float>, dim3(M), dim3(256), 0, s, (const float *)tok_emb, hist, drafts, block_tok, h,
-                       d, hist_base, from_hist);
+                       d, hist_base, mode);
 }
 
 // ---------------------------------------------------------------------------------------------

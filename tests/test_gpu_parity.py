@@ -138,7 +138,7 @@ def test_bigram_scores_and_next1_table(tiny):
 
 
 # 1, 9, 112, 288, 6, 40, 65 and 96 block rows: GEMM row tiles of 1, 7, 8 (several passes), 3, 5 and 6 column blocks
-@pytest.mark.parametrize("k,w", [(1, 0), (1, 8), (16, 6), (32, 8), (3, 1), (8, 4), (13, 4), (12, 7)])
+@pytest.mark.parametrize("k,w", [(1, 0), (8, 0), (32, 0), (1, 8), (16, 6), (32, 8), (3, 1), (8, 4), (13, 4), (12, 7)])
 def test_block_shapes_including_more_than_64_rows(tiny, k, w):
     desc, run, _, prompt, model, ctx = tiny
     cfg = dict(k=k, w=w, k_ctx_max=k, q_min=1, q_max=3)
@@ -294,6 +294,48 @@ def test_adaptive_allocation_follows_the_oracle():
     assert st_fixed["alloc_hist"] == fixed["alloc_hist"]                      # back to the fixed rule
     assert st["alloc_hist"] != fixed["alloc_hist"] and st["ctx_rows"] < fixed["ctx_rows"]
     print("adaptive allocation:", st["alloc_hist"][:9], "fixed:", fixed["alloc_hist"][:9])
+
+
+def test_seeded_sweep_of_block_shapes_prompt_lengths_and_query_lengths(tiny):
+    """Forty seeded combinations of k, w, context-row cap, query back-off range and prompt length on the tiny fp32
+    model, two steps each, everything compared with the oracle (no tolerated disagreement in fp32)."""
+    desc, run, w, prompt0, model, ctx = tiny
+    rng = np.random.default_rng(2024)
+    for case in range(40):
+        k, wd = int(rng.integers(1, 33)), int(rng.integers(0, 9))
+        q_min = int(rng.integers(1, 4))
+        cfg = dict(k=k, w=wd, k_ctx_max=int(rng.integers(0, k + 1)), q_min=q_min, q_max=int(rng.integers(q_min, 5)))
+        n_prompt = int(rng.integers(1, 200))
+        prompt = si.prompt_spans(desc["vocab"], n_prompt, float(rng.uniform(0.1, 0.7)), seed=100 + case)
+        print("case", case, cfg, n_prompt, flush=True)
+        rep = lockstep_run(ctx, model, prompt, 2 * (wd + 1), cfg, TOL["f32"], max_steps=2)
+        assert rep.tolerated_argmax == 0 and rep.tolerated_draft == 0 and rep.max_rel_logit_err <= 1e-4, (case, cfg, n_prompt)
+
+
+def test_seeded_sweep_of_the_matcher_without_a_model():
+    """Two hundred seeded token streams (alphabet 2 .. 5000 symbols, 1 .. 4000 tokens, with and without copied
+    spans) x random (w, k_ctx_max, q_min, q_max): the context rows of the allocation-free entry point, which runs
+    the same matcher kernel on a caller's token buffer, against the oracle, exactly."""
+    import torch
+    rng = np.random.default_rng(77)
+    rows_total = 0
+    for case in range(200):
+        n = int(rng.integers(1, 4001))
+        vocab = int(rng.choice([2, 3, 7, 50, 512, 5000]))
+        x = (si.prompt_spans(vocab, n, float(rng.uniform(0.0, 0.8)), seed=500 + case) if rng.random() < 0.7
+             else rng.integers(0, vocab, n).astype(np.int32))
+        wd, kc = int(rng.integers(1, 33)), int(rng.integers(1, 33))
+        q0 = int(rng.integers(1, 5)); q1 = int(rng.integers(q0, 8))
+        t = torch.tensor(x, device="cuda")
+        rows = torch.full((kc, wd), -1, dtype=torch.int32, device="cuda")
+        n_rows = torch.zeros(1, dtype=torch.int32, device="cuda")
+        ngg.context_drafts_static(t, wd, kc, q0, q1, rows, n_rows)
+        torch.cuda.synchronize()
+        want = oracle.context_rows(x, wd, kc, q0, q1)
+        got = rows.cpu().numpy()[:int(n_rows.item())]
+        assert [tuple(int(v) for v in r) for r in got] == [tuple(r) for r in want], (case, n, vocab, wd, kc, q0, q1)
+        rows_total += len(want)
+    assert rows_total > 500
 
 
 def test_row_permutation_and_duplicate_rows(tiny):
@@ -597,7 +639,7 @@ def test_cfg2_small_bf16_lockstep():
     assert rep.tolerated_argmax <= 0.1 * positions
 
 
-@pytest.mark.parametrize("k,w", [(16, 6), (32, 8), (13, 4), (12, 7), (13, 9), (20, 7), (32, 7), (20, 14), (32, 32)])
+@pytest.mark.parametrize("k,w", [(16, 0), (16, 6), (32, 8), (13, 4), (12, 7), (13, 9), (20, 7), (32, 7), (20, 14), (32, 32)])
 def test_bf16_blocks_of_more_than_64_rows(k, w):
     """Blocks of 112, 288, 65 and 96 rows on the small 16-bit widths (3 layers): GEMM row tiles of 7, 8, 5
     and 6 column blocks and the attention workgroups with two query groups per wave; then the wide GEMM
