@@ -366,19 +366,23 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
 // Wide blocks (more than 128 rows; 16-bit types): one pass over W for up to 16*FM = 288 block rows.
 // Section 3's cost model has the call leave the memory-bound regime as k*(w+1) grows; with 128-row
 // tiles the skinny kernel re-streamed all of W for every further 128 rows, which put that transition
-// far below the chip's ops-to-bytes ratio.  Here a workgroup's four waves own FN different 16-row
-// fragments of W each (8 fragments = 128 rows of W per workgroup) and keep accumulators for ALL row
-// blocks of the tile (FN * FM fragments per wave), so a W fragment is loaded once from HBM and meets
-// every block row.  X is staged through LDS in slices of 64 contraction elements (two MFMA steps), double
-// buffered, and every wave reads all of it (LDS reads and MFMA issue are about balanced at FN = 2).
-// W goes from global memory straight into registers, 4 steps ahead, as in the skinny kernel.  No hand-over
-// between waves: each wave finishes its own fragments.  gridDim.y splits the contraction (residual only).
+// far below the chip's ops-to-bytes ratio.  Here a workgroup owns 2 FN fragments of W (64 or 128 rows) and
+// all row blocks of the tile; its four waves are laid out 2 x 2: a wave takes FN of the fragments and half
+// of the row blocks (FN * FM / 2 <= 36 accumulator fragments), so a W fragment is loaded once from HBM and
+// meets every block row.  X is staged through LDS in slices of 64 contraction elements (two MFMA steps),
+// double buffered; a wave reads only its half of the rows from LDS (with the four waves side by side along
+// W every wave read all of X, and the LDS reads cost as much as the MFMAs: 10-20 % slower at 130-290 rows).
+// W goes from global memory straight into registers, 4 steps ahead, as in the skinny kernel; the two waves
+// that share a fragment both load it (the second request is served by the L2).  No hand-over between waves:
+// each wave finishes its own accumulators.  gridDim.y splits the contraction (residual only).
 // ---------------------------------------------------------------------------------------------
 template <typename T, int EPI, int FM, int FN>
 __global__ __launch_bounds__(256) void gemm_wide_kernel(const GemmArgs a) {
   static_assert(sizeof(T) == 2, "16-bit operands only");
   constexpr bool PAIRED = EPI == EPI_QKV || EPI == EPI_GATEUP;
-  static_assert(PAIRED || FN == 2, "unembedding partials are indexed by pairs of fragments");
+  static_assert(PAIRED || FN % 2 == 0, "unembedding partials are indexed by pairs of fragments");
+  static_assert(FM % 2 == 0, "the waves are laid out 2 x 2 over (row blocks, fragments)");
+  constexpr int FMW = FM / 2;                // row blocks per wave
   constexpr int KC = KChunk<T>::value;       // chunk of the activation layout (256)
   constexpr int KW = 64;                     // contraction elements staged per slice: two steps
   constexpr int SPS = KW / 32;               // steps per slice
@@ -393,6 +397,7 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(const GemmArgs a) {
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int li = lane & 15, g = lane >> 4;
+  const int wn = wave & 1, wm = wave >> 1;   // this wave: fragments wn * FN .. of the workgroup's 2 FN, row blocks wm * FMW ..
   const int K = a.K, M = a.M;
   const int n_frags = a.n_groups;            // 16-row fragments of W (the launcher fills it)
   const int n_steps = K / 32;
@@ -405,7 +410,7 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(const GemmArgs a) {
   bool frag_live[FN];
 #pragma unroll
   for (int f = 0; f < FN; ++f) {
-    int frag = (blockIdx.x * 4 + wave) * FN + f;
+    int frag = (blockIdx.x * 2 + wn) * FN + f;
     frag_live[f] = frag < n_frags;
     if (!frag_live[f]) frag = n_frags - 1;   // repeats a fragment it does not store
     fragi[f] = frag;
@@ -448,11 +453,11 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(const GemmArgs a) {
       for (int i = 0; i < PIECES; ++i) *reinterpret_cast<u32x4 *>(xs + (size_t)buf * ROWS * LDX + xdst[i]) = st[i];
     };
 
-    f32x4 acc[FN][FM];
+    f32x4 acc[FN][FMW];
 #pragma unroll
     for (int f = 0; f < FN; ++f)
 #pragma unroll
-      for (int fm = 0; fm < FM; ++fm) acc[f][fm] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int fm = 0; fm < FMW; ++fm) acc[f][fm] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     Frag<T> ring[RING][FN];
     auto load_w = [&](Frag<T> (&slot)[FN], int t) {         // wave-step t >= 0 is global step c0 * SPS + t (clamped)
@@ -472,13 +477,13 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(const GemmArgs a) {
         if (!warm) stage_store(stage[cc], cc);
         __syncthreads();
         stage_load(stage[cc], max(sl + 2, c0));
-        const T *xb = xs + (size_t)cc * ROWS * LDX + li * LDX + g * 8;
+        const T *xb = xs + (size_t)cc * ROWS * LDX + (wm * FMW * 16 + li) * LDX + g * 8;
 #pragma unroll
         for (int i = 0; i < SPS; ++i) {
           const int slot = cc * SPS + i;
           if (!warm && sl < c1 && sl * SPS + i < n_steps) {   // uniform per workgroup
 #pragma unroll
-            for (int fm = 0; fm < FM; ++fm) {
+            for (int fm = 0; fm < FMW; ++fm) {
               const Frag<T> xf = load_frag(xb + fm * 16 * LDX + i * 32);
 #pragma unroll
               for (int f = 0; f < FN; ++f) mma(acc[f][fm], ring[slot][f], xf);
@@ -494,11 +499,12 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(const GemmArgs a) {
     __syncthreads();
 
 #pragma unroll
-    for (int fm = 0; fm < FM; ++fm) {
-      const int m = m0 + fm * 16 + li;
+    for (int fm = 0; fm < FMW; ++fm) {
+      const int row = (wm * FMW + fm) * 16 + li;             // row of the tile
+      const int m = m0 + row;
       const bool live = m < M;
       if constexpr (PAIRED) {
-        const float rs = rs_lds[fm * 16 + li];
+        const float rs = rs_lds[row];
 #pragma unroll
         for (int f = 0; f < FN; ++f)
           if (frag_live[f]) epi_paired<T, EPI>(a, fragi[f], m, M, g, rs, acc[f][fm]);     // uniform per wave
@@ -507,23 +513,24 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(const GemmArgs a) {
         for (int f = 0; f < FN; ++f)
           if (live && frag_live[f]) epi_residual(a, ks, m, fragi[f] * 16, g, acc[f][fm]);
       } else {
-        if (frag_live[0]) {                                  // a pair of fragments is live or not as a whole (N % 32 == 0)
-          int nbase[FN];
-          f32x4 sums[FN];
 #pragma unroll
-          for (int f = 0; f < FN; ++f) { nbase[f] = fragi[f] * 16; sums[f] = acc[f][fm]; }
-          epi_unembed<FN>(a, fragi[0] / FN, m, live, g, rs_lds[fm * 16 + li], nbase, sums);
-        }
+        for (int f = 0; f < FN; f += 2)
+          if (frag_live[f]) {                                // a pair of fragments is live or not as a whole (N % 32 == 0)
+            const int nbase[2] = {fragi[f] * 16, fragi[f + 1] * 16};
+            const f32x4 sums[2] = {acc[f][fm], acc[f + 1][fm]};
+            epi_unembed<2>(a, fragi[f] / 2, m, live, g, rs_lds[row], nbase, sums);
+          }
       }
     }
     __syncthreads();                                         // LDS is reused by the next tile
   }
 }
 
+// FN: fragments per wave; a workgroup owns 2 FN
 template <typename T, int EPI, int FM, int FN>
 static void launch_wide_cfg(const GemmArgs &a, int KS, hipStream_t s) {
   const size_t lds = (size_t)2 * 16 * FM * (64 + 8) * sizeof(T);
-  const int blocks = (a.n_groups + 4 * FN - 1) / (4 * FN);
+  const int blocks = (a.n_groups + 2 * FN - 1) / (2 * FN);
   if (lds > 64 * 1024) {
     static const hipError_t opted = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_wide_kernel<T, EPI, FM, FN>),
                                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -537,18 +544,17 @@ static void launch_wide_fm(const GemmArgs &a_in, int KS, hipStream_t s) {
   GemmArgs a = a_in;
   a.n_groups = a.N / 16 * ((EPI == EPI_GATEUP) ? 2 : 1);     // fragments: gate/up interleaves 2 * d_ffn rows
   if (EPI == EPI_QKV) a.n_groups = (a.H + 2 * a.Hkv) * (a.hd / 16);
-  // Two fragments per wave (128 rows of W per workgroup) where that still gives most CUs a workgroup, one
+  // 128 rows of W per workgroup (four fragments per wave) where that still gives most CUs a workgroup, 64
   // otherwise (q/k/v of a 4096-wide model has 768 fragments: 96 workgroups against 192): every workgroup reads
-  // all of X whatever it owns, so the W rows per workgroup only matter once the chip is full.
-  // (q/k/v tiles of 16 and 18 row blocks always take one: with two, the unrolled rotary epilogue over 36
-  // accumulator fragments no longer fits the registers)
-  if constexpr (EPI == EPI_QKV && FM >= 16) {
-    launch_wide_cfg<T, EPI, FM, 1>(a, KS, s);
-  } else {
-    if constexpr (EPI == EPI_QKV || EPI == EPI_GATEUP) {
-      if ((a.n_groups + 7) / 8 * KS < 160) { launch_wide_cfg<T, EPI, FM, 1>(a, KS, s); return; }
-    }
+  // all of X whatever it owns, so the W rows per workgroup only matter once the chip is full.  q/k/v always
+  // takes 64: the unrolled rotary epilogue over more accumulator fragments does not fit the registers.
+  if constexpr (EPI == EPI_QKV) {
     launch_wide_cfg<T, EPI, FM, 2>(a, KS, s);
+  } else {
+    if constexpr (EPI == EPI_GATEUP) {
+      if ((a.n_groups + 7) / 8 * KS < 160) { launch_wide_cfg<T, EPI, FM, 2>(a, KS, s); return; }
+    }
+    launch_wide_cfg<T, EPI, FM, 4>(a, KS, s);
   }
 }
 
