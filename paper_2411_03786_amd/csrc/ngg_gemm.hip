@@ -476,19 +476,33 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(const GemmArgs a) {
         const int sl = c0 + ci + cc;                         // slice of this half trip
         if (!warm) stage_store(stage[cc], cc);
         __syncthreads();
-        stage_load(stage[cc], max(sl + 2, c0));
         const T *xb = xs + (size_t)cc * ROWS * LDX + (wm * FMW * 16 + li) * LDX + g * 8;
+        // All X fragments of a step are read from LDS in one go: those of the slice's first step right behind
+        // the barrier (the global loads of the next slices are issued while they are on their way), those of
+        // the second step before the first step's MFMAs.  The scheduling barriers keep that order (left alone,
+        // the compiler fetched one fragment at a time and waited for each between the MFMAs).
+        const bool live = !warm && sl < c1;                  // uniform per workgroup
+        Frag<T> xf[SPS][FMW];
+#pragma unroll
+        for (int fm = 0; fm < FMW; ++fm) xf[0][fm] = load_frag(xb + fm * 16 * LDX);
+        __builtin_amdgcn_sched_barrier(0);
+        stage_load(stage[cc], max(sl + 2, c0));
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < SPS; ++i) {
           const int slot = cc * SPS + i;
-          if (!warm && sl < c1 && sl * SPS + i < n_steps) {   // uniform per workgroup
+          if (i + 1 < SPS) {
 #pragma unroll
-            for (int fm = 0; fm < FMW; ++fm) {
-              const Frag<T> xf = load_frag(xb + fm * 16 * LDX + i * 32);
-#pragma unroll
-              for (int f = 0; f < FN; ++f) mma(acc[f][fm], ring[slot][f], xf);
-            }
+            for (int fm = 0; fm < FMW; ++fm) xf[i + 1][fm] = load_frag(xb + fm * 16 * LDX + (i + 1) * 32);
           }
+          __builtin_amdgcn_sched_barrier(0);
+          if (live && sl * SPS + i < n_steps) {
+#pragma unroll
+            for (int fm = 0; fm < FMW; ++fm)
+#pragma unroll
+              for (int f = 0; f < FN; ++f) mma(acc[f][fm], ring[slot][f], xf[i][fm]);
+          }
+          __builtin_amdgcn_sched_barrier(0);
           load_w(ring[slot], max((ci + cc) * SPS + i + RING, 0));
         }
       }
