@@ -21,77 +21,101 @@
 namespace ngg {
 
 // Softmax arithmetic: the fp32 configuration uses expf on scores scaled by 1/sqrt(hd); the 16-bit
-// configuration keeps scores, running maxima and the stored partial maxima in the base-2 domain
-// (scores times log2(e)/sqrt(hd)) so that each probability is one subtraction and one v_exp_f32.
-// There the probabilities are computed as 2^(s - max + 10): the factor 2^10 is carried by the running
+// configuration keeps scores, reference maxima and the stored partial maxima in the base-2 domain
+// (scores times log2(e)/sqrt(hd)) so that each probability is one fused multiply-add and one v_exp_f32.
+// There the probabilities are computed as 2^(s - ref + 10): the factor 2^10 is carried by the running
 // sums and by the output alike and cancels in their quotient; it keeps probabilities down to 2^-24 of
-// the row maximum in fp16's normal range (an fp16 matrix operand below 2^-14 may be flushed to zero,
+// the reference in fp16's normal range (an fp16 matrix operand below 2^-14 may be flushed to zero,
 // and thousands of such keys can add up to a visible share of a long context's softmax).
+//
+// The reference of a query is a maximum of its scores so far, brought up to date only when a tile holds a
+// score more than `lazy` above it: softmax is invariant under the choice of reference as long as sums and
+// output use the same one, so most tiles skip the cross-lane maximum, the rescaling factor and the rescaling
+// of the output (16-bit: probabilities stay below 2^15; fp32: lazy = 0, the reference is the running maximum).
 template <typename T> struct Softmax;
 template <> struct Softmax<float> {
+  static constexpr float lazy = 0.0f;
   static __device__ __forceinline__ float factor(float scale) { return scale; }
   static __device__ __forceinline__ float ex(float x) { return expf(x); }
-  static __device__ __forceinline__ float prob(float x) { return expf(x); }
+  static __device__ __forceinline__ float bias(float ref) { return -ref; }
+  static __device__ __forceinline__ float prob(float raw, float sfac, float bias) { return expf(fmaf(raw, sfac, bias)); }
 };
 template <> struct Softmax<half_t> {
+  static constexpr float lazy = 5.0f;
   static __device__ __forceinline__ float factor(float scale) { return scale * 1.44269504088896f; }
   static __device__ __forceinline__ float ex(float x) { return __builtin_amdgcn_exp2f(x); }
-  static __device__ __forceinline__ float prob(float x) { return __builtin_amdgcn_exp2f(x + 10.0f); }
+  static __device__ __forceinline__ float bias(float ref) { return 10.0f - ref; }
+  static __device__ __forceinline__ float prob(float raw, float sfac, float bias) { return __builtin_amdgcn_exp2f(fmaf(raw, sfac, bias)); }
 };
 
-// One 16-query fragment against one 32-key tile, after the scores: online softmax and P.V.
-// Sc: transposed scores (fragment f's row i is key 8*(i/4) + 4f + (i%4) of the tile, so this lane
+// Probabilities are at most 2^15: no saturation needed on the way to fp16
+__device__ __forceinline__ void pack_probs(Frag<half_t> &f, const float *p) {
+#pragma unroll
+  for (int e = 0; e < 8; ++e) f.v[e] = (half_t)p[e];
+}
+__device__ __forceinline__ void pack_probs(Frag<float> &f, const float *p) { pack_frag(f, p); }
+
+// One 16-query fragment against one 32-key tile, after the scores: the softmax part.  Returns the
+// probabilities as the P operand of P.V, updates the query's reference maximum mref (the same in the four
+// lanes of a query), this lane's share lsum of the running sum (the four lanes are added up once, at the end)
+// and, when the reference moves, rescales the output so far.
+// Sc: transposed raw scores (fragment f's row i is key 8*(i/4) + 4f + (i%4) of the tile, so this lane
 // holds the 8 consecutive keys k0 .. k0+7 of its query); keys outside [lo, hi] are masked (except key 0
 // when key0 is set: the block token every row shares) unless the whole tile is visible to every query (full).
-template <typename T, int DF, typename VFrag>
-__device__ __forceinline__ void softmax_pv(const f32x4 (&Sc)[2], float sfac, bool full, int k0, int lo, int hi, bool key0,
-                                           float &mrun, float &lrun, f32x4 (&O)[DF], VFrag vfrag) {
-  float sv[8], p[8];
-  float mx = kNegBig, ps = 0.0f;
+template <typename T, int DF>
+__device__ __forceinline__ Frag<T> softmax_tile(const f32x4 (&Sc)[2], float sfac, bool full, int k0, int lo, int hi, bool key0,
+                                                float &mref, float &lsum, f32x4 (&O)[DF]) {
+  float raw[8], p[8];
+  unsigned vis = 0xffu;                                     // bit e: key k0 + e is visible to this lane's query
+  float mx = kNegBig;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) raw[e] = Sc[e >> 2][e & 3];
   if (full) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      sv[e] = Sc[e >> 2][e & 3] * sfac;
-      mx = fmaxf(mx, sv[e]);
-    }
+    for (int e = 0; e < 8; ++e) mx = fmaxf(mx, raw[e]);
   } else {
+    vis = 0;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      const bool vis = (k0 + e >= lo && k0 + e <= hi) || (key0 && k0 + e == 0);
-      sv[e] = vis ? Sc[e >> 2][e & 3] * sfac : kNegBig;
-      mx = fmaxf(mx, sv[e]);
+      const bool v = (k0 + e >= lo && k0 + e <= hi) || (key0 && k0 + e == 0);
+      vis |= v ? 1u << e : 0u;
+      mx = fmaxf(mx, v ? raw[e] : kNegBig);
     }
   }
-  const float mnew = fmaxf(mrun, rows_max(mx));
-  const float alpha = Softmax<T>::ex(mrun - mnew);
+  mx = mx > 0.5f * kNegBig ? mx * sfac : kNegBig;           // sfac > 0: the maximum commutes with the scaling
+  if (__ballot(mx > mref + Softmax<T>::lazy) != 0) {        // uniform; always taken on a query's first visible key
+    const float mnew = fmaxf(mref, rows_max(mx));
+    const float alpha = Softmax<T>::ex(mref - mnew);
+    lsum *= alpha;
+    // the output so far needs rescaling only if some query's reference moved, and not on the first
+    // tile (the output is still zero)
+    if (__ballot(mnew != mref && mref > 0.5f * kNegBig) != 0) {
+#pragma unroll
+      for (int df = 0; df < DF; ++df)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) O[df][r] *= alpha;
+    }
+    mref = mnew;
+  }
+  const float bias = Softmax<T>::bias(mref);
+  float ps = 0.0f;
   if (full) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      p[e] = Softmax<T>::prob(sv[e] - mnew);
+      p[e] = Softmax<T>::prob(raw[e], sfac, bias);
       ps += p[e];
     }
   } else {
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      p[e] = sv[e] > 0.5f * kNegBig ? Softmax<T>::prob(sv[e] - mnew) : 0.0f;
+      p[e] = (vis >> e & 1u) ? Softmax<T>::prob(raw[e], sfac, bias) : 0.0f;
       ps += p[e];
     }
   }
-  lrun = lrun * alpha + rows_sum(ps);
-  // the output so far needs rescaling only if some query's maximum moved, and not on the first
-  // tile (the output is still zero); the maxima settle after a few tiles
-  const bool rescale = __ballot(mnew != mrun && mrun > 0.5f * kNegBig) != 0;
-  mrun = mnew;
+  lsum += ps;
   Frag<T> Pf;
-  pack_frag(Pf, p);
-  if (rescale) {
-#pragma unroll
-    for (int df = 0; df < DF; ++df)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) O[df][r] *= alpha;
-  }
-#pragma unroll
-  for (int df = 0; df < DF; ++df) mma(O[df], vfrag(df), Pf);
+  pack_probs(Pf, p);
+  return Pf;
 }
 
 // One workgroup = 4 waves that take the tiles of one (head, list slice) round-robin, each against
@@ -197,8 +221,10 @@ __global__ __launch_bounds__(256) void attn_stream_kernel(const AttnArgs a, int 
 #pragma unroll
         for (int j = 0; j < QG; ++j) {
           const int qf = q2 + j;
-          softmax_pv<T, DF>(Sc[j], sfac, full, k0, own ? qlo[qf] : 0, own ? qhi[qf] : P - 1, own && a.shared0, mrun[qf],
-                            lrun[qf], O[qf], [&](int df) { return vr[df]; });
+          const Frag<T> Pf = softmax_tile<T, DF>(Sc[j], sfac, full, k0, own ? qlo[qf] : 0, own ? qhi[qf] : P - 1,
+                                                 own && a.shared0, mrun[qf], lrun[qf], O[qf]);
+#pragma unroll
+          for (int df = 0; df < DF; ++df) mma(O[qf][df], vr[df], Pf);
         }
       }
     }
@@ -263,6 +289,7 @@ __global__ __launch_bounds__(256) void attn_stream_kernel(const AttnArgs a, int 
 #pragma unroll
       for (int r = 0; r < 4; ++r) o[r] += red[((size_t)w * DUMP + item * 4 + r) * 64 + lane] * wgt;
     }
+    l = rows_sum(l);                                        // the four lanes of a query each held a share of its sum
     // partial outputs keep the fragment order, [head][slice][16-query group][df][lane][4]: one store
     // instruction of the wave writes 1 KB contiguously
     const size_t blk = ((size_t)h * S + split) * (a.Mcap / 16) + (q0 / 16 + qf);
@@ -277,8 +304,8 @@ __global__ __launch_bounds__(256) void attn_stream_kernel(const AttnArgs a, int 
 
 // Workgroup = (head, list slice, group of 64*QF queries); wave w owns queries q0 + 16*QF*w .. and
 // reads every tile of the slice from the LDS copy.  Grid layout as in attn_stream_kernel.
-template <typename T, int HD, int QF>
-__global__ __launch_bounds__(256) void attn_shared_kernel(const AttnArgs a, int Z, int n_units) {
+template <typename T, int HD, int QF, bool NT>
+__global__ __launch_bounds__(256, 2) void attn_shared_kernel(const AttnArgs a, int Z, int n_units) {
   constexpr int DS = HD / 32, DF = HD / 16;
   constexpr int TILE = 32 * HD;
   constexpr int GQ = 64 * QF;                               // queries per workgroup
@@ -312,8 +339,10 @@ __global__ __launch_bounds__(256) void attn_shared_kernel(const AttnArgs a, int 
   const T *kc = (const T *)a.kcache + (size_t)hkv * a.Spad * HD, *vc = (const T *)a.vcache + (size_t)hkv * a.Spad * HD;
   const T *ksc = (const T *)a.kscr + (size_t)hkv * a.Mcap * HD, *vsc = (const T *)a.vscr + (size_t)hkv * a.Mcap * HD;
 
-  // two register stages: the tile after next is on its way while the current one is used
-  u32x4 kst[2][PPT], vst[2][PPT];
+  // DEPTH register stages: tile t + DEPTH is requested when tile t is used (four stages measured slower than
+  // two, at a 16K context and at 2K).  NT: the tiles are read with non-temporal loads (the launcher's choice).
+  constexpr int DEPTH = 2;
+  u32x4 kst[DEPTH][PPT], vst[DEPTH][PPT];
   auto stage_load = [&](u32x4 (&kr)[PPT], u32x4 (&vr)[PPT], int t) {
     const int ct = max(min(t_begin + t, t_end - 1), 0);     // clamped into the list: loads are unconditional
     const bool own = ct >= NP;
@@ -322,8 +351,10 @@ __global__ __launch_bounds__(256) void attn_shared_kernel(const AttnArgs a, int 
 #pragma unroll
     for (int i = 0; i < PPT; ++i) {
       const int pc = min(tid + 256 * i, PIECES - 1);        // surplus threads repeat the last piece
-      kr[i] = *reinterpret_cast<const u32x4 *>(kp + (size_t)pc * (16 / sizeof(T)));
-      vr[i] = *reinterpret_cast<const u32x4 *>(vp + (size_t)pc * (16 / sizeof(T)));
+      const u32x4 *ksrc = reinterpret_cast<const u32x4 *>(kp + (size_t)pc * (16 / sizeof(T)));
+      const u32x4 *vsrc = reinterpret_cast<const u32x4 *>(vp + (size_t)pc * (16 / sizeof(T)));
+      if constexpr (NT) { kr[i] = __builtin_nontemporal_load(ksrc); vr[i] = __builtin_nontemporal_load(vsrc); }
+      else              { kr[i] = *ksrc; vr[i] = *vsrc; }
     }
   };
   auto stage_store = [&](const u32x4 (&kr)[PPT], const u32x4 (&vr)[PPT], int buf) {
@@ -334,8 +365,8 @@ __global__ __launch_bounds__(256) void attn_shared_kernel(const AttnArgs a, int 
       *reinterpret_cast<u32x4 *>(vl + (size_t)buf * TILE + (size_t)pc * (16 / sizeof(T))) = vr[i];
     }
   };
-  stage_load(kst[0], vst[0], 0);
-  stage_load(kst[1], vst[1], 1);
+#pragma unroll
+  for (int u = 0; u < DEPTH; ++u) stage_load(kst[u], vst[u], u);
 
   // this lane's queries (result columns), one per group of 16: visible block keys are [qlo, qhi]
   int qlo[QF], qhi[QF];
@@ -378,22 +409,32 @@ __global__ __launch_bounds__(256) void attn_shared_kernel(const AttnArgs a, int 
 #pragma unroll
           for (int qf = 0; qf < QF; ++qf) mma(Sc[qf][f], kfrag, Q[qf][ds]);
         }
+      Frag<T> Pf[QF];
 #pragma unroll
       for (int qf = 0; qf < QF; ++qf)
-        softmax_pv<T, DF>(Sc[qf], sfac, full, k0, own ? qlo[qf] : 0, own ? qhi[qf] : P - 1, own && a.shared0, mrun[qf],
-                          lrun[qf], O[qf], [&](int df) { return load_frag_tiled(vt + df * 512); });
+        Pf[qf] = softmax_tile<T, DF>(Sc[qf], sfac, full, k0, own ? qlo[qf] : 0, own ? qhi[qf] : P - 1, own && a.shared0,
+                                     mrun[qf], lrun[qf], O[qf]);
+#pragma unroll
+      for (int df = 0; df < DF; ++df) {                     // every value fragment is read from LDS once for all query groups
+        const Frag<T> vfrag = load_frag_tiled(vt + df * 512);
+#pragma unroll
+        for (int qf = 0; qf < QF; ++qf) mma(O[qf][df], vfrag, Pf[qf]);
+      }
     }
   };
 
-  for (int t = 0; t < n_tiles; t += 2) {                    // barriers are uniform; the odd tail only loads
-    stage_store(kst[0], vst[0], 0);
-    __syncthreads();
-    stage_load(kst[0], vst[0], t + 2);
-    compute(t, 0);
-    stage_store(kst[1], vst[1], 1);
-    __syncthreads();
-    stage_load(kst[1], vst[1], t + 3);
-    compute(t + 1, 1);
+  // The query fragments must have landed before the loop: left pending, the compiler guards their first use
+  // inside the loop body with a count that in later trips also waits for the tile requested one trip earlier,
+  // and the loop runs one tile deep, at the memory latency (the first tile is needed right away anyway).
+  __builtin_amdgcn_s_waitcnt(0x0F70);                       // vmcnt(0)
+  for (int t = 0; t < n_tiles; t += DEPTH) {                // barriers are uniform; the tail of a round only loads
+#pragma unroll
+    for (int u = 0; u < DEPTH; ++u) {
+      stage_store(kst[u], vst[u], u & 1);
+      __syncthreads();
+      stage_load(kst[u], vst[u], t + u + DEPTH);
+      compute(t + u, u & 1);
+    }
   }
 
   if (active) {
@@ -406,10 +447,11 @@ __global__ __launch_bounds__(256) void attn_shared_kernel(const AttnArgs a, int 
         *reinterpret_cast<float4 *>(a.part_o + ((blk * DF + df) * 64 + lane) * 4) =
             float4{O[qf][df][0], O[qf][df][1], O[qf][df][2], O[qf][df][3]};
       const int m = qw + qf * 16 + li;
+      const float l = rows_sum(lrun[qf]);                   // the four lanes of a query each held a share of its sum
       if (m < M && g == 0) {
         const size_t slot = ((size_t)h * S + split) * a.Mcap + m;
         a.part_ml[slot * 2 + 0] = mrun[qf];
-        a.part_ml[slot * 2 + 1] = lrun[qf];
+        a.part_ml[slot * 2 + 1] = l;
       }
     }
   }
@@ -480,7 +522,13 @@ static void launch_shared(const AttnArgs &a, hipStream_t s) {
   const size_t lds = (size_t)4 * 32 * HD * sizeof(T);
   const int Z = (a.M + 64 * QF - 1) / (64 * QF);
   const int n_units = a.n_splits * a.H;
-  hipLaunchKernelGGL((attn_shared_kernel<T, HD, QF>), dim3((n_units + 7) / 8 * 8 * Z), dim3(256), lds, s, a, Z, n_units);
+  // Slices of a dozen tiles or more that no other workgroup shares are read with non-temporal loads (measured on
+  // MI355X, whole verify step: 7.07 -> 6.86 ms at a 16.4K context with 32 tiles per slice, 3.08 -> 3.06 ms at 13
+  // tiles; 4.18 -> 4.19 ms at 8 tiles, where they stay ordinary loads)
+  const int tiles = ((a.P + 31) / 32 + 1) / a.n_splits;
+  const bool nt = Z == 1 && tiles >= 12;
+  if (nt) hipLaunchKernelGGL((attn_shared_kernel<T, HD, QF, true>), dim3((n_units + 7) / 8 * 8 * Z), dim3(256), lds, s, a, Z, n_units);
+  else hipLaunchKernelGGL((attn_shared_kernel<T, HD, QF, false>), dim3((n_units + 7) / 8 * 8 * Z), dim3(256), lds, s, a, Z, n_units);
 }
 
 template <typename T, int HD>
