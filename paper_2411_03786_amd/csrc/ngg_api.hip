@@ -242,10 +242,12 @@ ngg_status ensure_logits(ngg_ctx *c) {
 
 ngg_status build_next1(ngg_ctx *c) {
   // next1[x] = argmax_v <unemb[v], tok_emb[x]>: the unembedding GEMM applied to rows of the input
-  // embedding (no normalisation), 64 vocabulary entries per pass.
+  // embedding (no normalisation), 256 vocabulary entries per pass over the output embedding (16-bit models: one
+  // pass of the wide kernel; with 64 per pass a 128K vocabulary cost 2004 sweeps of 788 MB) or 64 (fp32).
   const ngg_model_desc &d = c->d;
-  for (int x0 = 0; x0 < d.vocab; x0 += 64) {
-    const int M = std::min(64, d.vocab - x0);
+  const int rows = d.dtype == NGG_BF16 ? 256 : 64;       // Mcap >= 256
+  for (int x0 = 0; x0 < d.vocab; x0 += rows) {
+    const int M = std::min(rows, d.vocab - x0);
     launch_pack_rows(d.dtype, (const char *)c->w.tok_emb + (size_t)x0 * d.d_model * c->esize, c->xn, d.d_model, M, c->Mcap,
                      c->stream, c->emb_scale);
     GemmArgs g{};
