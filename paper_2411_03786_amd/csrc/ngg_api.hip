@@ -3,6 +3,7 @@
 #include "ngg.h"
 #include "ngg_internal.h"
 
+#include <algorithm>
 #include <chrono>
 #include <cmath>
 #include <cstdarg>
@@ -24,7 +25,10 @@ static __device__ __align__(256) int32_t scratch[kStaticInts];
 
 namespace {
 
-constexpr int kPrefillChunk = 256;   // prompt tokens per forward pass of ngg_prefill: one pass of the wide GEMM kernel (fp32: two 128-row tiles)
+// Prompt tokens per forward pass of ngg_prefill.  16-bit models: up to 2048, which the wide GEMM kernel takes as
+// row tiles of 256 that share the weights through the L2 (one sweep of the weights from HBM per 2048 tokens instead
+// of per 256); fp32 models: 256 (two 128-row passes of the skinny kernel).
+constexpr int kPrefillChunk16 = 2048, kPrefillChunk32 = 256;
 thread_local std::string g_create_error = "";
 
 struct ProfSpan { int cls; hipEvent_t e0, e1; };
@@ -38,6 +42,8 @@ struct ngg_ctx {
   hipStream_t stream = nullptr;
   int esize = 2;          // bytes per weight / KV element
   int Spad = 0, Mcap = 0, max_splits = 0, unembed_tiles = 0;
+  int prefill_chunk = 0;           // prompt tokens per forward pass of ngg_prefill
+  size_t part_rows = 0;            // rows (slices x block rows rounded to 128) the attention partial buffers hold per head
   // device buffers
   int32_t *hist = nullptr, *drafts = nullptr, *block_tok = nullptr, *res = nullptr, *next1 = nullptr;
   int32_t *mlist = nullptr, *reps = nullptr, *gtab = nullptr, *ctx_rows = nullptr, *n_ctx = nullptr;
@@ -157,6 +163,9 @@ ngg_status forward(ngg_ctx *c, int R, int C, int P, bool from_hist, int w, bool 
   const int n_splits = attention_splits(dt, d.head_dim, d.n_heads, M, P, c->max_splits);
   c->attn_layout[0] = n_splits; c->attn_layout[1] = attention_workgroups(dt, d.head_dim, d.n_heads, M, n_splits);
   c->attn_layout[2] = M; c->attn_layout[3] = P;
+  const int Mpart = (M + 127) / 128 * 128;
+  if ((size_t)n_splits * Mpart > c->part_rows)
+    return fail(c, NGG_ECAPACITY, "attention partials: %d slices of %d rows exceed the %zu rows allocated", n_splits, Mpart, c->part_rows);
   const size_t part_stride = (size_t)c->Mcap * d.d_model;
   const int ks_o = gemm_residual_splits(dt, M, d.d_model, dq), ks_down = gemm_residual_splits(dt, M, d.d_model, d.d_ffn);
   const int ss_segs = rmsnorm_segments(d.d_model);
@@ -188,7 +197,7 @@ ngg_status forward(ngg_ctx *c, int R, int C, int P, bool from_hist, int w, bool 
       a.kscr = kscr_l; a.vscr = vscr_l;
       a.part_o = c->part_o; a.part_ml = c->part_ml; a.out = c->attn;
       a.H = d.n_heads; a.Hkv = d.n_kv_heads; a.Mcap = c->Mcap; a.Spad = c->Spad; a.M = M; a.C = C; a.P = P;
-      a.n_splits = n_splits; a.shared0 = shared0;
+      a.n_splits = n_splits; a.shared0 = shared0; a.Mpart = Mpart;
       a.scale = 1.0f / std::sqrt((float)d.head_dim);
       launch_attention(dt, d.head_dim, a, s);
     }
@@ -401,7 +410,8 @@ ngg_status ngg_create(const ngg_model_desc *desc, const ngg_weights *weights, vo
   c->esize = d.dtype == NGG_BF16 ? 2 : 4;
   c->Spad = (int)rup((size_t)d.max_seq + 1, 32);
   // whole GEMM row tiles: 64 rows, or 128-row tiles once a block has more than 64 rows
-  c->Mcap = (int)rup((size_t)std::max(d.max_k * (d.max_w + 1), kPrefillChunk), 64);
+  c->prefill_chunk = d.dtype == NGG_BF16 ? std::min(kPrefillChunk16, (int)rup((size_t)d.max_seq, 256)) : kPrefillChunk32;
+  c->Mcap = (int)rup((size_t)std::max(d.max_k * (d.max_w + 1), c->prefill_chunk), 64);
   if (c->Mcap > 64) c->Mcap = (int)rup((size_t)c->Mcap, 128);
   c->max_splits = 32;
   c->unembed_tiles = d.vocab / 32;
@@ -434,8 +444,11 @@ ngg_status ngg_create(const ngg_model_desc *desc, const ngg_weights *weights, vo
   TRY(dev_alloc(c, &c->q, (size_t)c->Mcap * dq * c->esize, true));
   TRY(dev_alloc(c, &c->attn, act_elems(d.dtype, c->Mcap, dq) * c->esize, true));
   TRY(dev_alloc(c, &c->act, act_elems(d.dtype, c->Mcap, d.d_ffn) * c->esize, true));
-  TRY(dev_alloc(c, &c->part_o, (size_t)d.n_heads * (c->max_splits + 1) * c->Mcap * d.head_dim * 4, true));
-  TRY(dev_alloc(c, &c->part_ml, (size_t)d.n_heads * (c->max_splits + 1) * c->Mcap * 2 * 4, true));
+  // attention partials, [head][slice][rows]: slices x rows is at most 32 x 128 for blocks of up to 64 tokens, and
+  // (two workgroups per CU) x 128 rows per workgroup, shared among the heads, above that (attention_splits)
+  c->part_rows = std::max({(size_t)(c->Mcap + 127) / 128 * 128, (size_t)65536 / d.n_heads + 128, (size_t)(c->max_splits + 1) * 128});
+  TRY(dev_alloc(c, &c->part_o, (size_t)d.n_heads * c->part_rows * d.head_dim * 4, true));
+  TRY(dev_alloc(c, &c->part_ml, (size_t)d.n_heads * c->part_rows * 2 * 4, true));
   TRY(dev_alloc(c, &c->pmax_val, (size_t)c->unembed_tiles * c->Mcap * 4, true));
   TRY(dev_alloc(c, &c->pmax_idx, (size_t)c->unembed_tiles * c->Mcap * 4, true));
   TRY(dev_alloc(c, &c->z, (size_t)d.vocab * 4, true));
@@ -486,8 +499,8 @@ ngg_status ngg_prefill(ngg_ctx *c, const int32_t *prompt, int32_t n_prompt) {
   c->tokens.assign(prompt, prompt + n_prompt);
   NGG_HIP(c, hipMemcpyAsync(c->hist, prompt, (size_t)n_prompt * 4, hipMemcpyHostToDevice, c->stream));
   const ngg_model_desc &d = c->d;
-  for (int p0 = 0; p0 < n_prompt; p0 += kPrefillChunk) {
-    const int C = std::min(kPrefillChunk, n_prompt - p0);
+  for (int p0 = 0; p0 < n_prompt; p0 += c->prefill_chunk) {
+    const int C = std::min(c->prefill_chunk, n_prompt - p0);
     const bool last = p0 + C == n_prompt;
     ngg_status st = forward(c, 1, C, p0, true, 0, last, false);
     if (st != NGG_OK) return st;
@@ -499,7 +512,7 @@ ngg_status ngg_prefill(ngg_ctx *c, const int32_t *prompt, int32_t n_prompt) {
                   c->Mcap, C, 0, p0, nullptr, 0, C, C, c->hist, c->stream);
   }
   // first generated token = greedy prediction after the last prompt token
-  const int last_c = (n_prompt - 1) % kPrefillChunk;
+  const int last_c = (n_prompt - 1) % c->prefill_chunk;
   int32_t first = 0;
   NGG_HIP(c, hipMemcpyAsync(&first, c->res + res_greedy_off(d.max_k) + last_c, 4, hipMemcpyDeviceToHost, c->stream));
   NGG_HIP(c, hipStreamSynchronize(c->stream));

@@ -292,10 +292,10 @@ __global__ __launch_bounds__(256) void attn_stream_kernel(const AttnArgs a, int 
     l = rows_sum(l);                                        // the four lanes of a query each held a share of its sum
     // partial outputs keep the fragment order, [head][slice][16-query group][df][lane][4]: one store
     // instruction of the wave writes 1 KB contiguously
-    const size_t blk = ((size_t)h * S + split) * (a.Mcap / 16) + (q0 / 16 + qf);
+    const size_t blk = ((size_t)h * S + split) * (a.Mpart / 16) + (q0 / 16 + qf);
     *reinterpret_cast<float4 *>(a.part_o + ((blk * DF + df) * 64 + lane) * 4) = float4{o[0], o[1], o[2], o[3]};
     if (m < M && df == 0 && g == 0) {
-      const size_t slot = ((size_t)h * S + split) * a.Mcap + m;
+      const size_t slot = ((size_t)h * S + split) * a.Mpart + m;
       a.part_ml[slot * 2 + 0] = mstar;
       a.part_ml[slot * 2 + 1] = l;
     }
@@ -441,7 +441,7 @@ __global__ __launch_bounds__(256, 2) void attn_shared_kernel(const AttnArgs a, i
 #pragma unroll
     for (int qf = 0; qf < QF; ++qf) {
       // partial outputs keep the fragment order, [head][slice][16-query group][df][lane][4]
-      const size_t blk = ((size_t)h * S + split) * (a.Mcap / 16) + (qw / 16 + qf);
+      const size_t blk = ((size_t)h * S + split) * (a.Mpart / 16) + (qw / 16 + qf);
 #pragma unroll
       for (int df = 0; df < DF; ++df)
         *reinterpret_cast<float4 *>(a.part_o + ((blk * DF + df) * 64 + lane) * 4) =
@@ -449,7 +449,7 @@ __global__ __launch_bounds__(256, 2) void attn_shared_kernel(const AttnArgs a, i
       const int m = qw + qf * 16 + li;
       const float l = rows_sum(lrun[qf]);                   // the four lanes of a query each held a share of its sum
       if (m < M && g == 0) {
-        const size_t slot = ((size_t)h * S + split) * a.Mcap + m;
+        const size_t slot = ((size_t)h * S + split) * a.Mpart + m;
         a.part_ml[slot * 2 + 0] = mrun[qf];
         a.part_ml[slot * 2 + 1] = l;
       }
@@ -465,14 +465,14 @@ template <typename T, int HD>
 __global__ __launch_bounds__(256) void attn_merge_kernel(const AttnArgs a) {
   constexpr int DF = HD / 16;
   const int qb = blockIdx.x, h = blockIdx.y;
-  const int S = a.n_splits, MB = a.Mcap / 16;
+  const int S = a.n_splits, MB = a.Mpart / 16;
   // two workgroups per (16-query group, head), one per half of the output fragments: more CUs pull the partials
   const int idx0 = blockIdx.z * (DF * 32), idx1 = idx0 + DF * 32;
   for (int idx = idx0 + threadIdx.x; idx < idx1; idx += 256) {
     const int df = idx >> 6, lane = idx & 63;
     const int m = qb * 16 + (lane & 15), d4 = df * 16 + 4 * (lane >> 4);
     if (m >= a.M) continue;
-    const size_t slot0 = (size_t)h * S * a.Mcap + m;
+    const size_t slot0 = (size_t)h * S * a.Mpart + m;
     float mrun = kNegBig, l = 0.0f;
     float4 o{0.f, 0.f, 0.f, 0.f};
     for (int s0 = 0; s0 < S; s0 += 8) {
@@ -482,7 +482,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const AttnArgs a) {
       for (int i = 0; i < 8; ++i) {
         const int sc = min(s0 + i, S - 1);
         v[i] = *reinterpret_cast<const float4 *>(a.part_o + (((((size_t)h * S + sc) * MB + qb) * DF + df) * 64 + lane) * 4);
-        ml[i] = *reinterpret_cast<const float2 *>(a.part_ml + (slot0 + (size_t)sc * a.Mcap) * 2);
+        ml[i] = *reinterpret_cast<const float2 *>(a.part_ml + (slot0 + (size_t)sc * a.Mpart) * 2);
       }
       float mnew = mrun;
 #pragma unroll

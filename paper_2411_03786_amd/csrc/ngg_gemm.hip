@@ -17,6 +17,7 @@
 // Epilogues: rotary embedding + KV-scratch write (q, k, v), SwiGLU (gate, up), residual partial,
 // and per-position argmax partials for the greedy choice (output embedding).
 #include "ngg_internal.h"
+#include <algorithm>
 
 namespace ngg {
 
@@ -376,8 +377,8 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_skinny_kernel(const GemmArg
 // that share a fragment both load it (the second request is served by the L2).  No hand-over between waves:
 // each wave finishes its own accumulators.  gridDim.y splits the contraction (residual only).
 // ---------------------------------------------------------------------------------------------
-template <typename T, int EPI, int FM, int FN>
-__global__ __launch_bounds__(256) void gemm_wide_kernel(const GemmArgs a) {
+template <typename T, int EPI, int FM, int FN, bool TILED>
+__global__ __launch_bounds__(256) void gemm_wide_kernel(const GemmArgs a, int MT) {
   static_assert(sizeof(T) == 2, "16-bit operands only");
   constexpr bool PAIRED = EPI == EPI_QKV || EPI == EPI_GATEUP;
   static_assert(PAIRED || FN % 2 == 0, "unembedding partials are indexed by pairs of fragments");
@@ -403,6 +404,13 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(const GemmArgs a) {
   const int n_steps = K / 32;
   const int n_slices = (n_steps + SPS - 1) / SPS;
   const int KS = gridDim.y, ks = blockIdx.y;
+  // Workgroup -> (rows of W, row tile).  With several row tiles (TILED: prefill pieces of more than 288 rows) the
+  // MT workgroups that share rows of W take consecutive slots of one XCD (workgroup b runs on XCD b % 8), so they
+  // run at about the same time on one L2 and the rows come from HBM once; W is then read with ordinary loads
+  // (a non-temporal line may be gone before the next workgroup asks for it).
+  const int nb = TILED ? (blockIdx.x / 8 / MT) * 8 + blockIdx.x % 8 : blockIdx.x;
+  const int m0 = TILED ? (blockIdx.x / 8 % MT) * (16 * FM) : 0;
+  if (TILED && nb * 2 * FN >= n_frags) return;               // padding of the last row of 8
   const int c0 = (int)(((long)n_slices * ks) / KS), c1 = (int)(((long)n_slices * (ks + 1)) / KS);
 
   const T *wblk[FN];
@@ -410,7 +418,7 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(const GemmArgs a) {
   bool frag_live[FN];
 #pragma unroll
   for (int f = 0; f < FN; ++f) {
-    int frag = (blockIdx.x * 2 + wn) * FN + f;
+    int frag = (nb * 2 + wn) * FN + f;
     frag_live[f] = frag < n_frags;
     if (!frag_live[f]) frag = n_frags - 1;   // repeats a fragment it does not store
     fragi[f] = frag;
@@ -427,7 +435,7 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(const GemmArgs a) {
     return r * a.out_scale;
   };
 
-  for (int m0 = 0; m0 < M; m0 += ROWS) {
+  {
     // X staging: piece p = tid + 256 i is row p / PPR, 16 bytes at column piece p % PPR of the slice; pieces
     // past the tile repeat its last row, rows past the block's last row repeat that row (the same cache lines
     // as the threads that stage it: no further traffic from L2; never stored)
@@ -463,7 +471,7 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(const GemmArgs a) {
     auto load_w = [&](Frag<T> (&slot)[FN], int t) {         // wave-step t >= 0 is global step c0 * SPS + t (clamped)
       const int st = min(c0 * SPS + t, n_steps - 1);
 #pragma unroll
-      for (int f = 0; f < FN; ++f) slot[f] = load_frag_stream(wblk[f] + (size_t)st * 512);
+      for (int f = 0; f < FN; ++f) slot[f] = TILED ? load_frag(wblk[f] + (size_t)st * 512) : load_frag_stream(wblk[f] + (size_t)st * 512);
     };
 
     // As in the skinny kernel the loop starts one unrolled group (two slices) early with the multiplications
@@ -512,9 +520,28 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(const GemmArgs a) {
     for (int r = tid; r < ROWS; r += 256) rs_lds[r] = row_scale(m0 + r);
     __syncthreads();
 
+    const int row0 = wm * FMW * 16 + li;
+    if constexpr (EPI == EPI_QKV) {
+      // q/k/v: the accumulators leave the registers through LDS (every wave its own region, behind the row scales)
+      // and the rotary epilogue takes them back one item at a time.  Unrolled over the registers, the FN * FM / 2
+      // items' table entries and addresses were all live at once and the register allocator answered by storing
+      // every accumulator to scratch memory right where the main loop produces it.
+      f32x4 *dump = reinterpret_cast<f32x4 *>(smem + (ROWS * sizeof(float) + 15) / 16 * 16) + (size_t)wave * (FN * FMW * 64);
+#pragma unroll
+      for (int f = 0; f < FN; ++f)
+#pragma unroll
+        for (int fm = 0; fm < FMW; ++fm) dump[(f * FMW + fm) * 64 + lane] = acc[f][fm];
+#pragma unroll 2
+      for (int idx = 0; idx < FN * FMW; ++idx) {
+        const int f = idx / FMW, fm = idx - f * FMW;
+        const int frag = (nb * 2 + wn) * FN + f;
+        const int row = row0 + fm * 16;
+        if (frag < n_frags) epi_paired<T, EPI>(a, frag, m0 + row, M, g, rs_lds[row], dump[idx * 64 + lane]);   // uniform per wave
+      }
+    } else {
 #pragma unroll
     for (int fm = 0; fm < FMW; ++fm) {
-      const int row = (wm * FMW + fm) * 16 + li;             // row of the tile
+      const int row = row0 + fm * 16;                        // row of the tile
       const int m = m0 + row;
       const bool live = m < M;
       if constexpr (PAIRED) {
@@ -536,25 +563,29 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(const GemmArgs a) {
           }
       }
     }
-    __syncthreads();                                         // LDS is reused by the next tile
+    }
   }
 }
 
-// FN: fragments per wave; a workgroup owns 2 FN
+// FN: fragments per wave; a workgroup owns 2 FN.  MT: row tiles of 16 FM rows (1: the tile holds the whole block).
 template <typename T, int EPI, int FM, int FN>
-static void launch_wide_cfg(const GemmArgs &a, int KS, hipStream_t s) {
-  const size_t lds = (size_t)2 * 16 * FM * (64 + 8) * sizeof(T);
+static void launch_wide_cfg(const GemmArgs &a, int KS, int MT, hipStream_t s) {
+  size_t lds = (size_t)2 * 16 * FM * (64 + 8) * sizeof(T);
+  if (EPI == EPI_QKV) lds = std::max(lds, (size_t)(16 * FM * 4 + 15) / 16 * 16 + (size_t)4 * FN * (FM / 2) * 1024);   // accumulator hand-back
   const int blocks = (a.n_groups + 2 * FN - 1) / (2 * FN);
   if (lds > 64 * 1024) {
-    static const hipError_t opted = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_wide_kernel<T, EPI, FM, FN>),
+    static const hipError_t opted = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_wide_kernel<T, EPI, FM, FN, false>),
                                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    (void)opted;
+    static const hipError_t opted_t = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_wide_kernel<T, EPI, FM, FN, true>),
+                                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    (void)opted; (void)opted_t;
   }
-  hipLaunchKernelGGL((gemm_wide_kernel<T, EPI, FM, FN>), dim3(blocks, KS), dim3(256), lds, s, a);
+  if (MT == 1) hipLaunchKernelGGL((gemm_wide_kernel<T, EPI, FM, FN, false>), dim3(blocks, KS), dim3(256), lds, s, a, 1);
+  else hipLaunchKernelGGL((gemm_wide_kernel<T, EPI, FM, FN, true>), dim3((blocks + 7) / 8 * 8 * MT, KS), dim3(256), lds, s, a, MT);
 }
 
 template <typename T, int EPI, int FM>
-static void launch_wide_fm(const GemmArgs &a_in, int KS, hipStream_t s) {
+static void launch_wide_fm(const GemmArgs &a_in, int KS, int MT, hipStream_t s) {
   GemmArgs a = a_in;
   a.n_groups = a.N / 16 * ((EPI == EPI_GATEUP) ? 2 : 1);     // fragments: gate/up interleaves 2 * d_ffn rows
   if (EPI == EPI_QKV) a.n_groups = (a.H + 2 * a.Hkv) * (a.hd / 16);
@@ -562,33 +593,31 @@ static void launch_wide_fm(const GemmArgs &a_in, int KS, hipStream_t s) {
   // otherwise (q/k/v of a 4096-wide model has 768 fragments: 96 workgroups against 192): every workgroup reads
   // all of X whatever it owns, so the W rows per workgroup only matter once the chip is full.  q/k/v always
   // takes 64: the unrolled rotary epilogue over more accumulator fragments does not fit the registers.
-  if constexpr (EPI == EPI_QKV) {
-    launch_wide_cfg<T, EPI, FM, 2>(a, KS, s);
-  } else {
-    if constexpr (EPI == EPI_GATEUP) {
-      if ((a.n_groups + 7) / 8 * KS < 160) { launch_wide_cfg<T, EPI, FM, 2>(a, KS, s); return; }
-    }
-    launch_wide_cfg<T, EPI, FM, 4>(a, KS, s);
+  if constexpr (EPI == EPI_QKV || EPI == EPI_GATEUP) {
+    if ((a.n_groups + 7) / 8 * KS * MT < 160) { launch_wide_cfg<T, EPI, FM, 2>(a, KS, MT, s); return; }
   }
+  launch_wide_cfg<T, EPI, FM, 4>(a, KS, MT, s);
 }
 
-// Row tiles of the wide kernel: as few passes as possible (288 rows at most each), then the smallest even
-// number of 16-row blocks that holds a pass's share of the rows.
+// Row tiles of the wide kernel: as few as possible (288 rows at most each), then the smallest even
+// number of 16-row blocks that holds a tile's share of the rows.
+static int gemm_wide_row_tiles(int M) { return (M + 287) / 288; }
 int gemm_wide_row_blocks(int M) {
-  const int passes = (M + 287) / 288;
-  const int rows = (M + passes - 1) / passes;
+  const int tiles = gemm_wide_row_tiles(M);
+  const int rows = (M + tiles - 1) / tiles;
   const int fm = (rows + 15) / 16;
   return (fm + 1) / 2 * 2 < 10 ? 10 : (fm + 1) / 2 * 2;
 }
 
 template <typename T, int EPI>
 static void launch_wide(const GemmArgs &a, int KS, hipStream_t s) {
+  const int MT = gemm_wide_row_tiles(a.M);
   switch (gemm_wide_row_blocks(a.M)) {
-    case 10: launch_wide_fm<T, EPI, 10>(a, KS, s); break;
-    case 12: launch_wide_fm<T, EPI, 12>(a, KS, s); break;
-    case 14: launch_wide_fm<T, EPI, 14>(a, KS, s); break;
-    case 16: launch_wide_fm<T, EPI, 16>(a, KS, s); break;
-    default: launch_wide_fm<T, EPI, 18>(a, KS, s);
+    case 10: launch_wide_fm<T, EPI, 10>(a, KS, MT, s); break;
+    case 12: launch_wide_fm<T, EPI, 12>(a, KS, MT, s); break;
+    case 14: launch_wide_fm<T, EPI, 14>(a, KS, MT, s); break;
+    case 16: launch_wide_fm<T, EPI, 16>(a, KS, MT, s); break;
+    default: launch_wide_fm<T, EPI, 18>(a, KS, MT, s);
   }
 }
 
@@ -700,7 +729,7 @@ static bool residual_narrow(int M, int N, int K) { return M <= 16 || K <= N; }
 // long as each split keeps at least 2 chunks.
 int gemm_residual_splits(int dtype, int M, int N, int K) {
   if (dtype == 1 && M > 128) {              // wide kernel: 128 rows of W per workgroup, slices of 64; at least 8 slices per split
-    const int blocks = (N / 16 + 7) / 8, n_slices = (K + 63) / 64;
+    const int blocks = (N / 16 + 7) / 8 * ((M + 287) / 288), n_slices = (K + 63) / 64;   // row tiles count as workgroups
     int ks = (256 + blocks - 1) / blocks;
     ks = ks > kMaxResidualSplits ? kMaxResidualSplits : ks;
     while (ks > 1 && n_slices / ks < 8) --ks;

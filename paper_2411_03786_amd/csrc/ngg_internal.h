@@ -277,8 +277,9 @@ struct AttnArgs {
   const void *vcache;     // this layer's cached values, same tiling (v_offset)
   const void *kscr;       // this layer's block keys, [Hkv][Mcap/32] tiles
   const void *vscr;       // this layer's block values, [Hkv][Mcap/32] tiles
-  float *part_o;          // [H][n_splits][Mcap/16][hd/16][64 lanes][4]: output fragments as the registers hold them
-  float *part_ml;         // [H][n_splits][Mcap][2]
+  float *part_o;          // [H][n_splits][Mpart/16][hd/16][64 lanes][4]: output fragments as the registers hold them
+  float *part_ml;         // [H][n_splits][Mpart][2]
+  int Mpart;              // rows per (head, slice) of the two partial buffers: M rounded up to 128
   void *out;              // chunk-major [H*hd/KC][Mcap][KC] T
   int H, Hkv, Mcap, Spad, M, C, P, n_splits;   // n_splits: workgroups that share a head's list of key tiles
   int shared0;            // block layout (block_index)
