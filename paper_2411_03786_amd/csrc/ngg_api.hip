@@ -146,7 +146,9 @@ ngg_status dev_alloc(ngg_ctx *c, P **p, size_t bytes, bool zero) {
 // context of P tokens (Section 3).  Leaves this block's keys/values in the scratch, and, when
 // `unembed` is set, the per-tile argmax partials (and optional logits) of every block position.
 ngg_status forward(ngg_ctx *c, int R, int C, int P, bool from_hist, int w, bool unembed, bool want_logits,
-                   const int32_t *tok_src = nullptr) {   // tok_src: from_hist reads its tokens here instead of the history
+                   const int32_t *tok_src = nullptr,     // tok_src: from_hist reads its tokens here instead of the history
+                   bool last_row_only = false,           // unembedding of the block's last token alone (it becomes row 0 of the partials)
+                   bool kv_direct = false) {             // a prefill piece at a tile boundary writes its keys/values straight into the cache
   const ngg_model_desc &d = c->d;
   // a verify block keeps one copy of the column every row shares (the uncached last context token): 1 + R*w tokens
   const int shared0 = (!from_hist && C >= 2) ? 1 : 0;
@@ -175,13 +177,19 @@ ngg_status forward(ngg_ctx *c, int R, int C, int P, bool from_hist, int w, bool 
     const size_t kv_layer = (size_t)l * d.n_kv_heads;
     char *kscr_l = (char *)c->kscr + kv_layer * c->Mcap * d.head_dim * c->esize;
     char *vscr_l = (char *)c->vscr + kv_layer * d.head_dim * c->Mcap * c->esize;
+    int kv_rows = c->Mcap;
+    if (kv_direct) {                                 // the block's tiles are the cache's tiles P / 32 ..
+      kscr_l = (char *)c->kcache + (kv_layer * c->Spad + P) * d.head_dim * c->esize;
+      vscr_l = (char *)c->vcache + (kv_layer * c->Spad + P) * d.head_dim * c->esize;
+      kv_rows = c->Spad;
+    }
     { ProfScope ps(c, NGG_PROF_NORM); launch_rmsnorm(dt, c->h, c->hpart, pending, part_stride, lw.attn_norm, c->xn, d.d_model, M, c->Mcap, c->row_ss, s); }
     {
       ProfScope ps(c, NGG_PROF_GEMM_QKV);
       GemmArgs g{};
       g.X = c->xn; g.W0 = c->lt[l].wqkv;
       g.M = M; g.N = dq + 2 * d.n_kv_heads * d.head_dim; g.K = d.d_model;
-      g.q = c->q; g.kscr = kscr_l; g.vscr = vscr_l;
+      g.q = c->q; g.kscr = kscr_l; g.vscr = vscr_l; g.kv_rows = kv_rows;
       g.H = d.n_heads; g.Hkv = d.n_kv_heads; g.hd = d.head_dim; g.Mcap = c->Mcap; g.C = C; g.P = P; g.shared0 = shared0;
       g.rope_cos = c->rope_cos; g.rope_sin = c->rope_sin;
       g.row_ss = c->row_ss; g.ss_segs = ss_segs; g.ss_eps = d.rms_eps;
@@ -194,7 +202,7 @@ ngg_status forward(ngg_ctx *c, int R, int C, int P, bool from_hist, int w, bool 
       a.q = c->q;
       a.kcache = (char *)c->kcache + kv_layer * c->Spad * d.head_dim * c->esize;
       a.vcache = (char *)c->vcache + kv_layer * d.head_dim * c->Spad * c->esize;
-      a.kscr = kscr_l; a.vscr = vscr_l;
+      a.kscr = kscr_l; a.vscr = vscr_l; a.kv_rows = kv_rows;
       a.part_o = c->part_o; a.part_ml = c->part_ml; a.out = c->attn;
       a.H = d.n_heads; a.Hkv = d.n_kv_heads; a.Mcap = c->Mcap; a.Spad = c->Spad; a.M = M; a.C = C; a.P = P;
       a.n_splits = n_splits; a.shared0 = shared0; a.Mpart = Mpart;
@@ -237,6 +245,12 @@ ngg_status forward(ngg_ctx *c, int R, int C, int P, bool from_hist, int w, bool 
     g.logits = want_logits ? c->logits : nullptr;
     g.pmax_val = c->pmax_val; g.pmax_idx = c->pmax_idx; g.Mcap = c->Mcap;
     g.row_ss = c->row_ss; g.ss_segs = ss_segs; g.ss_eps = d.rms_eps;
+    if (last_row_only) {                               // rows of the activation layout lie one chunk row apart in every chunk
+      const int kc = dt == 1 ? KChunk<half_t>::value : KChunk<float>::value;
+      g.X = (const char *)c->xn + (size_t)(M - 1) * kc * c->esize;
+      g.row_ss = c->row_ss + (size_t)(M - 1) * kNormSegs;
+      g.M = 1;
+    }
     g.out_scale = 1.0f / c->unemb_scale;
     launch_gemm(dt, EPI_UNEMBED, g, s);
   }
@@ -438,7 +452,8 @@ ngg_status ngg_create(const ngg_model_desc *desc, const ngg_weights *weights, vo
   TRY(dev_alloc(c, &c->kscr, kv_elems * c->Mcap * c->esize, true));
   TRY(dev_alloc(c, &c->vscr, kv_elems * c->Mcap * c->esize, true));
   TRY(dev_alloc(c, &c->h, (size_t)c->Mcap * d.d_model * 4, true));
-  TRY(dev_alloc(c, &c->row_ss, (size_t)c->Mcap * kNormSegs * 4, true));
+  // (+ 16 rows: the unembedding of a piece's last token alone starts its row tile at that row)
+  TRY(dev_alloc(c, &c->row_ss, (size_t)(c->Mcap + 16) * kNormSegs * 4, true));
   TRY(dev_alloc(c, &c->hpart, (size_t)kMaxResidualSplits * c->Mcap * d.d_model * 4, true));
   TRY(dev_alloc(c, &c->xn, act_elems(d.dtype, c->Mcap, d.d_model) * c->esize, true));
   TRY(dev_alloc(c, &c->q, (size_t)c->Mcap * dq * c->esize, true));
@@ -502,19 +517,18 @@ ngg_status ngg_prefill(ngg_ctx *c, const int32_t *prompt, int32_t n_prompt) {
   for (int p0 = 0; p0 < n_prompt; p0 += c->prefill_chunk) {
     const int C = std::min(c->prefill_chunk, n_prompt - p0);
     const bool last = p0 + C == n_prompt;
-    ngg_status st = forward(c, 1, C, p0, true, 0, last, false);
+    // pieces start at multiples of 256 positions: their key/value tiles are cache tiles, written in place (no commit copy)
+    ngg_status st = forward(c, 1, C, p0, true, 0, last, false, nullptr, true, true);   // the last piece predicts the first new token
     if (st != NGG_OK) return st;
     ProfScope ps(c, NGG_PROF_ACCEPT_COMMIT);
     if (last)
-      launch_argmax_accept(c->pmax_val, c->pmax_idx, c->unembed_tiles, c->Mcap, 1, 0, C, 0, nullptr, nullptr, nullptr, c->res,
+      launch_argmax_accept(c->pmax_val, c->pmax_idx, c->unembed_tiles, c->Mcap, 1, 0, 1, 0, nullptr, nullptr, nullptr, c->res,
                            res_greedy_off(d.max_k), c->stream);
-    launch_commit(d.dtype, c->kcache, c->vcache, c->kscr, c->vscr, d.n_layers, d.n_kv_heads, d.head_dim, c->Spad,
-                  c->Mcap, C, 0, p0, nullptr, 0, C, C, c->hist, c->stream);
+
   }
   // first generated token = greedy prediction after the last prompt token
-  const int last_c = (n_prompt - 1) % c->prefill_chunk;
   int32_t first = 0;
-  NGG_HIP(c, hipMemcpyAsync(&first, c->res + res_greedy_off(d.max_k) + last_c, 4, hipMemcpyDeviceToHost, c->stream));
+  NGG_HIP(c, hipMemcpyAsync(&first, c->res + res_greedy_off(d.max_k), 4, hipMemcpyDeviceToHost, c->stream));
   NGG_HIP(c, hipStreamSynchronize(c->stream));
   NGG_HIP(c, hipMemcpyAsync(c->hist + n_prompt, &first, 4, hipMemcpyHostToDevice, c->stream));
   NGG_HIP(c, hipStreamSynchronize(c->stream));

@@ -157,7 +157,7 @@ __global__ __launch_bounds__(256) void attn_stream_kernel(const AttnArgs a, int 
   const int t_begin = (int)((long)TL * split / S), t_end = (int)((long)TL * (split + 1) / S);
   const int n_tiles = active ? t_end - t_begin : 0;
   const T *kc = (const T *)a.kcache + (size_t)hkv * a.Spad * HD, *vc = (const T *)a.vcache + (size_t)hkv * a.Spad * HD;
-  const T *ksc = (const T *)a.kscr + (size_t)hkv * a.Mcap * HD, *vsc = (const T *)a.vscr + (size_t)hkv * a.Mcap * HD;
+  const T *ksc = (const T *)a.kscr + (size_t)hkv * a.kv_rows * HD, *vsc = (const T *)a.vscr + (size_t)hkv * a.kv_rows * HD;
 
   // this lane's queries (result columns), one per group of 16: visible block keys are [qlo, qhi]
   int qlo[QF], qhi[QF];
@@ -337,7 +337,7 @@ __global__ __launch_bounds__(256, 2) void attn_shared_kernel(const AttnArgs a, i
   const int t_begin = (int)((long)TL * split / S), t_end = (int)((long)TL * (split + 1) / S);
   const int n_tiles = t_end - t_begin;
   const T *kc = (const T *)a.kcache + (size_t)hkv * a.Spad * HD, *vc = (const T *)a.vcache + (size_t)hkv * a.Spad * HD;
-  const T *ksc = (const T *)a.kscr + (size_t)hkv * a.Mcap * HD, *vsc = (const T *)a.vscr + (size_t)hkv * a.Mcap * HD;
+  const T *ksc = (const T *)a.kscr + (size_t)hkv * a.kv_rows * HD, *vsc = (const T *)a.vscr + (size_t)hkv * a.kv_rows * HD;
 
   // DEPTH register stages: tile t + DEPTH is requested when tile t is used (four stages measured slower than
   // two, at a 16K context and at 2K).  NT: the tiles are read with non-temporal loads (the launcher's choice).

@@ -61,12 +61,12 @@ __device__ __forceinline__ void epi_paired(const GemmArgs &a, int frag, int m, i
           store4(dst, lo[0], lo[1], lo[2], lo[3]);
           store4(dst + half, hi[0], hi[1], hi[2], hi[3]);
         } else {                                     // keys: tiles of 32 block positions in operand order
-          T *kh = (T *)a.kscr + (size_t)head * a.Mcap * a.hd;
+          T *kh = (T *)a.kscr + (size_t)head * a.kv_rows * a.hd;
           store4(kh + k_offset(m, i0, a.hd, (int)sizeof(T)), lo[0], lo[1], lo[2], lo[3]);
           store4(kh + k_offset(m, i0 + half, a.hd, (int)sizeof(T)), hi[0], hi[1], hi[2], hi[3]);
         }
       } else {                                       // values: the transposed tiles
-        T *vh = (T *)a.vscr + (size_t)head * a.Mcap * a.hd;
+        T *vh = (T *)a.vscr + (size_t)head * a.kv_rows * a.hd;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           vh[v_offset(m, i0 + r, a.hd, (int)sizeof(T))] = from_f32<T>(v[r]);

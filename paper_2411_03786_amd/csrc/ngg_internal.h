@@ -257,8 +257,10 @@ struct GemmArgs {
   void *act;              // chunk-major [N/KC][Mcap][KC] T  (N = d_ffn)
   // EPI_QKV
   void *q;                // [H][Mcap][hd] T
-  void *kscr;             // this layer's block keys, [Hkv][Mcap/32] tiles (k_offset)
-  void *vscr;             // this layer's block values, [Hkv][Mcap/32] tiles (v_offset)
+  void *kscr;             // this layer's block keys, [Hkv][kv_rows/32] tiles (k_offset)
+  void *vscr;             // this layer's block values, [Hkv][kv_rows/32] tiles (v_offset)
+  int kv_rows;            // positions per kv head of kscr/vscr: Mcap for the scratch; the cache's padded length when a
+                          // prefill piece writes its keys and values straight to their cache tiles
   int H, Hkv, hd, Mcap, C, P;   // block token m sits at position P + block_col(m, C, shared0)
   int shared0;
   const float *rope_cos, *rope_sin;   // [Spad][hd/2]
@@ -275,8 +277,9 @@ struct AttnArgs {
   const void *q;          // [H][Mcap][hd]
   const void *kcache;     // this layer's cached keys, [Hkv][Spad/32] tiles of 32 positions (k_offset)
   const void *vcache;     // this layer's cached values, same tiling (v_offset)
-  const void *kscr;       // this layer's block keys, [Hkv][Mcap/32] tiles
-  const void *vscr;       // this layer's block values, [Hkv][Mcap/32] tiles
+  const void *kscr;       // this layer's block keys, [Hkv][kv_rows/32] tiles
+  const void *vscr;       // this layer's block values, [Hkv][kv_rows/32] tiles
+  int kv_rows;            // positions per kv head of kscr/vscr (Mcap, or the cache's padded length: see GemmArgs)
   float *part_o;          // [H][n_splits][Mpart/16][hd/16][64 lanes][4]: output fragments as the registers hold them
   float *part_ml;         // [H][n_splits][Mpart][2]
   int Mpart;              // rows per (head, slice) of the two partial buffers: M rounded up to 128

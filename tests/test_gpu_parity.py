@@ -655,12 +655,21 @@ def test_bf16_blocks_of_more_than_64_rows(k, w):
 
 
 def test_prefill_piece_boundaries_16_bit():
-    """Prompts around the prefill's 256-token pieces on the small 16-bit widths (2 layers): the last piece has
-    1 .. 256 rows, so the first generated token comes through the skinny kernel (up to 128 rows) or the wide one."""
+    """Prompt lengths around the row tiles of the prefill (16-bit models take pieces of up to 2048 tokens; the wide
+    GEMM kernel cuts a piece into tiles of up to 288 rows, the skinny kernel takes up to 128 rows) and around the
+    piece boundary itself, on the small 16-bit widths (2 layers).  A context created with a short max_seq has
+    shorter pieces (max_seq rounded up to 256): the second loop runs the same prompts through 768-token pieces."""
     desc = si.reduced_layers(si.MODELS["small"], 2)
-    run = dict(si.RUNS["cfg2"], prompt_len=700, n_gen=8)
+    run = dict(si.RUNS["cfg2"], prompt_len=2400, n_gen=8)
     w_, _, model, ctx = _setup(desc, run)
-    for n_prompt in (129, 200, 255, 256, 257, 300, 384, 385, 512, 513, 640):
+    for n_prompt in (129, 200, 256, 257, 288, 289, 300, 513, 577, 1000, 2047, 2048, 2049, 2305):
+        prompt = si.prompt_spans(desc["vocab"], n_prompt, 0.3, seed=7)
+        rep = lockstep_run(ctx, model, prompt, 4, run, TOL["bf16"], max_steps=1)
+        assert rep.max_rel_logit_err <= 2e-2, n_prompt
+    ctx.close()
+    run = dict(si.RUNS["cfg2"], prompt_len=700, n_gen=8)                  # max_seq 716: pieces of 768 tokens
+    w_, _, model, ctx = _setup(desc, run)
+    for n_prompt in (255, 384, 640, 700):
         prompt = si.prompt_spans(desc["vocab"], n_prompt, 0.3, seed=7)
         rep = lockstep_run(ctx, model, prompt, 4, run, TOL["bf16"], max_steps=1)
         assert rep.max_rel_logit_err <= 2e-2, n_prompt
