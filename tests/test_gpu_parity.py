@@ -644,7 +644,7 @@ def test_bf16_blocks_of_more_than_64_rows(k, w):
     """Blocks of 112, 288, 65 and 96 rows on the small 16-bit widths (3 layers): GEMM row tiles of 7, 8, 5
     and 6 column blocks and the attention workgroups with two query groups per wave; then the wide GEMM
     kernel (more than 128 rows in one pass over the weights): 130, 160, 256 and 288 rows (tiles of 10, 10, 16
-    and 18 row blocks), 300 rows (two passes of 160) and 1056 rows (four passes of 272)."""
+    and 18 row blocks), 300 rows (two row tiles of 160 in one launch) and 1056 rows (four row tiles of 272)."""
     desc = si.reduced_layers(si.MODELS["small"], 3)
     run = dict(si.RUNS["cfg2"], prompt_len=333, k=k, w=w, k_ctx_max=k, q_min=1, q_max=3, n_gen=30)
     w_, prompt, model, ctx = _setup(desc, run)
