@@ -207,6 +207,19 @@ ngg_status ngg_bigram_source(ngg_ctx *ctx, int32_t source);
 enum { NGG_ALLOC_FIXED = 0, NGG_ALLOC_ADAPTIVE = 1 };
 ngg_status ngg_allocation(ngg_ctx *ctx, int32_t mode, int32_t coverage_percent, int32_t warmup_wins);
 
+/* Replay of captured steps inside ngg_greedy_decode / ngg_decode_more (the method's loop of Section 3: drafts, one
+ * model call on the (k, w+1) block, acceptance, commit).  A step whose launch shapes equal the previous step's can be
+ * replayed from a HIP graph (recorded on a stream of the library's own, launched on the context's stream); its
+ * kernels read the context length from device memory, which the graph's last node advances, so the same graph serves
+ * step after step and is captured again only when k, w, the draft settings or the number of attention slices change.
+ * Steps that the generation budget clamps (the last ones), steps with profiling brackets enabled and the first step
+ * of every shape are always launched on the stream.  mode 0: never replay.  mode 1: replay every step that qualifies.
+ * mode 2 (default): per step shape, time three steps launched on the stream and three replayed, keep the faster way
+ * (replay pays where a step is bound by its launches: small models; at the 7B shapes it measures no gain).  In every
+ * mode the same kernels run in the same shapes: the committed tokens and the statistics are identical.
+ * ngg_build_drafts, ngg_verify_step and ngg_commit called directly always launch on the stream. */
+ngg_status ngg_step_graphs(ngg_ctx *ctx, int32_t mode);
+
 /* Committed token history: copies min(n, cap) tokens to dst (HOST), n to *n. */
 ngg_status ngg_get_tokens(const ngg_ctx *ctx, int32_t *dst, int32_t cap, int32_t *n);
 
@@ -268,7 +281,8 @@ ngg_status ngg_profile_read_bandwidth(ngg_ctx *ctx, double *gbps);
  * + k%8 for 2-byte elements), "attn" (attention output of the last layer, model dtype, in
  * chunks of 256 (bf16) or 128 (fp32) features: [feature chunk][Mcap rows][chunk]).
  * "attn_layout" (int32[4], host-side record of the last model call: slices of the key list per head,
- * workgroups of the attention kernel, block rows, cached positions).  Synchronises the stream. */
+ * workgroups of the attention kernel, block rows, cached positions).  "step_graphs" (int32[4], host-side record:
+ * replay mode, a capture failed, captures so far, replayed steps so far).  Synchronises the stream. */
 ngg_status ngg_debug_peek(ngg_ctx *ctx, const char *name, void *dst, int64_t cap, int64_t *bytes, int32_t *stride);
 
 #ifdef __cplusplus

@@ -23,7 +23,7 @@ PROF_CLASSES = ("gemm_qkv", "gemm_o", "gemm_gateup", "gemm_down", "gemm_unembed"
 EXPORTS = ("ngg_create", "ngg_destroy", "ngg_prefill", "ngg_build_drafts", "ngg_verify_step", "ngg_commit",
            "ngg_greedy_decode", "ngg_get_tokens", "ngg_last_error", "ngg_profile_enable", "ngg_profile_reset",
            "ngg_profile_read", "ngg_debug_peek", "ngg_bigram_table_build", "ngg_bigram_source", "ngg_profile_bracket_overhead", "ngg_unigram_build", "ngg_decode_more", "ngg_profile_sample",
-           "ngg_context_drafts_static", "ngg_allocation", "ngg_profile_read_bandwidth")
+           "ngg_context_drafts_static", "ngg_allocation", "ngg_profile_read_bandwidth", "ngg_step_graphs")
 NGG_STATIC_MAX_TOKENS = 32768
 
 
@@ -96,6 +96,7 @@ def load_library():
     lib.ngg_profile_bracket_overhead.argtypes = [vp, C.POINTER(C.c_double)]
     lib.ngg_bigram_source.argtypes = [vp, C.c_int32]
     lib.ngg_allocation.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32]
+    lib.ngg_step_graphs.argtypes = [vp, C.c_int32]
     lib.ngg_profile_read_bandwidth.argtypes = [vp, C.POINTER(C.c_double)]
     lib.ngg_context_drafts_static.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp, vp, vp]
     for name in EXPORTS:
@@ -264,6 +265,9 @@ class Context:
 
     def allocation(self, mode, coverage_percent=90, warmup_wins=8):
         self._check(self.lib.ngg_allocation(self.h, int(mode), int(coverage_percent), int(warmup_wins)))
+
+    def step_graphs(self, mode):
+        self._check(self.lib.ngg_step_graphs(self.h, int(mode)))
 
     def bigram_source(self, source):
         """0 = direct sweep per step (default), 1 = the precomputed full-model table, 2 = the unigram."""

@@ -139,7 +139,7 @@ __global__ __launch_bounds__(256) void attn_stream_kernel(const AttnArgs a, int 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: tile indices and their branches stay uniform
   const int li = lane & 15, g = lane >> 4;
-  const int M = a.M, C = a.C, P = a.P;
+  const int M = a.M, C = a.C, P = a.n_dev ? *a.n_dev - 1 : a.P;
   const int q0 = (slot_b % Z) * GQ;                         // first query of this workgroup
   const bool active = q0 < M;
 
@@ -320,7 +320,7 @@ __global__ __launch_bounds__(256, 2) void attn_shared_kernel(const AttnArgs a, i
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int li = lane & 15, g = lane >> 4;
-  const int M = a.M, C = a.C, P = a.P;
+  const int M = a.M, C = a.C, P = a.n_dev ? *a.n_dev - 1 : a.P;
   const int q0 = (slot_b % Z) * GQ;                         // first query of this workgroup (< M)
   const int qw = q0 + wv * 16 * QF;                         // first query of this wave
   const bool active = qw < M;

@@ -47,7 +47,7 @@ __device__ __forceinline__ void epi_paired(const GemmArgs &a, int frag, int m, i
       const int head = kind == 0 ? hh : (kind == 1 ? hh - a.H : hh - a.H - a.Hkv);
       const int i0 = sub * 8 + 4 * g;                // dims i0 .. i0+3 and their partners i0 + half ..
       if (kind < 2) {                                // rotary embedding on q and k
-        const int pos = a.P + block_col(m, a.C, a.shared0);
+        const int pos = (a.n_dev ? *a.n_dev - 1 : a.P) + block_col(m, a.C, a.shared0);
         const float *cs = a.rope_cos + (size_t)pos * half + i0;
         const float *sn = a.rope_sin + (size_t)pos * half + i0;
         float lo[4], hi[4];

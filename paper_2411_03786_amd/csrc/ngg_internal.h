@@ -262,6 +262,7 @@ struct GemmArgs {
   int kv_rows;            // positions per kv head of kscr/vscr: Mcap for the scratch; the cache's padded length when a
                           // prefill piece writes its keys and values straight to their cache tiles
   int H, Hkv, hd, Mcap, C, P;   // block token m sits at position P + block_col(m, C, shared0)
+  const int32_t *n_dev;   // when set, P = *n_dev - 1 (see DraftArgs)
   int shared0;
   const float *rope_cos, *rope_sin;   // [Spad][hd/2]
   // EPI_UNEMBED
@@ -285,6 +286,7 @@ struct AttnArgs {
   int Mpart;              // rows per (head, slice) of the two partial buffers: M rounded up to 128
   void *out;              // chunk-major [H*hd/KC][Mcap][KC] T
   int H, Hkv, Mcap, Spad, M, C, P, n_splits;   // n_splits: workgroups that share a head's list of key tiles
+  const int32_t *n_dev;   // when set, P = *n_dev - 1 (see DraftArgs)
   int shared0;            // block layout (block_index)
   float scale;
 };
@@ -301,7 +303,7 @@ int attention_workgroups(int dtype, int hd, int H, int M, int n_splits);   // wo
 // layout (token 0 is hist[hist_base], token m >= 1 is drafts[m - 1]); mode 2: a block of single-column rows (w = 0),
 // every token hist[hist_base]
 void launch_embed(int dtype, const void *tok_emb, const int32_t *hist, const int32_t *drafts, int32_t *block_tok,
-                  float *h, int d, int M, int hist_base, int mode, hipStream_t s);
+                  float *h, int d, int M, int hist_base, int mode, hipStream_t s, const int32_t *n_dev = nullptr);   // n_dev: hist_base = *n_dev - 1
 // h[m] += sum of n_part partials (hpart[s][m], stride part_stride floats between splits), then
 // xn[m] = rmsnorm(h[m]) * gain, written chunk-major
 // dst = (src - centre) * scale in the internal element type (src: the user's storage type)
@@ -317,6 +319,7 @@ int rmsnorm_segments(int d);
 
 struct DraftArgs {
   const int32_t *hist; int n;
+  const int32_t *n_dev;   // when set, the kernels take n from here instead (a captured step replays with the same arguments)
   int k, w, k_ctx_max, q_min, q_max;
   int32_t *mlist;         // [max_seq] scratch: matching window starts
   int32_t *reps;          // [2*max_seq] scratch: (count, last_start) of each distinct continuation
@@ -364,9 +367,12 @@ inline int res_greedy_off(int max_k) { return RES_ACCEPT + ((max_k + 7) / 8) * 8
 void launch_argmax_accept(const float *pmax_val, const int *pmax_idx, int tiles, int Mcap, int rows, int k, int C, int shared0,
                           const int32_t *drafts, const int8_t *row_src, const int32_t *n_ctx, int32_t *res, int greedy_off,
                           hipStream_t s);
+// n_dev: P = *n_dev - 1 instead of the argument
 void launch_commit(int dtype, void *kcache, void *vcache, const void *kscr, const void *vscr, int L, int Hkv, int hd,
                    int Spad, int Mcap, int C, int shared0, int P, const int32_t *res, int fixed_row, int fixed_n, int max_new,
-                   int32_t *hist, hipStream_t s);
+                   int32_t *hist, hipStream_t s, const int32_t *n_dev = nullptr);
+// *n_dev += min(res[RES_NNEW], max_new): the commit's bookkeeping on the device, after the commit kernel has read *n_dev
+void launch_advance(int32_t *n_dev, const int32_t *res, int max_new, hipStream_t s);
 void launch_next1_finish(const float *pmax_val, const int *pmax_idx, int tiles, int Mcap, int M, int32_t *next1_out,
                          hipStream_t s);
 

@@ -15,8 +15,10 @@ namespace ngg {
 // ---------------------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void embed_kernel(const T *tok_emb, const int32_t *hist, const int32_t *drafts,
-                                                    int32_t *block_tok, float *h, int d, int hist_base, int mode) {
+                                                    int32_t *block_tok, float *h, int d, int hist_base, int mode,
+                                                    const int32_t *n_dev) {
   const int m = blockIdx.x;
+  if (n_dev) hist_base = *n_dev - 1;
   // mode 0: a verify block whose rows share token 0 (the last context token), then the drafts row by row;
   // mode 1: consecutive history tokens; mode 2: single-column rows, every one the last context token
   const int tok = mode == 1 ? hist[hist_base + m] : (m == 0 || mode == 2 ? hist[hist_base] : drafts[m - 1]);
@@ -35,13 +37,13 @@ __global__ __launch_bounds__(256) void embed_kernel(const T *tok_emb, const int3
 }
 
 void launch_embed(int dtype, const void *tok_emb, const int32_t *hist, const int32_t *drafts, int32_t *block_tok,
-                  float *h, int d, int M, int hist_base, int mode, hipStream_t s) {
+                  float *h, int d, int M, int hist_base, int mode, hipStream_t s, const int32_t *n_dev) {
   if (dtype == 1)
     hipLaunchKernelGGL(embed_kernel<bf16_t>, dim3(M), dim3(256), 0, s, (const bf16_t *)tok_emb, hist, drafts, block_tok,
-                       h, d, hist_base, mode);
+                       h, d, hist_base, mode, n_dev);
   else
     hipLaunchKernelGGL(embed_kernel<float>, dim3(M), dim3(256), 0, s, (const float *)tok_emb, hist, drafts, block_tok, h,
-                       d, hist_base, mode);
+                       d, hist_base, mode, n_dev);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -285,7 +287,7 @@ __global__ __launch_bounds__(1024) void ctx_match_kernel(const DraftArgs a) {
   __shared__ unsigned long long wkey[NWAVE * WANT_MAX];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int32_t *x = a.hist;
-  const int n = a.n, w = a.w;
+  const int n = a.n_dev ? *a.n_dev : a.n, w = a.w;
   const int kmax = min(a.k_ctx_max, a.k);
   if (tid == 0) n_taken = 0;
   __syncthreads();
@@ -437,12 +439,13 @@ __device__ __forceinline__ bool ranks_before(float v, int i, float ov, int oi) {
 }
 
 template <typename U, typename T>
-__global__ __launch_bounds__(256) void bigram_gemv_kernel(const U *tok_emb, const T *unemb_t, const int32_t *hist, int n,
+__global__ __launch_bounds__(256) void bigram_gemv_kernel(const U *tok_emb, const T *unemb_t, const int32_t *hist, int n, const int32_t *n_dev,
                                                           int d, int vocab, int ksel, float *z, float *cand_val,
                                                           int *cand_idx, float emb_scale, float out_scale) {
   extern __shared__ __attribute__((aligned(16))) unsigned char gemv_smem[];
   T *es = reinterpret_cast<T *>(gemv_smem);                  // [d] embedding of x_last (times emb_scale, internal type)
   float *zs = reinterpret_cast<float *>(gemv_smem + (size_t)d * sizeof(T));   // this block's scores
+  if (n_dev) n = *n_dev;
   const int x = hist[n - 1];
   for (int i = threadIdx.x; i < d; i += 256) es[i] = from_f32<T>(to_f32(tok_emb[(size_t)x * d + i]) * emb_scale);
   __syncthreads();
@@ -676,7 +679,7 @@ __global__ __launch_bounds__(64) void table_assemble_kernel(const DraftArgs a) {
   } else {
     // first token: the (r - n_ctx)-th ranked successor of the last token in the bigram table, or the
     // (r - n_ctx)-th nearest token of the unigram (context-free); then each token's top-ranked successor
-    int t0 = a.uni_top ? a.uni_top[r - n_ctx] : a.bg_table[(size_t)a.hist[a.n - 1] * a.bg_K + (r - n_ctx)];
+    int t0 = a.uni_top ? a.uni_top[r - n_ctx] : a.bg_table[(size_t)a.hist[(a.n_dev ? *a.n_dev : a.n) - 1] * a.bg_K + (r - n_ctx)];
     for (int t = 0; t < a.w; ++t) {
       a.drafts[r * a.w + t] = t0;
       t0 = a.bg_table ? a.bg_table[(size_t)t0 * a.bg_K] : a.next1[t0];
@@ -701,11 +704,11 @@ void launch_build_drafts(int dtype, const DraftArgs &a, hipStream_t s) {
     const float out_scale = 1.0f / (a.emb_scale * a.unemb_scale);       // powers of two: exact
     if (dtype == 1)
       hipLaunchKernelGGL((bigram_gemv_kernel<bf16_t, half_t>), dim3(kGemvBlocks), dim3(256), lds, s, (const bf16_t *)a.tok_emb,
-                         (const half_t *)a.unemb_t, a.hist, a.n, a.d, a.vocab, a.k, a.z, a.cand_val, a.cand_idx,
+                         (const half_t *)a.unemb_t, a.hist, a.n, a.n_dev, a.d, a.vocab, a.k, a.z, a.cand_val, a.cand_idx,
                          a.emb_scale, out_scale);
     else
       hipLaunchKernelGGL((bigram_gemv_kernel<float, float>), dim3(kGemvBlocks), dim3(256), lds, s, (const float *)a.tok_emb,
-                         (const float *)a.unemb_t, a.hist, a.n, a.d, a.vocab, a.k, a.z, a.cand_val, a.cand_idx,
+                         (const float *)a.unemb_t, a.hist, a.n, a.n_dev, a.d, a.vocab, a.k, a.z, a.cand_val, a.cand_idx,
                          a.emb_scale, out_scale);
   }
   hipLaunchKernelGGL(ctx_match_kernel, dim3(1), dim3(1024), 0, s, a);
@@ -892,8 +895,9 @@ void launch_iota(int32_t *dst, int first, int n, hipStream_t s) {
 template <typename T>
 __global__ __launch_bounds__(256) void commit_kernel(T *kcache, T *vcache, const T *kscr, const T *vscr, int Hkv, int hd,
                                                      int Spad, int Mcap, int C, int shared0, int P, const int32_t *res, int fixed_row,
-                                                     int fixed_n, int max_new, int32_t *hist) {
+                                                     int fixed_n, int max_new, int32_t *hist, const int32_t *n_dev) {
   const int layer = blockIdx.y, hkv = blockIdx.x;
+  if (n_dev) P = *n_dev - 1;
   int row = fixed_row, n_new = fixed_n;
   if (res) { row = res[RES_WINNER]; n_new = min(res[RES_NNEW], max_new); }
   const size_t lh = (size_t)layer * Hkv + hkv;
@@ -913,15 +917,21 @@ __global__ __launch_bounds__(256) void commit_kernel(T *kcache, T *vcache, const
 
 void launch_commit(int dtype, void *kcache, void *vcache, const void *kscr, const void *vscr, int L, int Hkv, int hd,
                    int Spad, int Mcap, int C, int shared0, int P, const int32_t *res, int fixed_row, int fixed_n, int max_new,
-                   int32_t *hist, hipStream_t s) {
+                   int32_t *hist, hipStream_t s, const int32_t *n_dev) {
   if (dtype == 1)
     hipLaunchKernelGGL(commit_kernel<half_t>, dim3(Hkv, L), dim3(256), 0, s, (half_t *)kcache, (half_t *)vcache,
                        (const half_t *)kscr, (const half_t *)vscr, Hkv, hd, Spad, Mcap, C, shared0, P, res, fixed_row, fixed_n,
-                       max_new, hist);
+                       max_new, hist, n_dev);
   else
     hipLaunchKernelGGL(commit_kernel<float>, dim3(Hkv, L), dim3(256), 0, s, (float *)kcache, (float *)vcache,
                        (const float *)kscr, (const float *)vscr, Hkv, hd, Spad, Mcap, C, shared0, P, res, fixed_row, fixed_n,
-                       max_new, hist);
+                       max_new, hist, n_dev);
+}
+
+__global__ void advance_kernel(int32_t *n_dev, const int32_t *res, int max_new) { *n_dev += min(res[RES_NNEW], max_new); }
+
+void launch_advance(int32_t *n_dev, const int32_t *res, int max_new, hipStream_t s) {
+  hipLaunchKernelGGL(advance_kernel, dim3(1), dim3(1), 0, s, n_dev, res, max_new);
 }
 
 }  // namespace ngg

@@ -93,6 +93,49 @@ def test_decode_more_in_pieces_equals_greedy_decode_and_the_oracle(tiny):
     assert e.value.status == ngg.NGG_ECAPACITY
 
 
+def test_graph_replay_equals_stream_launches(tiny):
+    """ngg_decode_more can replay captured steps (mode 1: whenever a step qualifies; mode 2, the default: where it
+    measures faster).  The same generation with the replay switched off (every step launched on the stream) must
+    give the same tokens and the same statistics in both modes, for two block shapes and the single-token loop; the replaying run is cut into calls of three steps with launches on the stream in between
+    (a verify call that is not committed), crosses several changes of the attention slice count (a new capture
+    each) and ends on steps that the remaining budget clamps (launched on the stream)."""
+    desc, run, w, prompt, model, ctx = tiny
+    n_gen = 70
+    want = oracle.greedy_plain_cached(model, prompt, n_gen)
+    plain = dict(k=1, w=0, k_ctx_max=0, q_min=1, q_max=1)
+    keys = ("calls", "tokens", "new_hist", "accept_hist", "rank_hist", "winner_src", "ctx_rows", "alloc_hist")
+    try:
+        for cfg in (run, dict(run, k=8, w=5, k_ctx_max=4), None):
+            ctx.step_graphs(0)
+            ctx.prefill(prompt)
+            ref, st_ref = ctx.decode_more(n_gen - 1, 10 ** 6, cfg)
+            ctx.step_graphs(2)
+            ctx.prefill(prompt)
+            auto, st_auto = ctx.decode_more(n_gen - 1, 10 ** 6, cfg)
+            assert list(auto) == list(ref)
+            ctx.step_graphs(1)
+            ctx.prefill(prompt)
+            before = ctx.debug_peek("step_graphs", np.int32)[0]
+            whole, st_whole = ctx.decode_more(n_gen - 1, 10 ** 6, cfg)
+            after = ctx.debug_peek("step_graphs", np.int32)[0]
+            assert after[0] == 1 and after[1] == 0 and after[3] - before[3] >= st_whole["calls"] // 2, (before, after)
+            assert list(whole) == list(ref) == want[1:]
+            for key in keys:
+                assert np.array_equal(np.asarray(st_whole[key]), np.asarray(st_ref[key])), key
+                assert np.array_equal(np.asarray(st_auto[key]), np.asarray(st_ref[key])), key
+            ctx.prefill(prompt)
+            out = []
+            c = cfg or plain
+            while len(out) < n_gen - 1:
+                toks, _ = ctx.decode_more(n_gen - 1 - len(out), 3, cfg)
+                out += list(toks)
+                ctx.build_drafts(c)                                   # stream launches between the replays
+                ctx.verify_step(None, c["k"], c["w"])
+            assert out == want[1:]
+    finally:
+        ctx.step_graphs(2)
+
+
 def test_injected_drafts_every_accept_length(tiny):
     desc, run, w, prompt, model, ctx = tiny
     V = desc["vocab"]
