@@ -995,6 +995,7 @@ ngg_status ngg_bigram_table_build(ngg_ctx *c, int32_t top_k) {
   const ngg_model_desc &d = c->d;
   if (top_k < 1 || top_k > 64 || top_k > d.vocab) return fail(c, NGG_EINVAL, "ngg_bigram_table_build: need 1 <= top_k <= min(64, vocab)");
   if (top_k < d.max_k) return fail(c, NGG_EINVAL, "ngg_bigram_table_build: top_k=%d is below max_k=%d (a step may ask for max_k bigram rows)", top_k, d.max_k);
+  c->graph_key[7] = 0;                                  // a captured step may hold the old table's address
   if (c->bg_table) { (void)hipFree(c->bg_table); c->bg_table = nullptr; c->bg_use = false; }
   ngg_status st = dev_alloc(c, &c->bg_table, (size_t)d.vocab * top_k * 4, true);
   if (st != NGG_OK) return st;
@@ -1022,6 +1023,7 @@ ngg_status ngg_unigram_build(ngg_ctx *c, int32_t top_k) {
   const ngg_model_desc &d = c->d;
   if (top_k < 1 || top_k > 64 || top_k > d.vocab) return fail(c, NGG_EINVAL, "ngg_unigram_build: need 1 <= top_k <= min(64, vocab)");
   if (top_k < d.max_k) return fail(c, NGG_EINVAL, "ngg_unigram_build: top_k=%d is below max_k=%d (a step may ask for max_k rows)", top_k, d.max_k);
+  c->graph_key[7] = 0;                                  // a captured step may hold the old list's address
   if (c->uni_top) { (void)hipFree(c->uni_top); c->uni_top = nullptr; c->uni_use = false; }
   ngg_status st = dev_alloc(c, &c->uni_top, (size_t)top_k * 4, true);
   if (st != NGG_OK) return st;
