@@ -120,8 +120,10 @@ def measure(ngg, si, torch, workload, steps, warmup, dev_w, args, full=True):
         ctx.verify_step(None, k, w, fetch=False)
         ctx.commit()
 
-    for _ in range(warmup):
-        step()
+    if warmup:
+        # through the library's own loop, as the timed steps: what it does once per step shape (timing a captured
+        # replay of the step against plain launches) falls into the warm-up
+        ctx.decode_more(warmup * (w + 1) + w + 1, warmup, run)
     n_start = len(ctx.get_tokens())
     events = full and not args.no_kernel_events
     if events:
@@ -291,7 +293,7 @@ def main():
         for wl in ("cfg4", "cfg5", "cfg2", "cfg1"):
             model_name = si.RUNS[wl]["model"]
             wts = dev_w if model_name == run["model"] else si.make_weights_device(si.MODELS[model_name], seed=0)
-            s = measure(ngg, si, torch, wl, 10, 3, wts, args, full=False)
+            s = measure(ngg, si, torch, wl, 10, 6, wts, args, full=False)
             del wts
             secondary.append({"workload": workload_name(wl, s), "verify_step_latency_us": s["ms_per_step"] * 1e3,
                               "decode_step_latency_us": s["decode_ms"] * 1e3,

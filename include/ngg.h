@@ -214,8 +214,10 @@ ngg_status ngg_allocation(ngg_ctx *ctx, int32_t mode, int32_t coverage_percent, 
  * step after step and is captured again only when k, w, the draft settings or the number of attention slices change.
  * Steps that the generation budget clamps (the last ones), steps with profiling brackets enabled and the first step
  * of every shape are always launched on the stream.  mode 0: never replay.  mode 1: replay every step that qualifies.
- * mode 2 (default): per step shape, time three steps launched on the stream and three replayed, keep the faster way
- * (replay pays where a step is bound by its launches: small models; at the 7B shapes it measures no gain).  In every
+ * mode 2 (default): per step shape, time three steps launched on the stream and, unless those took more than 6 us
+ * per kernel launch (a step bound by the device: replay cannot win and the capture is not paid), three replayed; keep the
+ * faster way (replay pays where a step is bound by its launches: small models; at the 7B shapes it measured no
+ * gain).  In every
  * mode the same kernels run in the same shapes: the committed tokens and the statistics are identical.
  * ngg_build_drafts, ngg_verify_step and ngg_commit called directly always launch on the stream. */
 ngg_status ngg_step_graphs(ngg_ctx *ctx, int32_t mode);

@@ -698,6 +698,8 @@ static int context_row_cap(const ngg_ctx *c, int configured) {
   return std::min(configured, std::max(1, cap));
 }
 
+constexpr double kGraphLaunchMs = 0.006;   // per kernel launch; steps slower than this are never captured in mode 2
+
 // What fixes the launch shapes and constant arguments of a decode step: a captured step is replayed only while
 // these stay the same (the number of attention slices moves with the context length)
 static void step_key(const ngg_ctx *c, const ngg_draft_cfg &s, int key[8]) {
@@ -832,7 +834,12 @@ static ngg_status decode_loop(ngg_ctx *c, int n0, int n_gen, int64_t max_calls, 
       if (which == 1 && !replayed) c->tune_choice = 0;       // no graph to be had
       else {
         c->tune_ms[which] = std::min(c->tune_ms[which], now_ms() - t0);
-        if (++c->tune_count == 6) c->tune_choice = c->tune_ms[1] < 0.98 * c->tune_ms[0] ? 1 : 0;
+        ++c->tune_count;
+        // A step that takes more than kGraphLaunchMs per kernel it launches (ten per layer, a dozen around them) is
+        // bound by the device, not by its launches (the host queues one in about 2.5 us): replay cannot win, so
+        // the capture (milliseconds for a 32-layer step) is not paid either.
+        if (c->tune_count == 3 && c->tune_ms[0] > kGraphLaunchMs * (10 * c->d.n_layers + 12)) c->tune_choice = 0;
+        else if (c->tune_count == 6) c->tune_choice = c->tune_ms[1] < 0.98 * c->tune_ms[0] ? 1 : 0;
       }
     }
     st.calls += 1;
