@@ -18,6 +18,7 @@
 // and per-position argmax partials for the greedy choice (output embedding).
 #include "ngg_internal.h"
 #include <algorithm>
+#include <type_traits>
 
 namespace ngg {
 
@@ -29,11 +30,10 @@ namespace ngg {
 // q/k/v and gate/up: the fragment's rows 0..7 are the first members of 8 output pairs, rows 8..15 the
 // second members (rotary pairs (i, i + hd/2) of one head; gate and up of 8 FFN features).  rs: the row's
 // 1 / rms times the operand scales.  The caller has checked frag < n_groups; lanes g >= 2 only lend values.
+// v: the first members (fragment rows 4g .. 4g+3, g < 2), x2: their partners (rows 8 + 4g ..), both already scaled
 template <typename T, int EPI>
-__device__ __forceinline__ void epi_paired(const GemmArgs &a, int frag, int m, int M, int g, float rs, const f32x4 &sum) {
-  float v[4], x2[4];
-#pragma unroll
-  for (int r = 0; r < 4; ++r) { v[r] = sum[r] * rs; x2[r] = other_half(v[r]); }
+__device__ __forceinline__ void epi_paired_vals(const GemmArgs &a, int frag, int m, int M, int g, const float (&v)[4],
+                                                const float (&x2)[4]) {
   if (m < M && g < 2) {
     if constexpr (EPI == EPI_GATEUP) {
       float o[4];
@@ -75,6 +75,14 @@ __device__ __forceinline__ void epi_paired(const GemmArgs &a, int frag, int m, i
       }
     }
   }
+}
+
+template <typename T, int EPI>
+__device__ __forceinline__ void epi_paired(const GemmArgs &a, int frag, int m, int M, int g, float rs, const f32x4 &sum) {
+  float v[4], x2[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) { v[r] = sum[r] * rs; x2[r] = other_half(v[r]); }
+  epi_paired_vals<T, EPI>(a, frag, m, M, g, v, x2);
 }
 
 // residual: split ks stores its fp32 partial of output features n0 + 4g .. +4 of block row m
@@ -567,6 +575,267 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(const GemmArgs a, int MT
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// The wide kernel on the 32x32x16 MFMA, for tiles whose row blocks come in pairs (FM a multiple of 4, an even
+// number of fragments).  Same workgroup, staging and ring as above; what changes is the tile one instruction
+// covers: 32 rows of W (two neighbouring fragments) times 32 block rows over 16 contraction elements.  An
+// operand register then meets twice as many multiply-adds, so the kernel reads half the LDS bytes and issues half
+// the W loads per flop, and the instruction itself runs closer to the matrix cores' rate on this part (a loop of
+// nothing but MFMAs on all CUs: 2.1-2.2 PFLOP/s with 32x32x16 against 1.45-1.55 with 16x16x32).
+// Operand lanes: lane = 32 h + r takes row r of the 32 and contraction elements 8 h .. 8 h + 7 of the 16.  The
+// weights stay in their 16 x 32 blocks: for the q-th half of a step, lane (r, h) reads the 16 bytes that lane
+// (16 (2 q + h) + r % 16) of fragment r / 16 owns in the block (each load still covers whole 128-byte lines: 512
+// contiguous bytes in each of the two blocks).  Accumulator register 4 j + i of lane (r, h) is row 8 j + 4 h + i of the 32 W rows at block row
+// r: fragment j / 2, and inside it what the 16x16 layout keeps in lane group 2 (j % 2) + h, so the
+// epilogues above are called with that group.  Both halves of an output pair now sit in one lane (j and j + 1).
+// ---------------------------------------------------------------------------------------------
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+template <typename T, int EPI, int FM, int FN, bool TILED>
+__global__ __launch_bounds__(256) void gemm_wide32_kernel(const GemmArgs a, int MT) {
+  static_assert(sizeof(T) == 2, "16-bit operands only");
+  constexpr bool PAIRED = EPI == EPI_QKV || EPI == EPI_GATEUP;
+  static_assert(FN % 2 == 0 && FM % 4 == 0, "pairs of fragments, pairs of row blocks per wave");
+  static_assert(EPI != EPI_UNEMBED, "the unembedding stays on gemm_wide_kernel");
+  constexpr int FNP = FN / 2;                // pairs of fragments (32 rows of W) per wave
+  constexpr int FMB = FM / 4;                // 32-row blocks of the tile per wave (the waves are laid out 2 x 2)
+  constexpr int KC = KChunk<T>::value;       // chunk of the activation layout (256)
+  constexpr int KW = 64;                     // contraction elements staged per slice: two steps
+  constexpr int SPS = KW / 32;               // steps per slice
+  constexpr int LDX = KW + 8;                // LDS row stride in elements (16 bytes of padding)
+  constexpr int ROWS = 16 * FM;
+  constexpr int PPR = KW / 8;                // 16-byte pieces per row
+  constexpr int PIECES = (ROWS * PPR + 255) / 256;
+  constexpr int RING = 4;                    // W steps in flight per wave (two slices)
+
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  T *xs = reinterpret_cast<T *>(smem);       // [2][ROWS][LDX]
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int r32 = lane & 31, h = lane >> 5;
+  const int wn = wave & 1, wm = wave >> 1;   // this wave: fragments wn * FN .. of the workgroup's 2 FN, 32-row blocks wm * FMB ..
+  const int K = a.K, M = a.M;
+  const int n_frags = a.n_groups;            // 16-row fragments of W, an even number (the launcher checks)
+  const int n_steps = K / 32;
+  const int n_slices = (n_steps + SPS - 1) / SPS;
+  const int KS = gridDim.y, ks = blockIdx.y;
+  // workgroup -> (rows of W, row tile) as in gemm_wide_kernel
+  const int nb = TILED ? (blockIdx.x / 8 / MT) * 8 + blockIdx.x % 8 : blockIdx.x;
+  const int m0 = TILED ? (blockIdx.x / 8 % MT) * (16 * FM) : 0;
+  if (TILED && nb * 2 * FN >= n_frags) return;               // padding of the last row of 8
+  const int c0 = (int)(((long)n_slices * ks) / KS), c1 = (int)(((long)n_slices * (ks + 1)) / KS);
+
+  const T *wptr[FNP];                        // this lane's 16 bytes of the pair's first step, first half
+  int frag0[FNP];                            // first fragment of the pair
+  bool pair_live[FNP];
+#pragma unroll
+  for (int p = 0; p < FNP; ++p) {
+    int f0 = (nb * 2 + wn) * FN + 2 * p;
+    pair_live[p] = f0 < n_frags;
+    if (!pair_live[p]) f0 = n_frags - 2;     // repeats a pair it does not store
+    frag0[p] = f0;
+    wptr[p] = tiled_block((const T *)a.W0, f0 + (r32 >> 4), n_steps, 16 * h + (r32 & 15));
+  }
+
+  static_assert(kNormSegs == 4, "one float4 per row");
+  auto row_scale = [&](int m) {
+    float r = 1.0f;
+    if (a.row_ss) {
+      const f32x4 ss = *reinterpret_cast<const f32x4 *>(a.row_ss + (size_t)(m < a.Mcap ? m : a.Mcap - 1) * kNormSegs);
+      r = 1.0f / sqrtf((((ss[0] + ss[1]) + ss[2]) + ss[3]) / (float)K + a.ss_eps);
+    }
+    return r * a.out_scale;
+  };
+
+  // X staging as in gemm_wide_kernel
+  const T *xsrc[PIECES];
+  int xdst[PIECES];
+#pragma unroll
+  for (int i = 0; i < PIECES; ++i) {
+    const int p = tid + 256 * i;
+    const int row = min(p / PPR, ROWS - 1), col = p % PPR;
+    xsrc[i] = (const T *)a.X + (size_t)min(m0 + row, M - 1) * KC + col * 8;
+    xdst[i] = row * LDX + col * 8;
+  }
+  u32x4 stage[2][PIECES];
+  auto stage_load = [&](u32x4 (&st)[PIECES], int c) {       // slice c of the matrix (clamped into it)
+    const int cl = min(c, n_slices - 1);
+    const int k0 = cl * KW;
+    const size_t off = (size_t)(k0 / KC) * a.Mcap * KC + k0 % KC;
+#pragma unroll
+    for (int i = 0; i < PIECES; ++i) st[i] = *reinterpret_cast<const u32x4 *>(xsrc[i] + off);
+  };
+  auto stage_store = [&](const u32x4 (&st)[PIECES], int buf) {
+#pragma unroll
+    for (int i = 0; i < PIECES; ++i) *reinterpret_cast<u32x4 *>(xs + (size_t)buf * ROWS * LDX + xdst[i]) = st[i];
+  };
+
+  f32x16 acc[FNP][FMB];
+#pragma unroll
+  for (int p = 0; p < FNP; ++p)
+#pragma unroll
+    for (int b = 0; b < FMB; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[p][b][r] = 0.f;
+#pragma unroll
+  for (int c = 0; c < 2; ++c)
+#pragma unroll
+    for (int i = 0; i < PIECES; ++i) stage[c][i] = u32x4{0u, 0u, 0u, 0u};
+
+  Frag<T> ring[RING][FN];                                   // [2 p + q]: pair p, half q of the step
+  auto load_w = [&](Frag<T> (&slot)[FN], int t) {           // wave-step t >= 0 is global step c0 * SPS + t (clamped)
+    const int st = min(c0 * SPS + t, n_steps - 1);
+#pragma unroll
+    for (int p = 0; p < FNP; ++p)
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const T *src = wptr[p] + (size_t)st * 512 + q * 256;
+        slot[2 * p + q] = TILED ? load_frag(src) : load_frag_stream(src);
+      }
+  };
+
+  // One slice = two steps = two blocks of MFMAs, and between them the slice's only barrier.  The memory
+  // instructions ride in the shadow of the MFMAs (one wave per SIMD: whatever is issued while no MFMA is in
+  // flight leaves the matrix core idle; with the phases one after the other it was busy 38 % of the time):
+  //   first block (step 0 of slice s):  LDS reads of step 1, global loads of slice s + 2, LDS writes of slice s + 1
+  //                                     into the other buffer (its last readers passed the previous barrier)
+  //   barrier; LDS reads of step 0 of slice s + 1 (they land under the second block)
+  //   second block (step 1 of slice s): the W loads that refill the ring
+  // The groups below ask the scheduler for that order.
+  constexpr int NM = 2 * FMB * FNP;                         // MFMAs per step
+  constexpr int MEM_A = 2 * FMB + 2 * PIECES;               // memory instructions of the first block
+  constexpr int PER_A = (MEM_A + NM - 1) / NM;
+  const int rowoff = (wm * FMB * 32 + r32) * LDX + h * 8;
+  Frag<T> xf[SPS][2 * FMB];                                 // [2 b + q]: 32-row block b, half q of the step
+#pragma unroll
+  for (int i = 0; i < SPS; ++i)
+#pragma unroll
+    for (int e = 0; e < 2 * FMB; ++e) xf[i][e].v = half8{0, 0, 0, 0, 0, 0, 0, 0};
+  auto half_trip = [&](auto cc_tag, auto live_tag, int sl, int t0) {
+    constexpr int cc = decltype(cc_tag)::value;
+    constexpr bool live = decltype(live_tag)::value;
+    const T *xcur = xs + (size_t)cc * ROWS * LDX + rowoff, *xnxt = xs + (size_t)(cc ^ 1) * ROWS * LDX + rowoff;
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int b = 0; b < FMB; ++b)
+#pragma unroll
+      for (int q = 0; q < 2; ++q) xf[1][2 * b + q] = load_frag(xcur + b * 32 * LDX + 32 + q * 16);
+    stage_load(stage[cc], max(sl + 2, c0));
+    stage_store(stage[cc ^ 1], cc ^ 1);
+    if constexpr (live) {
+#pragma unroll
+      for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int b = 0; b < FMB; ++b)
+#pragma unroll
+          for (int p = 0; p < FNP; ++p)
+            acc[p][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ring[2 * cc][2 * p + q].v, xf[0][2 * b + q].v, acc[p][b], 0, 0, 0);
+#pragma unroll
+      for (int k = 0; k < NM; ++k) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x320, PER_A, 0);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+#pragma unroll
+    for (int b = 0; b < FMB; ++b)
+#pragma unroll
+      for (int q = 0; q < 2; ++q) xf[0][2 * b + q] = load_frag(xnxt + b * 32 * LDX + q * 16);
+    __builtin_amdgcn_sched_barrier(0);
+    load_w(ring[2 * cc], max(t0 + RING, 0));
+    if constexpr (live) {
+#pragma unroll
+      for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int b = 0; b < FMB; ++b)
+#pragma unroll
+          for (int p = 0; p < FNP; ++p)
+            acc[p][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ring[2 * cc + 1][2 * p + q].v, xf[1][2 * b + q].v, acc[p][b], 0, 0, 0);
+#pragma unroll
+      for (int k = 0; k < NM; ++k) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (k < FN) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    load_w(ring[2 * cc + 1], max(t0 + 1 + RING, 0));
+  };
+
+  // two slices without MFMAs fill the pipeline (the same memory instructions in the same order as the loop's, so
+  // the loop is entered with the loads outstanding that every later trip finds); the loop itself has no branch
+  using Cc0 = std::integral_constant<int, 0>;
+  using Cc1 = std::integral_constant<int, 1>;
+  half_trip(Cc0{}, std::false_type{}, c0 - 2, -2 * SPS);
+  half_trip(Cc1{}, std::false_type{}, c0 - 1, -1 * SPS);
+  int sl = c0;
+  for (; sl + 1 < c1; sl += 2) {
+    half_trip(Cc0{}, std::true_type{}, sl, (sl - c0) * SPS);
+    half_trip(Cc1{}, std::true_type{}, sl + 1, (sl + 1 - c0) * SPS);
+  }
+  if (sl < c1) half_trip(Cc0{}, std::true_type{}, sl, (sl - c0) * SPS);   // an odd number of slices
+  __syncthreads();                                           // everyone is done with xs
+  float *rs_lds = reinterpret_cast<float *>(smem);           // [ROWS] 1 / rms (times the operand scales) of the tile's rows
+  for (int r = tid; r < ROWS; r += 256) rs_lds[r] = row_scale(m0 + r);
+  __syncthreads();
+
+  const int row0 = wm * FMB * 32 + r32;                      // this lane's row of the tile in 32-row block 0
+  if constexpr (EPI == EPI_QKV) {
+    // the accumulators leave the registers through LDS (every wave its own region, behind the row scales) and the
+    // rotary epilogue takes them back one fragment at a time, as in gemm_wide_kernel
+    f32x4 *dump = reinterpret_cast<f32x4 *>(smem + (ROWS * sizeof(float) + 15) / 16 * 16) + (size_t)wave * (FN * FMB * 2 * 64);
+#pragma unroll
+    for (int p = 0; p < FNP; ++p)
+#pragma unroll
+      for (int b = 0; b < FMB; ++b)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          dump[((p * FMB + b) * 4 + j) * 64 + lane] = f32x4{acc[p][b][4 * j], acc[p][b][4 * j + 1], acc[p][b][4 * j + 2], acc[p][b][4 * j + 3]};
+#pragma unroll 2
+    for (int idx = 0; idx < FNP * FMB * 2; ++idx) {          // item: (pair, 32-row block, fragment of the pair)
+      const int pb = idx >> 1, t = idx & 1;
+      const int p = pb / FMB, b = pb - p * FMB;
+      const int frag = (nb * 2 + wn) * FN + 2 * p + t;
+      const int row = row0 + b * 32;
+      if (frag < n_frags) {                                  // uniform per wave
+        const float rs = rs_lds[row];
+        const f32x4 lo = dump[(pb * 4 + 2 * t) * 64 + lane], hi = dump[(pb * 4 + 2 * t + 1) * 64 + lane];
+        const float v[4] = {lo[0] * rs, lo[1] * rs, lo[2] * rs, lo[3] * rs};
+        const float x2[4] = {hi[0] * rs, hi[1] * rs, hi[2] * rs, hi[3] * rs};
+        epi_paired_vals<T, EPI>(a, frag, m0 + row, M, h, v, x2);
+      }
+    }
+  } else {
+#pragma unroll
+    for (int b = 0; b < FMB; ++b) {
+      const int row = row0 + b * 32;                         // row of the tile
+      const int m = m0 + row;
+      const bool live = m < M;
+      const float rs = PAIRED ? rs_lds[row] : 1.0f;
+#pragma unroll
+      for (int p = 0; p < FNP; ++p) {
+        if (!pair_live[p]) continue;                         // uniform per wave
+        if constexpr (EPI == EPI_GATEUP) {
+#pragma unroll
+          for (int t = 0; t < 2; ++t) {
+            float v[4], x2[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) { v[r] = acc[p][b][8 * t + r] * rs; x2[r] = acc[p][b][8 * t + 4 + r] * rs; }
+            epi_paired_vals<T, EPI>(a, frag0[p] + t, m, M, h, v, x2);
+          }
+        } else {
+          if (live) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+              epi_residual(a, ks, m, (frag0[p] + (j >> 1)) * 16, 2 * (j & 1) + h,
+                           f32x4{acc[p][b][4 * j], acc[p][b][4 * j + 1], acc[p][b][4 * j + 2], acc[p][b][4 * j + 3]});
+          }
+        }
+      }
+    }
+  }
+}
+
 // FN: fragments per wave; a workgroup owns 2 FN.  MT: row tiles of 16 FM rows (1: the tile holds the whole block).
 template <typename T, int EPI, int FM, int FN>
 static void launch_wide_cfg(const GemmArgs &a, int KS, int MT, hipStream_t s) {
@@ -584,6 +853,22 @@ static void launch_wide_cfg(const GemmArgs &a, int KS, int MT, hipStream_t s) {
   else hipLaunchKernelGGL((gemm_wide_kernel<T, EPI, FM, FN, true>), dim3((blocks + 7) / 8 * 8 * MT, KS), dim3(256), lds, s, a, MT);
 }
 
+template <typename T, int EPI, int FM, int FN>
+static void launch_wide32_cfg(const GemmArgs &a, int KS, int MT, hipStream_t s) {
+  size_t lds = (size_t)2 * 16 * FM * (64 + 8) * sizeof(T);
+  if (EPI == EPI_QKV) lds = std::max(lds, (size_t)(16 * FM * 4 + 15) / 16 * 16 + (size_t)4 * FN * (FM / 2) * 1024);   // accumulator hand-back
+  const int blocks = (a.n_groups + 2 * FN - 1) / (2 * FN);
+  if (lds > 64 * 1024) {
+    static const hipError_t opted = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_wide32_kernel<T, EPI, FM, FN, false>),
+                                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    static const hipError_t opted_t = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_wide32_kernel<T, EPI, FM, FN, true>),
+                                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    (void)opted; (void)opted_t;
+  }
+  if (MT == 1) hipLaunchKernelGGL((gemm_wide32_kernel<T, EPI, FM, FN, false>), dim3(blocks, KS), dim3(256), lds, s, a, 1);
+  else hipLaunchKernelGGL((gemm_wide32_kernel<T, EPI, FM, FN, true>), dim3((blocks + 7) / 8 * 8 * MT, KS), dim3(256), lds, s, a, MT);
+}
+
 template <typename T, int EPI, int FM>
 static void launch_wide_fm(const GemmArgs &a_in, int KS, int MT, hipStream_t s) {
   GemmArgs a = a_in;
@@ -593,10 +878,23 @@ static void launch_wide_fm(const GemmArgs &a_in, int KS, int MT, hipStream_t s) 
   // otherwise (q/k/v of a 4096-wide model has 768 fragments: 96 workgroups against 192): every workgroup reads
   // all of X whatever it owns, so the W rows per workgroup only matter once the chip is full.  q/k/v always
   // takes 64: the unrolled rotary epilogue over more accumulator fragments does not fit the registers.
-  if constexpr (EPI == EPI_QKV || EPI == EPI_GATEUP) {
-    if ((a.n_groups + 7) / 8 * KS * MT < 160) { launch_wide_cfg<T, EPI, FM, 2>(a, KS, MT, s); return; }
+  bool narrow = false;
+  if constexpr (EPI == EPI_QKV || EPI == EPI_GATEUP) narrow = (a.n_groups + 7) / 8 * KS * MT < 160;
+  // The 32x32x16 kernel where the tile's row blocks pair up (192 and 256 rows: every prefill piece of 2048 tokens)
+  // and it measured faster on MI355X: q/k/v and gate/up always (7B shapes, 161-192 and 225-256 block rows: q/k/v
+  // 52 -> 48 and 64 -> 57 us, gate/up 70.5 -> 69 and 82 -> 79 us; prefill pieces: 271 -> 230 and 519 -> 464 us), the
+  // residual GEMMs only with several row tiles (prefill: 77 -> 72 and 242 -> 232 us; a single tile streams W from
+  // HBM and was 5 % slower: 18.2 -> 19.2 and 41 -> 42 us).
+  if constexpr (FM % 4 == 0 && EPI != EPI_UNEMBED) {
+    constexpr bool paired = EPI == EPI_QKV || EPI == EPI_GATEUP;
+    if (a.n_groups % 2 == 0 && a.K % 64 == 0 && (paired || MT > 1)) {
+      if (narrow) launch_wide32_cfg<T, EPI, FM, 2>(a, KS, MT, s);
+      else launch_wide32_cfg<T, EPI, FM, 4>(a, KS, MT, s);
+      return;
+    }
   }
-  launch_wide_cfg<T, EPI, FM, 4>(a, KS, MT, s);
+  if (narrow) launch_wide_cfg<T, EPI, FM, 2>(a, KS, MT, s);
+  else launch_wide_cfg<T, EPI, FM, 4>(a, KS, MT, s);
 }
 
 // Row tiles of the wide kernel: as few as possible (288 rows at most each), then the smallest even
