@@ -585,9 +585,10 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(const GemmArgs a, int MT
 // Operand lanes: lane = 32 h + r takes row r of the 32 and contraction elements 8 h .. 8 h + 7 of the 16.  The
 // weights stay in their 16 x 32 blocks: for the q-th half of a step, lane (r, h) reads the 16 bytes that lane
 // (16 (2 q + h) + r % 16) of fragment r / 16 owns in the block (each load still covers whole 128-byte lines: 512
-// contiguous bytes in each of the two blocks).  Accumulator register 4 j + i of lane (r, h) is row 8 j + 4 h + i of the 32 W rows at block row
-// r: fragment j / 2, and inside it what the 16x16 layout keeps in lane group 2 (j % 2) + h, so the
-// epilogues above are called with that group.  Both halves of an output pair now sit in one lane (j and j + 1).
+// contiguous bytes in each of the two blocks).  Accumulator register 4 j + i of lane (r, h) is row
+// 8 j + 4 h + i of the 32 W rows at block row r: fragment j / 2, and inside it what the 16x16 layout keeps
+// in lane group 2 (j % 2) + h, so the epilogues above are called with that group.  Both halves of an output
+// pair now sit in one lane (registers of j and j + 1).  The unembedding stays on gemm_wide_kernel.
 // ---------------------------------------------------------------------------------------------
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
