@@ -719,6 +719,25 @@ def test_prefill_piece_boundaries_16_bit():
     ctx.close()
 
 
+def test_row_tiles_of_256_with_an_odd_number_of_contraction_slices_16_bit():
+    """The 32x32x16 GEMM kernel takes tiles of 192 and 256 rows; its main loop handles two 64-element slices of the
+    contraction per trip and one more after it when their number is odd.  Widths of 192 (3 slices) and 448 (7 slices),
+    2 layers: a 512-token prompt is prefilled as two 256-row tiles (all four GEMMs on that kernel), then verify blocks
+    of 241 and 177 rows (one tile of 256 and of 192 rows: q/k/v and gate/up on it) and a step of the default shape."""
+    desc = dict(si.reduced_layers(si.MODELS["small"], 2), n_heads=3, n_kv_heads=3, head_dim=64, d_model=192, d_ffn=448,
+                vocab=4096)
+    run = dict(si.RUNS["cfg2"], prompt_len=512, n_gen=64)
+    w_, prompt, model, ctx = _setup(desc, run, max_k=16, max_w=15)
+    rep = lockstep_run(ctx, model, prompt, 8, run, TOL["bf16"], max_steps=1)
+    assert rep.max_rel_logit_err <= 2e-2, rep
+    for k, wd in ((16, 15), (16, 11)):
+        cfg = dict(run, k=k, w=wd, k_ctx_max=4)
+        rep = lockstep_run(ctx, model, prompt, 2 * (wd + 1), cfg, TOL["bf16"], max_steps=1)
+        print("odd slices:", k, wd, rep)
+        assert rep.max_rel_logit_err <= 2e-2, (k, wd, rep)
+    ctx.close()
+
+
 def test_7b_width_two_layer_twin_bf16_lockstep():
     """7B widths (d 4096, 32 heads of 128, FFN 14336, vocab 32000) with 2 layers so
     the oracle can run it: prompt 2048, k=10, w=5 -- the launch shapes of config 3."""
